@@ -1,0 +1,142 @@
+"""CPU oracle for token-ID BLEU -- TEST INFRASTRUCTURE, not part of the product path.
+
+`bleu_oracle.cpp` is the plain per-sentence dictionary-count definition (fp64, std::map);
+`paper_pipeline.py` walks the paper's own tensor-op steps (Sections 3.1-3.4) with numpy.
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this package; it
+imports nothing from the HIP package and the HIP package imports nothing from here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bleu_oracle.cpp")
+_LIB = os.path.join(_HERE, "libbleu_oracle.so")
+
+SMOOTHING = {"none": 0, "floor": 1, "add-k": 2, "exp": 3}
+
+
+def build(force: bool = False) -> str:
+    """Compile the C++ oracle with the host compiler (no GPU code involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread",
+                               "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i32p, i64p, f64p = (ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
+                            ctypes.POINTER(ctypes.c_double))
+        lib.oracle_bleu.restype = ctypes.c_int
+        lib.oracle_bleu.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p,
+                                    ctypes.c_int, ctypes.c_int, ctypes.c_int, f64p, ctypes.c_int,
+                                    ctypes.c_double, ctypes.c_int, i32p, i32p, i32p, i32p, i32p,
+                                    f64p, i64p, f64p]
+        lib.oracle_bleu_from_stats.restype = ctypes.c_double
+        lib.oracle_bleu_from_stats.argtypes = [i64p, i64p, ctypes.c_int64, ctypes.c_int64,
+                                               ctypes.c_int, f64p, ctypes.c_int, ctypes.c_double]
+        lib.oracle_group_counts.restype = ctypes.c_int
+        lib.oracle_group_counts.argtypes = [i32p, ctypes.c_int, i32p, ctypes.c_int64, i32p,
+                                            ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p, i32p,
+                                            i32p]
+        _lib = lib
+    return _lib
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+@dataclass
+class OracleResult:
+    clipped: np.ndarray         # [B, N] int32
+    total: np.ndarray           # [B, N] int32
+    closest_ref_len: np.ndarray  # [B] int32
+    group_distinct: np.ndarray  # [B, N] int32  distinct n-grams over candidate + references
+    cand_distinct: np.ndarray   # [B, N] int32  distinct n-grams of the candidate alone
+    bleu: np.ndarray            # [B] float64
+    corpus_stats: np.ndarray    # [2N+2] int64
+    corpus_bleu: float
+
+
+def bleu(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.ndarray,
+         max_n: int = 4, weights: Optional[Sequence[float]] = None, smoothing: str = "none",
+         smooth_param: float = 0.0, threads: int = 1) -> OracleResult:
+    """Per-sentence and corpus BLEU of a padded batch (see bleu_oracle.cpp for the definition)."""
+    lib = _load()
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    refs = np.ascontiguousarray(refs, dtype=np.int32)
+    cand_len = np.ascontiguousarray(cand_len, dtype=np.int32)
+    ref_len = np.ascontiguousarray(ref_len, dtype=np.int32)
+    B = cand.shape[0]
+    assert refs.ndim == 3 and refs.shape[0] == B and ref_len.shape == refs.shape[:2]
+    R = refs.shape[1]
+    assert (cand_len <= cand.shape[1]).all() and (ref_len <= refs.shape[2]).all()
+    assert (cand_len >= 0).all() and (ref_len >= 0).all()
+    N = int(max_n)
+    w = np.full(N, 1.0 / N) if weights is None else np.asarray(weights, dtype=np.float64)[:N]
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    clipped = np.zeros((B, N), np.int32)
+    total = np.zeros((B, N), np.int32)
+    closest = np.zeros(B, np.int32)
+    gd = np.zeros((B, N), np.int32)
+    cd = np.zeros((B, N), np.int32)
+    out = np.zeros(B, np.float64)
+    cstats = np.zeros(2 * N + 2, np.int64)
+    cb = np.zeros(1, np.float64)
+    rc = lib.oracle_bleu(_p(cand, ctypes.c_int32), cand.shape[1], _p(cand_len, ctypes.c_int32),
+                         _p(refs, ctypes.c_int32), refs.shape[2], _p(ref_len, ctypes.c_int32),
+                         B, R, N, _p(w, ctypes.c_double), SMOOTHING[smoothing],
+                         float(smooth_param), int(threads), _p(clipped, ctypes.c_int32),
+                         _p(total, ctypes.c_int32), _p(closest, ctypes.c_int32),
+                         _p(gd, ctypes.c_int32), _p(cd, ctypes.c_int32),
+                         _p(out, ctypes.c_double), _p(cstats, ctypes.c_int64),
+                         _p(cb, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle_bleu: invalid arguments")
+    return OracleResult(clipped, total, closest, gd, cd, out, cstats, float(cb[0]))
+
+
+def bleu_from_stats(clipped, total, c: int, r: int, weights, smoothing: str = "none",
+                    smooth_param: float = 0.0) -> float:
+    lib = _load()
+    cl = np.ascontiguousarray(clipped, dtype=np.int64)
+    to = np.ascontiguousarray(total, dtype=np.int64)
+    w = np.ascontiguousarray(weights, dtype=np.float64)
+    return float(lib.oracle_bleu_from_stats(_p(cl, ctypes.c_int64), _p(to, ctypes.c_int64),
+                                            int(c), int(r), len(cl), _p(w, ctypes.c_double),
+                                            SMOOTHING[smoothing], float(smooth_param)))
+
+
+def group_counts(cand_row: np.ndarray, cand_len: int, ref_rows: np.ndarray, ref_len: np.ndarray,
+                 n: int):
+    """Distinct n-grams of one sentence group with candidate count and max reference count."""
+    lib = _load()
+    cand_row = np.ascontiguousarray(cand_row, dtype=np.int32)
+    ref_rows = np.ascontiguousarray(ref_rows, dtype=np.int32)
+    ref_len = np.ascontiguousarray(ref_len, dtype=np.int32)
+    R = ref_rows.shape[0]
+    cap = int(max(cand_len, 0) + int(np.maximum(ref_len, 0).sum()) + 1)
+    grams = np.zeros((cap, n), np.int32)
+    cc = np.zeros(cap, np.int32)
+    rm = np.zeros(cap, np.int32)
+    k = lib.oracle_group_counts(_p(cand_row, ctypes.c_int32), int(cand_len),
+                                _p(ref_rows, ctypes.c_int32), ref_rows.shape[1],
+                                _p(ref_len, ctypes.c_int32), R, n, cap,
+                                _p(grams, ctypes.c_int32), _p(cc, ctypes.c_int32),
+                                _p(rm, ctypes.c_int32))
+    return grams[:k], cc[:k], rm[:k]
