@@ -1,0 +1,181 @@
+/*
+ * tensorbleu.h -- C ABI of the MI355X (gfx950) batched token-ID BLEU library.
+ *
+ * The library computes, for a batch of B candidate token-ID sequences with R references each,
+ * one BLEU score per candidate (tensorbleu_sentence) or one score for the batch
+ * (tensorbleu_corpus): n-gram extraction for n = 1..N, a compact dictionary of the n-grams
+ * present, offset batched counting, clipping against the maximum reference count, modified
+ * precisions, brevity penalty, smoothing and the weighted geometric mean (paper Sections
+ * 3.1-3.4 and the BLEU equation of Section 2.1).
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the library never allocates,
+ *     frees or keeps a pointer after the call returns).  `cfg`, `stats` and `layout` structs are
+ *     HOST memory, read (or written, for layout) during the call only.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  No entry point synchronises; outputs are valid once the stream has been
+ *     synchronised by the caller.
+ *   - Layout: candidate i is the row `cand + i*cand_stride`, valid for `cand_len[i]` tokens;
+ *     reference j of candidate i is the row `refs + (i*R + j)*ref_stride`, valid for
+ *     `ref_len[i*R + j]` tokens.  Strides are in elements (int32) and bound the lengths; cells
+ *     at or beyond a row's length are never interpreted (token id 0 inside the length is an
+ *     ordinary token).  Lengths found outside [0, stride] on the device are clamped and
+ *     reported through TB_DEV_LENGTH_RANGE.
+ *   - Host-detectable problems are reported through the return value (tb_status_t) before any
+ *     work is enqueued.  Conditions only visible on the device are OR-ed into
+ *     `stats->device_status` (caller clears it; may be NULL); scores of affected rows are then
+ *     unspecified but every access stays in bounds.
+ *   - B == 0 returns TB_OK without enqueuing work.
+ */
+#ifndef TENSORBLEU_H
+#define TENSORBLEU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TB_OK = 0,
+  TB_ERR_INVALID_ARG = 1, /* NULL required pointer, B < 0, R < 1, max_n outside 1..4, bad stride */
+  TB_ERR_WORKSPACE = 2,   /* workspace NULL, misaligned (256 B) or smaller than workspace_bytes */
+  TB_ERR_UNSUPPORTED = 3, /* shape outside what the kernels handle (see tensorbleu_workspace_layout) */
+  TB_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed */
+} tb_status_t;
+
+/* Smoothing of the modified precisions p_n (paper Section 3.4 names 'floor', 'add-k', 'exp'
+ * after Chen & Cherry 2014).  With c_n the clipped count and d_n = max(total_n, 1):
+ *   NONE   p_n = c_n / d_n; any p_n == 0 with w_n > 0 gives score 0
+ *   FLOOR  c_n == 0  ->  p_n = smooth_param / d_n
+ *   ADD_K  n >= 2    ->  p_n = (c_n + smooth_param) / (d_n + smooth_param); n = 1 unsmoothed
+ *   EXP    the z-th order (scanning n = 1..N) with c_n == 0 gets p_n = 1 / (2^z * d_n)
+ * In every mode a candidate with no matching unigram, or of length 0, scores 0. */
+typedef enum { TB_SMOOTH_NONE = 0, TB_SMOOTH_FLOOR = 1, TB_SMOOTH_ADD_K = 2, TB_SMOOTH_EXP = 3 } tb_smooth_t;
+
+/* Execution paths.  FUSED: one kernel, one workgroup per sentence group, tokens staged once in
+ * LDS and dictionary + counts kept in LDS.  GLOBAL: pack -> dictionary -> count/clip -> finalize
+ * with packed keys and inverse indices materialised in the workspace. */
+typedef enum { TB_PATH_AUTO = 0, TB_PATH_FUSED = 1, TB_PATH_GLOBAL = 2 } tb_path_t;
+
+/* Bits of *stats->device_status. */
+enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0, vocab_size) */
+       TB_DEV_LENGTH_RANGE = 2  /* a length was outside [0, stride] and was clamped */ };
+
+typedef struct tb_config {
+  int32_t max_n;        /* N: highest n-gram order, 1..4 (Section 2.1: "typically n=1 to 4") */
+  float   weights[4];   /* w_1..w_N of the BLEU equation, used as given (not renormalised);
+                           w_n == 0 drops order n; all zero means uniform 1/N */
+  int32_t smoothing;    /* tb_smooth_t */
+  float   smooth_param; /* eps for FLOOR, k for ADD_K; ignored otherwise */
+  int32_t vocab_size;   /* token ids lie in [0, vocab_size); fixes the key width:
+                           bits = ceil(log2(vocab_size)), order-n keys take n*bits bits and are
+                           stored in 8 bytes, or 16 bytes when n*bits > 64 */
+  int32_t force_path;   /* tb_path_t; TB_PATH_AUTO picks FUSED when a group fits its LDS budget */
+} tb_config_t;
+
+/* Optional integer outputs (each pointer may be NULL).  These are what the parity tests compare
+ * bit-exactly with the CPU oracle. */
+typedef struct tb_stats {
+  int32_t* clipped;         /* [B, N] sum over distinct candidate n-grams of min(count in candidate,
+                               max over references of count in reference)   (Section 3.3 step 3) */
+  int32_t* total;           /* [B, N] number of candidate n-grams, max(len - n + 1, 0) (Section 3.4) */
+  int32_t* closest_ref_len; /* [B] reference length closest to the candidate's (shorter on ties) */
+  int32_t* group_distinct;  /* [B, N] size of the group's dictionary: distinct n-grams over the
+                               candidate and its references (GLOBAL path only; FUSED writes the
+                               candidate's distinct count, its dictionary holds candidates only) */
+  int64_t* corpus_stats;    /* [2N+2] clipped_1..N, total_1..N, sum of candidate lengths, sum of
+                               closest reference lengths (Section 3.4, corpus variant) */
+  int32_t* device_status;   /* [1] OR of TB_DEV_* bits; cleared by the caller */
+} tb_stats_t;
+
+/* Where the GLOBAL path keeps its intermediates inside the workspace (byte offsets).  Slot
+ * numbering of the per-order key / inverse-index arrays: sentence group g owns slots
+ * [g*group_cap, (g+1)*group_cap); the candidate's n-gram starting at token p is slot
+ * g*group_cap + p, reference j's is g*group_cap + cand_stride + j*ref_stride + p.  A slot is
+ * written only when its window lies inside the row's length. */
+typedef struct tb_layout {
+  int32_t path;            /* path AUTO resolves to for this shape (TB_PATH_FUSED / TB_PATH_GLOBAL) */
+  int32_t bits;            /* ceil(log2(vocab_size)), at least 1 */
+  int32_t key_bytes[4];    /* 8 or 16 per order */
+  int64_t group_cap;       /* cand_stride + R*ref_stride */
+  size_t  keys_off[4];     /* packed keys of order n: B*group_cap entries of key_bytes[n-1] */
+  size_t  inv_off[4];      /* uint32 offset ids (g*group_cap + dense id in the group's dictionary) */
+  size_t  clipped_off, total_off, closest_off, distinct_off; /* int32 [B,N],[B,N],[B],[B,N] */
+  size_t  corpus_off;      /* int64 [2N+2] */
+  size_t  bytes;           /* total workspace size for this path */
+  int32_t fused_ok;        /* 1 if the FUSED path supports this shape */
+  int32_t global_ok;       /* 1 if the GLOBAL path supports this shape */
+} tb_layout_t;
+
+/* Workspace size in bytes for a problem shape (pure host function of the shapes; 0 on invalid
+ * arguments).  The size covers whichever path cfg->force_path selects (AUTO: the resolved one).
+ * The workspace must be 256-byte aligned device memory; its contents need no initialisation and
+ * are undefined afterwards. */
+size_t tensorbleu_workspace_bytes(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
+                                  const tb_config_t* cfg);
+
+/* Same computation as tensorbleu_workspace_bytes, returning the full layout.  Host only. */
+int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
+                                const tb_config_t* cfg, tb_layout_t* layout);
+
+/* One BLEU score per candidate: out_bleu[B] float32 (device).  Implements Sections 3.1-3.4 with
+ * the brevity penalty BP = 1 if c > r else exp(1 - r/c) and BLEU = BP * exp(sum_n w_n log p_n). */
+int tensorbleu_sentence(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                        const int32_t* refs, int64_t ref_stride, const int32_t* ref_len,
+                        int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
+                        const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+
+/* One score for the whole batch: numerators, denominators, candidate lengths and closest
+ * reference lengths are summed over the batch before the precisions are formed (Section 3.4,
+ * second paragraph).  out_bleu[1] float32 (device). */
+int tensorbleu_corpus(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                      const int32_t* refs, int64_t ref_stride, const int32_t* ref_len,
+                      int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
+                      const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+/* ---- The GLOBAL path one pass at a time (same arguments and workspace as above; the workspace
+ * must have been sized with force_path = TB_PATH_GLOBAL).  tensorbleu_sentence on the GLOBAL
+ * path is exactly pack, dictionary, count_clip, finalize in this order.  Exposed so that each
+ * pass can be checked and timed on its own. */
+
+/* Section 3.1 + 3.2 step 1: every valid n-gram, n = 1..N, packed big-endian into a key
+ * (first token in the most significant bits) and written to its slot in keys_off[n-1]. */
+int tensorbleu_pack(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                    const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+                    int32_t R, const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/* Section 3.2 step 2: per sentence group and order, a dictionary of the distinct keys (LDS hash
+ * table, exact key comparison) giving every n-gram occurrence a dense id in [0, U_g); written
+ * with the group's offset (Section 3.3 step 1) to inv_off[n-1]; U_g goes to distinct_off. */
+int tensorbleu_dictionary(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,
+                          int64_t ref_stride, int32_t B, int32_t R, const tb_config_t* cfg,
+                          const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Section 3.3 steps 2-3: counts of the offset ids for the candidate and for each reference (LDS
+ * atomics), maximum over references, minimum with the candidate count, summed to clipped[B,N];
+ * total[B,N] from the lengths. */
+int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,
+                          int64_t ref_stride, int32_t B, int32_t R, const tb_config_t* cfg,
+                          const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Section 3.4: closest reference length, brevity penalty, smoothing, geometric mean from the
+ * integer statistics in the workspace.  corpus != 0 writes out_bleu[1], else out_bleu[B]. */
+int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t B, int32_t R,
+                        int64_t cand_stride, int64_t ref_stride, const tb_config_t* cfg,
+                        int32_t corpus, float* out_bleu, const tb_stats_t* stats, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/* Text for a tb_status_t value (static storage, host). */
+const char* tensorbleu_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TENSORBLEU_H */

@@ -1,0 +1,281 @@
+"""ctypes binding of libtensorbleu.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see include/tensorbleu.h).
+PyTorch supplies device memory and the current HIP stream; every step of the computation runs
+in the library's kernels.  There is no CPU fallback: if the library is missing or no GPU is
+present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtensorbleu.so")
+
+TB_OK = 0
+SMOOTHING = {"none": 0, "floor": 1, "add-k": 2, "exp": 3}
+PATHS = {"auto": 0, "fused": 1, "global": 2}
+TB_DEV_TOKEN_RANGE, TB_DEV_LENGTH_RANGE = 1, 2
+
+EXPORTS = [
+    "tensorbleu_workspace_bytes", "tensorbleu_workspace_layout", "tensorbleu_sentence",
+    "tensorbleu_corpus", "tensorbleu_pack", "tensorbleu_dictionary", "tensorbleu_count_clip",
+    "tensorbleu_finalize", "tensorbleu_status_string",
+]
+
+
+class tb_config_t(ctypes.Structure):
+    _fields_ = [("max_n", ctypes.c_int32), ("weights", ctypes.c_float * 4),
+                ("smoothing", ctypes.c_int32), ("smooth_param", ctypes.c_float),
+                ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32)]
+
+
+class tb_stats_t(ctypes.Structure):
+    _fields_ = [("clipped", ctypes.c_void_p), ("total", ctypes.c_void_p),
+                ("closest_ref_len", ctypes.c_void_p), ("group_distinct", ctypes.c_void_p),
+                ("corpus_stats", ctypes.c_void_p), ("device_status", ctypes.c_void_p)]
+
+
+class tb_layout_t(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("bits", ctypes.c_int32),
+                ("key_bytes", ctypes.c_int32 * 4), ("group_cap", ctypes.c_int64),
+                ("keys_off", ctypes.c_size_t * 4), ("inv_off", ctypes.c_size_t * 4),
+                ("clipped_off", ctypes.c_size_t), ("total_off", ctypes.c_size_t),
+                ("closest_off", ctypes.c_size_t), ("distinct_off", ctypes.c_size_t),
+                ("corpus_off", ctypes.c_size_t), ("bytes", ctypes.c_size_t),
+                ("fused_ok", ctypes.c_int32), ("global_ok", ctypes.c_int32)]
+
+
+class TensorBLEUError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise TensorBLEUError(
+            f"{LIB_PATH} is missing: run `python -m paper_2510_05485_amd.build` first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    cfgp, stp = ctypes.POINTER(tb_config_t), ctypes.POINTER(tb_stats_t)
+    lib.tensorbleu_workspace_bytes.restype = sz
+    lib.tensorbleu_workspace_bytes.argtypes = [i32, i32, i64, i64, cfgp]
+    lib.tensorbleu_workspace_layout.restype = ctypes.c_int
+    lib.tensorbleu_workspace_layout.argtypes = [i32, i32, i64, i64, cfgp,
+                                                ctypes.POINTER(tb_layout_t)]
+    full = [vp, i64, vp, vp, i64, vp, i32, i32, cfgp, vp, stp, vp, sz, vp]
+    lib.tensorbleu_sentence.restype = ctypes.c_int
+    lib.tensorbleu_sentence.argtypes = full
+    lib.tensorbleu_corpus.restype = ctypes.c_int
+    lib.tensorbleu_corpus.argtypes = full
+    lib.tensorbleu_pack.restype = ctypes.c_int
+    lib.tensorbleu_pack.argtypes = [vp, i64, vp, vp, i64, vp, i32, i32, cfgp, stp, vp, sz, vp]
+    stage = [vp, vp, i64, i64, i32, i32, cfgp, stp, vp, sz, vp]
+    lib.tensorbleu_dictionary.restype = ctypes.c_int
+    lib.tensorbleu_dictionary.argtypes = stage
+    lib.tensorbleu_count_clip.restype = ctypes.c_int
+    lib.tensorbleu_count_clip.argtypes = stage
+    lib.tensorbleu_finalize.restype = ctypes.c_int
+    lib.tensorbleu_finalize.argtypes = [vp, vp, i32, i32, i64, i64, cfgp, i32, vp, stp, vp, sz, vp]
+    lib.tensorbleu_status_string.restype = ctypes.c_char_p
+    lib.tensorbleu_status_string.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def tensorbleu_status_string(status: int) -> str:
+    return load_library().tensorbleu_status_string(int(status)).decode()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != TB_OK:
+        raise TensorBLEUError(f"{what}: {tensorbleu_status_string(rc)} (status {rc})")
+
+
+def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
+                smoothing: str = "none", smooth_param: float = 0.0, vocab_size: int = 1 << 16,
+                path: str = "auto") -> tb_config_t:
+    cfg = tb_config_t()
+    cfg.max_n = int(max_n)
+    w = [0.0] * 4
+    if weights is not None:
+        for n, x in enumerate(list(weights)[:4]):
+            w[n] = float(x)
+    cfg.weights = (ctypes.c_float * 4)(*w)
+    cfg.smoothing = SMOOTHING[smoothing] if isinstance(smoothing, str) else int(smoothing)
+    cfg.smooth_param = float(smooth_param)
+    cfg.vocab_size = int(vocab_size)
+    cfg.force_path = PATHS[path] if isinstance(path, str) else int(path)
+    return cfg
+
+
+@dataclass
+class Stats:
+    """Device tensors behind a tb_stats_t (allocated by `Stats.allocate`)."""
+    clipped: torch.Tensor
+    total: torch.Tensor
+    closest_ref_len: torch.Tensor
+    group_distinct: torch.Tensor
+    corpus_stats: torch.Tensor
+    device_status: torch.Tensor
+
+    @staticmethod
+    def allocate(B: int, N: int, device) -> "Stats":
+        z = lambda *s, dt=torch.int32: torch.zeros(*s, dtype=dt, device=device)
+        return Stats(z(B, N), z(B, N), z(B), z(B, N), z(2 * N + 2, dt=torch.int64), z(1))
+
+    def as_struct(self) -> tb_stats_t:
+        s = tb_stats_t()
+        s.clipped = self.clipped.data_ptr()
+        s.total = self.total.data_ptr()
+        s.closest_ref_len = self.closest_ref_len.data_ptr()
+        s.group_distinct = self.group_distinct.data_ptr()
+        s.corpus_stats = self.corpus_stats.data_ptr()
+        s.device_status = self.device_status.data_ptr()
+        return s
+
+
+@dataclass
+class _Batch:
+    cand: torch.Tensor
+    cand_len: torch.Tensor
+    refs: torch.Tensor
+    ref_len: torch.Tensor
+    B: int
+    R: int
+    cand_stride: int
+    ref_stride: int
+
+
+def _batch(cand, cand_len, refs, ref_len) -> _Batch:
+    for t, name in ((cand, "cand"), (cand_len, "cand_len"), (refs, "refs"), (ref_len, "ref_len")):
+        if not t.is_cuda:
+            raise TensorBLEUError(f"{name} must live on the GPU (got {t.device})")
+        if t.dtype != torch.int32:
+            raise TensorBLEUError(f"{name} must be int32 (got {t.dtype})")
+    if cand.dim() != 2 or refs.dim() != 3 or refs.shape[0] != cand.shape[0]:
+        raise TensorBLEUError("expected cand [B, Lc] and refs [B, R, Lr]")
+    B, R = int(cand.shape[0]), int(refs.shape[1])
+    if tuple(cand_len.shape) != (B,) or tuple(ref_len.shape) != (B, R):
+        raise TensorBLEUError("expected cand_len [B] and ref_len [B, R]")
+    cand, refs = cand.contiguous(), refs.contiguous()
+    return _Batch(cand, cand_len.contiguous(), refs, ref_len.contiguous(), B, R,
+                  int(cand.shape[1]), int(refs.shape[2]))
+
+
+def _stream_ptr(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def tensorbleu_workspace_layout(B: int, R: int, cand_stride: int, ref_stride: int,
+                                cfg: tb_config_t) -> tb_layout_t:
+    lay = tb_layout_t()
+    rc = load_library().tensorbleu_workspace_layout(B, R, cand_stride, ref_stride,
+                                                    ctypes.byref(cfg), ctypes.byref(lay))
+    _check(rc, "tensorbleu_workspace_layout")
+    return lay
+
+
+def tensorbleu_workspace_bytes(B: int, R: int, cand_stride: int, ref_stride: int,
+                               cfg: tb_config_t) -> int:
+    return int(load_library().tensorbleu_workspace_bytes(B, R, cand_stride, ref_stride,
+                                                         ctypes.byref(cfg)))
+
+
+def allocate_workspace(B: int, R: int, cand_stride: int, ref_stride: int, cfg: tb_config_t,
+                       device) -> torch.Tensor:
+    n = tensorbleu_workspace_bytes(B, R, cand_stride, ref_stride, cfg)
+    if n == 0:
+        raise TensorBLEUError("tensorbleu_workspace_bytes: invalid or unsupported shape")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _full(entry: str, cand, cand_len, refs, ref_len, cfg, out, stats, workspace, stream):
+    b = _batch(cand, cand_len, refs, ref_len)
+    if workspace is None:
+        workspace = allocate_workspace(b.B, b.R, b.cand_stride, b.ref_stride, cfg, b.cand.device)
+    st = stats.as_struct() if stats is not None else None
+    rc = getattr(load_library(), entry)(
+        b.cand.data_ptr(), b.cand_stride, b.cand_len.data_ptr(), b.refs.data_ptr(), b.ref_stride,
+        b.ref_len.data_ptr(), b.B, b.R, ctypes.byref(cfg), out.data_ptr(),
+        ctypes.byref(st) if st is not None else None, workspace.data_ptr(), workspace.numel(),
+        _stream_ptr(stream))
+    _check(rc, entry)
+    return out
+
+
+def tensorbleu_sentence(cand, cand_len, refs, ref_len, cfg: tb_config_t,
+                        out: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
+                        workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """float32 [B]: one BLEU score per candidate."""
+    if out is None:
+        out = torch.empty(cand.shape[0], dtype=torch.float32, device=cand.device)
+    return _full("tensorbleu_sentence", cand, cand_len, refs, ref_len, cfg, out, stats,
+                 workspace, stream)
+
+
+def tensorbleu_corpus(cand, cand_len, refs, ref_len, cfg: tb_config_t,
+                      out: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
+                      workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """float32 [1]: one BLEU score for the batch."""
+    if out is None:
+        out = torch.zeros(1, dtype=torch.float32, device=cand.device)
+    return _full("tensorbleu_corpus", cand, cand_len, refs, ref_len, cfg, out, stats, workspace,
+                 stream)
+
+
+def tensorbleu_pack(cand, cand_len, refs, ref_len, cfg, workspace, stats=None, stream=None):
+    b = _batch(cand, cand_len, refs, ref_len)
+    st = stats.as_struct() if stats is not None else None
+    rc = load_library().tensorbleu_pack(
+        b.cand.data_ptr(), b.cand_stride, b.cand_len.data_ptr(), b.refs.data_ptr(), b.ref_stride,
+        b.ref_len.data_ptr(), b.B, b.R, ctypes.byref(cfg),
+        ctypes.byref(st) if st is not None else None, workspace.data_ptr(), workspace.numel(),
+        _stream_ptr(stream))
+    _check(rc, "tensorbleu_pack")
+
+
+def _stage(entry, cand_len, ref_len, cand_stride, ref_stride, cfg, workspace, stats, stream):
+    B, R = int(ref_len.shape[0]), int(ref_len.shape[1])
+    st = stats.as_struct() if stats is not None else None
+    rc = getattr(load_library(), entry)(
+        cand_len.data_ptr(), ref_len.data_ptr(), cand_stride, ref_stride, B, R, ctypes.byref(cfg),
+        ctypes.byref(st) if st is not None else None, workspace.data_ptr(), workspace.numel(),
+        _stream_ptr(stream))
+    _check(rc, entry)
+
+
+def tensorbleu_dictionary(cand_len, ref_len, cand_stride, ref_stride, cfg, workspace,
+                          stats=None, stream=None):
+    _stage("tensorbleu_dictionary", cand_len, ref_len, cand_stride, ref_stride, cfg, workspace,
+           stats, stream)
+
+
+def tensorbleu_count_clip(cand_len, ref_len, cand_stride, ref_stride, cfg, workspace,
+                          stats=None, stream=None):
+    _stage("tensorbleu_count_clip", cand_len, ref_len, cand_stride, ref_stride, cfg, workspace,
+           stats, stream)
+
+
+def tensorbleu_finalize(cand_len, ref_len, cand_stride, ref_stride, cfg, corpus, out, workspace,
+                        stats=None, stream=None):
+    B, R = int(ref_len.shape[0]), int(ref_len.shape[1])
+    st = stats.as_struct() if stats is not None else None
+    rc = load_library().tensorbleu_finalize(
+        cand_len.data_ptr(), ref_len.data_ptr(), B, R, cand_stride, ref_stride, ctypes.byref(cfg),
+        1 if corpus else 0, out.data_ptr(), ctypes.byref(st) if st is not None else None,
+        workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(rc, "tensorbleu_finalize")
+    return out

@@ -1,0 +1,281 @@
+// C-ABI dispatcher: argument validation, workspace carving, path selection, kernel launches.
+// Nothing here allocates, synchronises or keeps state between calls.
+#include <cstring>
+
+#include "tb_kernels.h"
+
+namespace {
+
+using namespace tb;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
+
+int ceil_log2(int32_t v) {
+  int b = 0;
+  while ((int64_t(1) << b) < int64_t(v)) ++b;
+  return b < 1 ? 1 : b;
+}
+
+bool config_ok(const tb_config_t* cfg) {
+  if (!cfg) return false;
+  if (cfg->max_n < 1 || cfg->max_n > 4) return false;
+  if (cfg->vocab_size < 1) return false;
+  if (cfg->smoothing < TB_SMOOTH_NONE || cfg->smoothing > TB_SMOOTH_EXP) return false;
+  if (cfg->force_path < TB_PATH_AUTO || cfg->force_path > TB_PATH_GLOBAL) return false;
+  return true;
+}
+
+struct Plans {
+  tb_layout_t layout;
+  DictPlan dict;
+  CountPlan count;
+  FusedPlan fused;
+};
+
+// Everything that depends on shapes only.  Returns TB_OK or an error.
+int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
+               const tb_config_t* cfg, Plans* p) {
+  if (!config_ok(cfg) || B < 0 || R < 1 || cand_stride < 1 || ref_stride < 1)
+    return TB_ERR_INVALID_ARG;
+  tb_layout_t& L = p->layout;
+  std::memset(&L, 0, sizeof(L));
+  const int N = cfg->max_n;
+  L.bits = ceil_log2(cfg->vocab_size);
+  for (int n = 1; n <= 4; ++n) L.key_bytes[n - 1] = (n * L.bits > 64) ? 16 : 8;
+  if (cand_stride > (int64_t(1) << 30) || ref_stride > (int64_t(1) << 30) || R > (1 << 20))
+    return TB_ERR_UNSUPPORTED;
+  L.group_cap = cand_stride + int64_t(R) * ref_stride;
+  const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
+  L.global_ok = ids_fit && plan_dictionary(L.group_cap, L.key_bytes, N, &p->dict) &&
+                plan_count(L.group_cap, cand_stride, ref_stride, &p->count);
+  L.fused_ok = plan_fused(cand_stride, ref_stride, R, &p->fused);
+  int path = cfg->force_path;
+  if (path == TB_PATH_AUTO) path = L.fused_ok ? TB_PATH_FUSED : TB_PATH_GLOBAL;
+  if (path == TB_PATH_FUSED && !L.fused_ok) return TB_ERR_UNSUPPORTED;
+  if (path == TB_PATH_GLOBAL && !L.global_ok) return TB_ERR_UNSUPPORTED;
+  L.path = path;
+
+  size_t off = 0;
+  const size_t bn = size_t(B) * N;
+  L.clipped_off = off;  off = align_up(off + bn * 4);
+  L.total_off = off;    off = align_up(off + bn * 4);
+  L.closest_off = off;  off = align_up(off + size_t(B) * 4);
+  L.distinct_off = off; off = align_up(off + bn * 4);
+  L.corpus_off = off;   off = align_up(off + 10 * 8);
+  if (path == TB_PATH_GLOBAL) {
+    const size_t slots = size_t(B) * size_t(L.group_cap);
+    for (int n = 0; n < N; ++n) {
+      L.keys_off[n] = off;
+      off = align_up(off + slots * L.key_bytes[n]);
+    }
+    for (int n = 0; n < N; ++n) {
+      L.inv_off[n] = off;
+      off = align_up(off + slots * 4);
+    }
+  }
+  L.bytes = off < kAlign ? kAlign : off;
+  return TB_OK;
+}
+
+struct Call {
+  Plans plans;
+  Problem pb;
+  GlobalWs ws;
+  StatPtrs st;
+  ScoreParams sp;
+  hipStream_t stream;
+  bool want_corpus_stats;
+};
+
+int prepare(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+            const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
+            const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
+            size_t workspace_bytes, void* hip_stream, bool need_tokens, int forced_path,
+            Call* c) {
+  tb_config_t local;
+  if (cfg && forced_path != TB_PATH_AUTO) {
+    local = *cfg;
+    local.force_path = forced_path;
+    cfg = &local;
+  }
+  int rc = make_plans(B, R, cand_stride, ref_stride, cfg, &c->plans);
+  if (rc != TB_OK) return rc;
+  if (B == 0) return TB_OK;
+  if (!cand_len || !ref_len || (need_tokens && (!cand || !refs))) return TB_ERR_INVALID_ARG;
+  const tb_layout_t& L = c->plans.layout;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) ||
+      workspace_bytes < L.bytes)
+    return TB_ERR_WORKSPACE;
+  unsigned char* w = static_cast<unsigned char*>(workspace);
+  Problem& pb = c->pb;
+  pb.cand = cand;
+  pb.cand_len = cand_len;
+  pb.refs = refs;
+  pb.ref_len = ref_len;
+  pb.cand_stride = cand_stride;
+  pb.ref_stride = ref_stride;
+  pb.group_cap = L.group_cap;
+  pb.B = B;
+  pb.R = R;
+  pb.N = cfg->max_n;
+  pb.bits = L.bits;
+  pb.vocab = cfg->vocab_size;
+  pb.status = stats ? stats->device_status : nullptr;
+  for (int n = 0; n < 4; ++n) {
+    c->ws.keys[n] = (L.path == TB_PATH_GLOBAL && n < pb.N) ? w + L.keys_off[n] : nullptr;
+    c->ws.inv[n] = (L.path == TB_PATH_GLOBAL && n < pb.N)
+                       ? reinterpret_cast<uint32_t*>(w + L.inv_off[n]) : nullptr;
+    c->ws.wide[n] = L.key_bytes[n] == 16;
+  }
+  StatPtrs& st = c->st;
+  st.clipped = (stats && stats->clipped) ? stats->clipped
+                                         : reinterpret_cast<int32_t*>(w + L.clipped_off);
+  st.total = (stats && stats->total) ? stats->total : reinterpret_cast<int32_t*>(w + L.total_off);
+  st.closest = (stats && stats->closest_ref_len) ? stats->closest_ref_len
+                                                 : reinterpret_cast<int32_t*>(w + L.closest_off);
+  st.distinct = (stats && stats->group_distinct) ? stats->group_distinct
+                                                 : reinterpret_cast<int32_t*>(w + L.distinct_off);
+  st.corpus = (stats && stats->corpus_stats) ? stats->corpus_stats
+                                             : reinterpret_cast<int64_t*>(w + L.corpus_off);
+  c->want_corpus_stats = stats && stats->corpus_stats;
+  ScoreParams& sp = c->sp;
+  sp.N = cfg->max_n;
+  sp.smoothing = cfg->smoothing;
+  sp.param = cfg->smooth_param;
+  bool all_zero = true;
+  for (int n = 0; n < sp.N; ++n) all_zero = all_zero && cfg->weights[n] == 0.0f;
+  for (int n = 0; n < 4; ++n)
+    sp.w[n] = (n < sp.N) ? (all_zero ? 1.0f / float(sp.N) : cfg->weights[n]) : 0.0f;
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  return TB_OK;
+}
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
+
+int run_all(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+            const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
+            const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats, void* workspace,
+            size_t workspace_bytes, void* hip_stream, bool corpus) {
+  Call c;
+  int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
+                   workspace, workspace_bytes, hip_stream, true, TB_PATH_AUTO, &c);
+  if (rc != TB_OK || B == 0) return rc;
+  if (!out_bleu) return TB_ERR_INVALID_ARG;
+  if (c.plans.layout.path == TB_PATH_FUSED) {
+    rc = hip_rc(launch_fused(c.pb, c.plans.fused, c.st, c.sp, corpus ? nullptr : out_bleu,
+                             c.stream));
+    if (rc != TB_OK) return rc;
+    if (corpus || c.want_corpus_stats) {
+      // per-sentence work is done by the fused kernel; only the batch sums remain
+      Problem quiet = c.pb;
+      quiet.status = nullptr;
+      return hip_rc(launch_finalize(quiet, c.st, c.sp, false, true, corpus, out_bleu, c.stream));
+    }
+    return TB_OK;
+  }
+  if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
+  if ((rc = hip_rc(launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream))) != TB_OK)
+    return rc;
+  if ((rc = hip_rc(launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream))) != TB_OK)
+    return rc;
+  return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
+                                out_bleu, c.stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tensorbleu_workspace_bytes(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
+                                  const tb_config_t* cfg) {
+  Plans p;
+  if (make_plans(B, R, cand_stride, ref_stride, cfg, &p) != TB_OK) return 0;
+  return p.layout.bytes;
+}
+
+int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
+                                const tb_config_t* cfg, tb_layout_t* layout) {
+  if (!layout) return TB_ERR_INVALID_ARG;
+  Plans p;
+  int rc = make_plans(B, R, cand_stride, ref_stride, cfg, &p);
+  *layout = p.layout;
+  return rc;
+}
+
+int tensorbleu_sentence(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                        const int32_t* refs, int64_t ref_stride, const int32_t* ref_len,
+                        int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
+                        const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  return run_all(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, out_bleu,
+                 stats, workspace, workspace_bytes, hip_stream, false);
+}
+
+int tensorbleu_corpus(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                      const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+                      int32_t R, const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_all(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, out_bleu,
+                 stats, workspace, workspace_bytes, hip_stream, true);
+}
+
+int tensorbleu_pack(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                    const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+                    int32_t R, const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  Call c;
+  int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
+                   workspace, workspace_bytes, hip_stream, true, TB_PATH_GLOBAL, &c);
+  if (rc != TB_OK || B == 0) return rc;
+  return hip_rc(launch_pack(c.pb, c.ws, c.stream));
+}
+
+int tensorbleu_dictionary(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,
+                          int64_t ref_stride, int32_t B, int32_t R, const tb_config_t* cfg,
+                          const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  Call c;
+  int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
+                   workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
+  if (rc != TB_OK || B == 0) return rc;
+  return hip_rc(launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream));
+}
+
+int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,
+                          int64_t ref_stride, int32_t B, int32_t R, const tb_config_t* cfg,
+                          const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  Call c;
+  int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
+                   workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
+  if (rc != TB_OK || B == 0) return rc;
+  return hip_rc(launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream));
+}
+
+int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t B, int32_t R,
+                        int64_t cand_stride, int64_t ref_stride, const tb_config_t* cfg,
+                        int32_t corpus, float* out_bleu, const tb_stats_t* stats, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  Call c;
+  int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
+                   workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
+  if (rc != TB_OK || B == 0) return rc;
+  if (!out_bleu) return TB_ERR_INVALID_ARG;
+  return hip_rc(launch_finalize(c.pb, c.st, c.sp, corpus == 0,
+                                corpus != 0 || c.want_corpus_stats, corpus != 0, out_bleu,
+                                c.stream));
+}
+
+const char* tensorbleu_status_string(int status) {
+  switch (status) {
+    case TB_OK: return "ok";
+    case TB_ERR_INVALID_ARG: return "invalid argument";
+    case TB_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TB_ERR_UNSUPPORTED: return "shape not supported by the selected path";
+    case TB_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

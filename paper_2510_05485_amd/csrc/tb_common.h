@@ -1,0 +1,124 @@
+// Shared device-side helpers and argument blocks of the gfx950 BLEU kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tensorbleu.h"
+
+namespace tb {
+
+constexpr int kWave = 64;                 // CDNA wavefront width
+constexpr uint32_t kEmpty = 0xFFFFFFFFu;  // empty hash-table word
+constexpr int kLdsBudget = 160 * 1024;    // LDS per compute unit (and per workgroup) on gfx950
+
+// 128-bit key for orders whose n*bits exceeds 64.  lo holds the least significant 64 bits.
+struct __attribute__((aligned(16))) Key128 {
+  uint64_t lo, hi;
+};
+
+__device__ __forceinline__ bool key_eq(uint64_t a, uint64_t b) { return a == b; }
+__device__ __forceinline__ bool key_eq(const Key128& a, const Key128& b) {
+  return a.lo == b.lo && a.hi == b.hi;
+}
+
+// 32-bit avalanche of a packed key; the low bits pick the slot, the top 16 are the fingerprint.
+__device__ __forceinline__ uint32_t fmix(uint32_t h) {
+  h ^= h >> 16;
+  h *= 0x7FEB352Du;
+  h ^= h >> 15;
+  h *= 0x846CA68Bu;
+  h ^= h >> 16;
+  return h;
+}
+__device__ __forceinline__ uint32_t key_hash(uint64_t k) {
+  uint32_t lo = uint32_t(k), hi = uint32_t(k >> 32);
+  return fmix(lo * 0x9E3779B1u ^ fmix(hi + 0x85EBCA77u));
+}
+__device__ __forceinline__ uint32_t key_hash(const Key128& k) {
+  return fmix(key_hash(k.lo) ^ (key_hash(k.hi) * 0xC2B2AE3Du + 0x27D4EB2Fu));
+}
+
+// Inclusive scan / sum across the 64 lanes of a wavefront with cross-lane shuffles.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(v, d, kWave);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_down(v, d, kWave);
+  return v;  // valid in lane 0
+}
+
+// Exclusive scan of one int per thread over the workgroup (up to 1024 threads); also returns
+// the workgroup total.  `scratch` needs 17 ints of LDS.  Contains two barriers.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* scratch, int* total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int nwaves = (blockDim.x + kWave - 1) / kWave;
+  int incl = wave_inclusive_scan(v);
+  if (lane == kWave - 1) scratch[wave] = incl;
+  __syncthreads();
+  if (wave == 0) {
+    int w = (lane < nwaves) ? scratch[lane] : 0;
+    int wi = wave_inclusive_scan(w);
+    if (lane < nwaves) scratch[lane] = wi - w;
+    if (lane == nwaves - 1) scratch[16] = wi;
+  }
+  __syncthreads();
+  *total = scratch[16];
+  return scratch[wave] + incl - v;
+}
+
+// Sum of one int per thread over the workgroup; result valid in every thread.
+// `scratch` needs 17 ints of LDS.  Contains two barriers.
+__device__ __forceinline__ int block_sum(int v, int* scratch) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int nwaves = (blockDim.x + kWave - 1) / kWave;
+  int s = wave_sum(v);
+  if (lane == 0) scratch[wave] = s;
+  __syncthreads();
+  if (wave == 0) {
+    int w = (lane < nwaves) ? scratch[lane] : 0;
+    w = wave_sum(w);
+    if (lane == 0) scratch[16] = w;
+  }
+  __syncthreads();
+  return scratch[16];
+}
+
+// Problem description handed to every kernel (device pointers + shapes).
+struct Problem {
+  const int32_t* cand;
+  const int32_t* cand_len;
+  const int32_t* refs;
+  const int32_t* ref_len;
+  int64_t cand_stride, ref_stride;
+  int64_t group_cap;  // cand_stride + R * ref_stride
+  int32_t B, R, N;
+  int32_t bits;       // ceil(log2(vocab)), >= 1
+  int32_t vocab;
+  int32_t* status;    // may be null
+};
+
+// Length of a row as the kernels use it: clamped into [0, stride].
+__device__ __forceinline__ int clamped_len(int len, int64_t stride, int32_t* status) {
+  if (len < 0 || len > stride) {
+    if (status) atomicOr(status, TB_DEV_LENGTH_RANGE);
+    len = len < 0 ? 0 : int(stride);
+  }
+  return len;
+}
+
+struct ScoreParams {
+  float w[4];
+  int32_t N;
+  int32_t smoothing;
+  float param;
+};
+
+}  // namespace tb

@@ -1,0 +1,110 @@
+// Score assembly from the integer statistics (paper Section 3.4): per-sentence scores, and the
+// corpus variant that sums numerators, denominators and lengths over the batch first.
+#include "tb_kernels.h"
+#include "tb_score.h"
+
+namespace tb {
+
+struct FinalArgs {
+  Problem pb;
+  StatPtrs st;
+  ScoreParams sp;
+  float* out;
+};
+
+// One lane per sentence.
+__global__ __launch_bounds__(256) void sentence_score_kernel(FinalArgs a) {
+  const Problem& pb = a.pb;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= pb.B) return;
+  const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
+  const int r = closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, pb.R, pb.ref_stride, pb.status);
+  a.st.closest[i] = r;
+  int cl[4], to[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    cl[n] = (n < pb.N) ? a.st.clipped[int64_t(i) * pb.N + n] : 0;
+    to[n] = (n < pb.N) ? a.st.total[int64_t(i) * pb.N + n] : 0;
+  }
+  a.out[i] = bleu_from_stats<int>(cl, to, c, r, a.sp);
+}
+
+__device__ __forceinline__ long long wave_sum64(long long v) {
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) {
+    int lo = __shfl_down(int(uint32_t(uint64_t(v))), d, kWave);
+    int hi = __shfl_down(int(uint32_t(uint64_t(v) >> 32)), d, kWave);
+    v += (long long)((uint64_t(uint32_t(hi)) << 32) | uint32_t(lo));
+  }
+  return v;
+}
+
+// A single workgroup strides over the batch, reduces the 2N+2 integer sums with wavefront
+// shuffles and LDS, and lane 0 forms the corpus score.
+__global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_score) {
+  __shared__ long long part[16][10];
+  const Problem& pb = a.pb;
+  long long acc[10];
+#pragma unroll
+  for (int k = 0; k < 10; ++k) acc[k] = 0;
+  for (int i = threadIdx.x; i < pb.B; i += blockDim.x) {
+    const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
+    const int r =
+        closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, pb.R, pb.ref_stride, pb.status);
+    a.st.closest[i] = r;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      if (n < pb.N) {
+        acc[n] += a.st.clipped[int64_t(i) * pb.N + n];
+        acc[4 + n] += a.st.total[int64_t(i) * pb.N + n];
+      }
+    }
+    acc[8] += c;
+    acc[9] += r;
+  }
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+  for (int k = 0; k < 10; ++k) {
+    const long long s = wave_sum64(acc[k]);
+    if (lane == 0) part[wave][k] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int nwaves = blockDim.x / kWave;
+    long long tot[10];
+    for (int k = 0; k < 10; ++k) {
+      tot[k] = 0;
+      for (int w = 0; w < nwaves; ++w) tot[k] += part[w][k];
+    }
+    for (int n = 0; n < pb.N; ++n) {
+      a.st.corpus[n] = tot[n];
+      a.st.corpus[pb.N + n] = tot[4 + n];
+    }
+    a.st.corpus[2 * pb.N] = tot[8];
+    a.st.corpus[2 * pb.N + 1] = tot[9];
+    if (write_score) a.out[0] = bleu_from_stats<long long>(tot, tot + 4, tot[8], tot[9], a.sp);
+  }
+}
+
+hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
+                           bool sentence_scores, bool corpus_sums, bool corpus_score,
+                           float* out_bleu, hipStream_t s) {
+  FinalArgs a;
+  a.pb = pb;
+  a.st = st;
+  a.sp = sp;
+  a.out = out_bleu;
+  if (sentence_scores) {
+    const int blocks = (pb.B + 255) / 256;
+    hipLaunchKernelGGL(sentence_score_kernel, dim3(blocks), dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (corpus_sums || corpus_score) {
+    hipLaunchKernelGGL(corpus_kernel, dim3(1), dim3(1024), 0, s, a, corpus_score ? 1 : 0);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
+}  // namespace tb

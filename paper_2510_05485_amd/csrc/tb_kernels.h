@@ -1,0 +1,60 @@
+// Host-side launch interface between the C-ABI dispatcher and the kernel translation units.
+#pragma once
+
+#include "tb_common.h"
+
+namespace tb {
+
+// Resolved pointers into the caller's workspace for the GLOBAL path.
+struct GlobalWs {
+  void* keys[4];      // packed keys per order, B * group_cap entries of 8 or 16 bytes
+  uint32_t* inv[4];   // offset dictionary ids per order, B * group_cap entries
+  int32_t wide[4];    // 1 when the order uses 16-byte keys
+};
+
+// Integer statistics (either the caller's arrays or workspace scratch; never null).
+struct StatPtrs {
+  int32_t* clipped;   // [B, N]
+  int32_t* total;     // [B, N]
+  int32_t* closest;   // [B]
+  int32_t* distinct;  // [B, N]
+  int64_t* corpus;    // [2N+2]
+};
+
+struct DictPlan {
+  int threads;        // workgroup size
+  int table_slots;    // power of two, >= 2 * group_cap and >= threads
+  int key_bytes;      // widest key among the orders (8 or 16)
+  size_t lds_bytes;   // dynamic LDS of the dictionary kernel
+  size_t lds_table_off, lds_slot_off;
+};
+struct CountPlan {
+  int threads;
+  size_t lds_bytes;
+};
+struct FusedPlan {
+  int threads;
+  int table_slots;     // power of two >= 2 * cand_stride
+  int ref_batch;       // references counted per sweep (2 per 32-bit counter word)
+  size_t lds_bytes;
+  size_t off_table, off_cand_cnt, off_ref_cnt;
+};
+
+bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan);
+bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, CountPlan* plan);
+bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, FusedPlan* plan);
+
+hipError_t launch_pack(const Problem& pb, const GlobalWs& ws, hipStream_t s);
+hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPlan& plan,
+                             int32_t* distinct, hipStream_t s);
+hipError_t launch_count_clip(const Problem& pb, const GlobalWs& ws, const CountPlan& plan,
+                             const StatPtrs& st, hipStream_t s);
+// sentence_scores: out_bleu[B] per-sentence scores; corpus_sums: fill st.corpus;
+// corpus_score: additionally write the corpus score to out_bleu[0] (not with sentence_scores).
+hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
+                           bool sentence_scores, bool corpus_sums, bool corpus_score,
+                           float* out_bleu, hipStream_t s);
+hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs& st,
+                        const ScoreParams& sp, float* out_bleu_or_null, hipStream_t s);
+
+}  // namespace tb

@@ -1,0 +1,93 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and its pure
+host functions (layout, argument validation, status strings) behave as the header says.  No
+kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_05485_amd as tb
+from paper_2510_05485_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tensorbleu.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(tb.LIB_PATH):
+        from paper_2510_05485_amd import build
+        build.build(verbose=False)
+    return tb.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tensorbleu_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 9
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_strings(lib):
+    assert tb.tensorbleu_status_string(0) == "ok"
+    seen = {tb.tensorbleu_status_string(k) for k in range(5)}
+    assert len(seen) == 5
+    assert tb.tensorbleu_status_string(99) == "unknown status"
+
+
+def test_layout_key_widths_follow_vocab(lib):
+    cfg = tb.make_config(vocab_size=50257, path="global")
+    lay = tb.tensorbleu_workspace_layout(512, 4, 1024, 1280, cfg)
+    assert lay.bits == 16 and list(lay.key_bytes) == [8, 8, 8, 8]
+    assert lay.group_cap == 1024 + 4 * 1280 and lay.path == 2 and lay.global_ok == 1
+    cfg = tb.make_config(vocab_size=262144, path="global")
+    lay = tb.tensorbleu_workspace_layout(1024, 1, 2048, 2048, cfg)
+    assert lay.bits == 18 and list(lay.key_bytes) == [8, 8, 8, 16]
+    slots = 1024 * 4096
+    assert lay.keys_off[3] - lay.keys_off[2] >= slots * 8
+    assert lay.inv_off[0] - lay.keys_off[3] >= slots * 16
+    assert lay.bytes >= lay.inv_off[3] + slots * 4
+    assert lay.bytes == tb.tensorbleu_workspace_bytes(1024, 1, 2048, 2048, cfg)
+    for off in list(lay.keys_off) + list(lay.inv_off) + [lay.corpus_off]:
+        assert off % 256 == 0
+    cfg = tb.make_config(vocab_size=64, path="global")
+    assert tb.tensorbleu_workspace_layout(4096, 2, 512, 640, cfg).bits == 6
+    cfg = tb.make_config(vocab_size=1, path="global")
+    assert tb.tensorbleu_workspace_layout(1, 1, 8, 8, cfg).bits == 1
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    good = tb.make_config(vocab_size=100, path="global")
+    assert tb.tensorbleu_workspace_bytes(4, 1, 16, 16, good) > 0
+    assert tb.tensorbleu_workspace_bytes(-1, 1, 16, 16, good) == 0
+    assert tb.tensorbleu_workspace_bytes(4, 0, 16, 16, good) == 0
+    assert tb.tensorbleu_workspace_bytes(4, 1, 0, 16, good) == 0
+    for bad in (tb.make_config(max_n=0, vocab_size=100), tb.make_config(max_n=5, vocab_size=100),
+                tb.make_config(vocab_size=0), tb.make_config(vocab_size=100, smoothing=7),
+                tb.make_config(vocab_size=100, path=3)):
+        assert tb.tensorbleu_workspace_bytes(4, 1, 16, 16, bad) == 0
+    lay = binding.tb_layout_t()
+    rc = lib.tensorbleu_workspace_layout(4, 1, 16, 16, None, ctypes.byref(lay))
+    assert rc == 1
+    # NULL data pointers / workspace are caught before any launch
+    args = [None, 16, None, None, 16, None, 4, 1, ctypes.byref(good), None, None, None, 0, None]
+    assert lib.tensorbleu_sentence(*args) == 1
+    # B == 0 is a successful no-op
+    args[6] = 0
+    assert lib.tensorbleu_sentence(*args) == 0
+
+
+def test_group_too_large_for_lds_is_unsupported_not_wrong(lib):
+    cfg = tb.make_config(vocab_size=50257, path="global")
+    lay = binding.tb_layout_t()
+    rc = lib.tensorbleu_workspace_layout(2, 8, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
+    assert rc == 3 and lay.global_ok == 0
+    assert tb.tensorbleu_workspace_bytes(2, 8, 8192, 8192, cfg) == 0

@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Integer statistics (clipped, total, closest reference length, dictionary sizes) must match
+bit-exactly; scores (fp32 on the GPU, fp64 in the oracle) within 1e-5 absolute.  The fp32 tail
+evaluates at most four log terms and two exps with |log p| < 25, each correctly rounded to a
+few ulp (~1e-7 relative), so 1e-5 leaves two orders of magnitude of slack.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_05485_amd as tb
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+DEV = "cuda:0"
+PATHS = ["global", "fused"]
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+class Device:
+    def __init__(self, w: syn.Workload):
+        self.w = w
+        self.cand, self.cand_len = dev(w.cand), dev(w.cand_len)
+        self.refs, self.ref_len = dev(w.refs), dev(w.ref_len)
+
+
+def path_supported(w, path, max_n=4):
+    cfg = tb.make_config(max_n=max_n, vocab_size=w.vocab, path="global")
+    lay = tb.binding.tb_layout_t()
+    import ctypes
+    tb.load_library().tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2],
+                                                  ctypes.byref(cfg), ctypes.byref(lay))
+    return bool(lay.fused_ok if path == "fused" else lay.global_ok)
+
+
+def run_gpu(d: Device, run: syn.Run, path, max_n=None, weights=None, corpus=None):
+    w = d.w
+    max_n = max_n or w.max_n
+    cfg = tb.make_config(max_n=max_n, weights=weights if weights is not None else w.weights,
+                         smoothing=run.smoothing, smooth_param=run.smooth_param,
+                         vocab_size=w.vocab, path=path)
+    stats = tb.Stats.allocate(w.B, max_n, DEV)
+    corpus = run.corpus if corpus is None else corpus
+    fn = tb.tensorbleu_corpus if corpus else tb.tensorbleu_sentence
+    out = fn(d.cand, d.cand_len, d.refs, d.ref_len, cfg, stats=stats)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), stats
+
+
+def run_oracle(w, run, max_n=None, weights=None, threads=8):
+    max_n = max_n or w.max_n
+    weights = weights if weights is not None else w.weights
+    return oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, max_n=max_n, weights=weights,
+                       smoothing=run.smoothing, smooth_param=run.smooth_param, threads=threads)
+
+
+def check(w, run, path, max_n=None, weights=None, d=None):
+    resolved = path
+    if path == "auto":
+        resolved = "fused" if path_supported(w, "fused", max_n or w.max_n) else "global"
+    if not path_supported(w, resolved, max_n or w.max_n):
+        pytest.skip(f"{path} path does not support this shape")
+    d = d or Device(w)
+    ref = run_oracle(w, run, max_n, weights)
+    out, st = run_gpu(d, run, path, max_n, weights, corpus=False)
+    assert st.device_status.item() == 0
+    np.testing.assert_array_equal(st.clipped.cpu().numpy(), ref.clipped)
+    np.testing.assert_array_equal(st.total.cpu().numpy(), ref.total)
+    np.testing.assert_array_equal(st.closest_ref_len.cpu().numpy(), ref.closest_ref_len)
+    expect_distinct = ref.group_distinct if resolved == "global" else ref.cand_distinct
+    np.testing.assert_array_equal(st.group_distinct.cpu().numpy(), expect_distinct)
+    assert np.isfinite(out).all()
+    assert np.abs(out.astype(np.float64) - ref.bleu).max() <= TOL
+    cout, cst = run_gpu(d, run, path, max_n, weights, corpus=True)
+    np.testing.assert_array_equal(cst.corpus_stats.cpu().numpy(), ref.corpus_stats)
+    assert abs(float(cout[0]) - ref.corpus_bleu) <= TOL
+    return out, ref
+
+
+ALL_MODES = [syn.Run("none"), syn.Run("floor", 0.1), syn.Run("add-k", 1.0), syn.Run("exp")]
+
+
+# ------------------------------------------------------------------------ small and edge cases
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("run", ALL_MODES, ids=lambda r: r.smoothing)
+def test_config1_all_smoothing_modes(path, run):
+    check(syn.make(1), run, path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("seed,B,R,V,L", [
+    (101, 33, 1, 3, 12),        # tiny vocabulary: almost every n-gram repeats
+    (102, 17, 3, 7, 70),        # several references, lengths 0..70 (empty rows included)
+    (103, 9, 2, 50257, 300),    # 64-bit keys at exactly 64 bits for n = 4
+    (104, 5, 1, 262144, 1500),  # 128-bit keys, more than one pack tile and a ragged tail
+    (105, 64, 5, 2, 40),        # binary vocabulary, five references
+    (106, 3, 1, 2 ** 31 - 1, 90),  # widest ids: 31 bits per token, 124-bit 4-grams
+    (107, 40, 2, 1000, 3),      # candidates shorter than the highest order
+])
+def test_random_ragged_batches(path, seed, B, R, V, L):
+    w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L)
+    d = Device(w)
+    for run in ALL_MODES:
+        check(w, run, path, d=d)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_lower_orders_and_custom_weights(path):
+    w = syn.random_small(111, B=20, R=2, vocab=9, max_len=50)
+    d = Device(w)
+    check(w, syn.Run("none"), path, max_n=1, weights=[1.0], d=d)
+    check(w, syn.Run("floor", 0.1), path, max_n=2, weights=[0.7, 0.3], d=d)
+    check(w, syn.Run("exp"), path, max_n=3, weights=[0.2, 0.3, 0.5], d=d)
+    check(w, syn.Run("add-k", 1.0), path, max_n=4, weights=[0.5, 0.5, 0.0, 0.0], d=d)
+    check(w, syn.Run("add-k", 0.5), path, max_n=4, weights=[1.0, 1.0, 1.0, 1.0], d=d)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_closed_forms_on_the_gpu(path):
+    # identical -> 1; prefix -> exp(1 - r/c); disjoint -> 0; clipping by max over references
+    L = 40
+    ref = np.arange(1, L + 1, dtype=np.int32)
+    cands = [ref.copy(), ref[:25].copy(), ref + 1000, np.full(L, 7, np.int32)]
+    refs = [[ref, ref], [ref, ref], [ref, ref],
+            [np.r_[np.full(2, 7), ref[7:37]].astype(np.int32),
+             np.r_[ref[7:27], np.full(3, 7)].astype(np.int32)]]
+    B, R = len(cands), 2
+    cand = np.zeros((B, 64), np.int32)
+    refa = np.zeros((B, R, 64), np.int32)
+    cl = np.zeros(B, np.int32)
+    rl = np.zeros((B, R), np.int32)
+    for i in range(B):
+        cand[i, :len(cands[i])] = cands[i]
+        cl[i] = len(cands[i])
+        for j in range(R):
+            refa[i, j, :len(refs[i][j])] = refs[i][j]
+            rl[i, j] = len(refs[i][j])
+    w = syn.Workload("closed", 2048, cand, cl, refa, rl)
+    if not path_supported(w, path):
+        pytest.skip("unsupported")
+    out, st = run_gpu(Device(w), syn.Run("none"), path)
+    assert abs(out[0] - 1.0) <= TOL
+    assert abs(out[1] - np.exp(1 - 40 / 25)) <= TOL
+    assert out[2] == 0.0
+    clipped = st.clipped.cpu().numpy()
+    assert list(clipped[3]) == [3, 2, 1, 0]      # max(2, 3) sevens, then 7-7 bigrams etc.
+    assert out[3] == 0.0
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_pad_cells_and_other_sentences_do_not_matter(path):
+    w = syn.random_small(120, B=24, R=2, vocab=30, max_len=90)
+    if not path_supported(w, path):
+        pytest.skip("unsupported")
+    run = syn.Run("exp")
+    base, st0 = run_gpu(Device(w), run, path)
+    rng = np.random.default_rng(5)
+    cand, refs = w.cand.copy(), w.refs.copy()
+    cpad = np.arange(cand.shape[1])[None, :] >= w.cand_len[:, None]
+    rpad = np.arange(refs.shape[2])[None, None, :] >= w.ref_len[:, :, None]
+    cand[cpad] = rng.integers(0, 30, cpad.sum())
+    refs[rpad] = rng.integers(0, 30, rpad.sum())
+    w2 = syn.Workload("poisoned", w.vocab, cand, w.cand_len, refs, w.ref_len)
+    out, st = run_gpu(Device(w2), run, path)
+    np.testing.assert_array_equal(out, base)
+    np.testing.assert_array_equal(st.clipped.cpu().numpy(), st0.clipped.cpu().numpy())
+    # sentence 3 alone gives the same bits as sentence 3 inside the batch
+    w3 = syn.Workload("alone", w.vocab, w.cand[3:4].copy(), w.cand_len[3:4].copy(),
+                      w.refs[3:4].copy(), w.ref_len[3:4].copy())
+    out3, _ = run_gpu(Device(w3), run, path)
+    assert out3[0] == base[3]
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_device_status_reports_bad_tokens_and_lengths(path):
+    w = syn.random_small(130, B=6, R=1, vocab=50, max_len=40, min_len=10)
+    if not path_supported(w, path):
+        pytest.skip("unsupported")
+    w.cand[2, 3] = 50                       # == vocab_size: out of range, inside the length
+    _, st = run_gpu(Device(w), syn.Run("none"), path)
+    assert st.device_status.item() & tb.binding.TB_DEV_TOKEN_RANGE
+    w = syn.random_small(130, B=6, R=1, vocab=50, max_len=40, min_len=10)
+    w.cand_len[4] = 41                      # beyond the stride: clamped, flagged, no fault
+    w.ref_len[1, 0] = -3
+    _, st = run_gpu(Device(w), syn.Run("none"), path)
+    assert st.device_status.item() & tb.binding.TB_DEV_LENGTH_RANGE
+
+
+def test_determinism_of_integer_statistics():
+    w = syn.make(1)
+    d = Device(w)
+    a, sa = run_gpu(d, syn.Run("exp"), "global")
+    b, sb = run_gpu(d, syn.Run("exp"), "global")
+    np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(sa.clipped.cpu().numpy(), sb.clipped.cpu().numpy())
+
+
+def test_paths_agree_bit_for_bit():
+    w = syn.config3(B=32)
+    if not (path_supported(w, "fused") and path_supported(w, "global")):
+        pytest.skip("needs both paths")
+    d = Device(w)
+    a, sa = run_gpu(d, syn.Run("exp"), "global")
+    b, sb = run_gpu(d, syn.Run("exp"), "fused")
+    np.testing.assert_array_equal(sa.clipped.cpu().numpy(), sb.clipped.cpu().numpy())
+    np.testing.assert_array_equal(sa.total.cpu().numpy(), sb.total.cpu().numpy())
+    np.testing.assert_array_equal(a, b)
+
+
+# ------------------------------------------------------------------- full-size configurations
+
+@pytest.mark.parametrize("path", PATHS + ["auto"])
+@pytest.mark.parametrize("config", [2, 3, 4, 5])
+def test_full_size_configs(config, path):
+    w = syn.make(config)
+    d = Device(w)
+    for run in w.runs:
+        if run.corpus:
+            continue                        # check() always covers the corpus variant too
+        check(w, run, path, d=d)

@@ -1,0 +1,100 @@
+"""GPU parity of the GLOBAL path one pass at a time (pack, dictionary, count/clip, finalize).
+
+Expected keys are formed here from the definition with Python integers; the dictionary's ids are
+internal (any bijection is correct), so the test checks what is unique: ids are equal exactly
+when the n-grams are equal, they are dense in the group's offset range, and the dictionary size
+equals the oracle's count of distinct n-grams.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_05485_amd as tb
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def stage_all(w, run=syn.Run("exp"), corpus=False):
+    cfg = tb.make_config(max_n=w.max_n, weights=w.weights, smoothing=run.smoothing,
+                         smooth_param=run.smooth_param, vocab_size=w.vocab, path="global")
+    cs, rs = w.cand.shape[1], w.refs.shape[2]
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, cs, rs, cfg)
+    ws = tb.allocate_workspace(w.B, w.R, cs, rs, cfg, DEV)
+    ws.fill_(0xAB)                                   # the workspace needs no initialisation
+    stats = tb.Stats.allocate(w.B, w.max_n, DEV)
+    cand, cl, refs, rl = dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len)
+    tb.tensorbleu_pack(cand, cl, refs, rl, cfg, ws, stats)
+    tb.tensorbleu_dictionary(cl, rl, cs, rs, cfg, ws, stats)
+    tb.tensorbleu_count_clip(cl, rl, cs, rs, cfg, ws, stats)
+    out = torch.empty(1 if corpus else w.B, dtype=torch.float32, device=DEV)
+    tb.tensorbleu_finalize(cl, rl, cs, rs, cfg, corpus, out, ws, stats)
+    torch.cuda.synchronize()
+    return lay, ws.cpu().numpy(), stats, out.cpu().numpy()
+
+
+def read_keys(wsb, lay, n, count):
+    kb = lay.key_bytes[n - 1]
+    raw = wsb[lay.keys_off[n - 1]: lay.keys_off[n - 1] + count * kb].view(np.uint64)
+    if kb == 8:
+        return [int(x) for x in raw]
+    return [int(lo) | (int(hi) << 64) for lo, hi in raw.reshape(-1, 2)]
+
+
+def expected_key(tokens, bits):
+    k = 0
+    for t in tokens:
+        k = (k << bits) | int(t)
+    return k
+
+
+@pytest.mark.parametrize("seed,B,R,V,L", [(201, 6, 2, 64, 50), (202, 4, 1, 50257, 1100),
+                                          (203, 3, 1, 262144, 1300), (204, 2, 3, 2 ** 31 - 1, 80)])
+def test_pack_dictionary_count_passes(seed, B, R, V, L):
+    w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=L // 2)
+    lay, wsb, stats, out = stage_all(w)
+    cap, cs, rs = lay.group_cap, w.cand.shape[1], w.refs.shape[2]
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+    for n in range(1, 5):
+        keys = read_keys(wsb, lay, n, B * cap)
+        inv = wsb[lay.inv_off[n - 1]: lay.inv_off[n - 1] + B * cap * 4].view(np.uint32)
+        for g in range(B):
+            rows = [(0, w.cand[g], w.cand_len[g])] + [
+                (cs + j * rs, w.refs[g, j], w.ref_len[g, j]) for j in range(R)]
+            seen = {}
+            for off, row, ln in rows:
+                for p in range(max(ln - n + 1, 0)):
+                    slot = g * cap + off + p
+                    gram = tuple(int(t) for t in row[p:p + n])
+                    assert keys[slot] == expected_key(gram, lay.bits), (n, g, off, p)
+                    local = int(inv[slot]) - g * cap
+                    assert seen.setdefault(gram, local) == local      # equal n-gram -> equal id
+            ids = sorted(seen.values())
+            assert ids == list(range(len(ids)))                        # dense and injective
+            assert len(ids) == ref.group_distinct[g, n - 1]
+    np.testing.assert_array_equal(stats.group_distinct.cpu().numpy(), ref.group_distinct)
+    np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
+    np.testing.assert_array_equal(stats.total.cpu().numpy(), ref.total)
+    assert np.abs(out - ref.bleu).max() <= 1e-5
+
+
+def test_staged_calls_equal_the_single_call_on_config1():
+    w = syn.make(1)
+    _, _, stats, out = stage_all(w, syn.Run("add-k", 1.0))
+    cfg = tb.make_config(smoothing="add-k", smooth_param=1.0, vocab_size=w.vocab, path="global")
+    st2 = tb.Stats.allocate(w.B, 4, DEV)
+    out2 = tb.tensorbleu_sentence(dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len), cfg,
+                                  stats=st2)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out, out2.cpu().numpy())
+    np.testing.assert_array_equal(stats.clipped.cpu().numpy(), st2.clipped.cpu().numpy())
+    _, _, cstats, cout = stage_all(w, syn.Run("add-k", 1.0), corpus=True)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="add-k", smooth_param=1.0)
+    np.testing.assert_array_equal(cstats.corpus_stats.cpu().numpy(), ref.corpus_stats)
+    assert abs(cout[0] - ref.corpus_bleu) <= 1e-5
