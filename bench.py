@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark: per-sentence token-ID BLEU sentences/s on one MI355X, with roofline and CPU baseline.
+
+A "step" is one pass of the whole hot path (n-gram extraction .. geometric mean) over one
+synthetic batch already resident in HBM.  The default workload is the headline configuration
+(B=512 candidates of 1024 tokens, 4 references each, vocabulary 50257).  One JSON line is
+printed; see the README section of the design doc for the meaning of every field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(w, lay, N):
+    """Bytes each pass must move by the method itself (tokens, keys, ids, statistics)."""
+    T = w.tokens
+    G = [w.ngrams(n) for n in range(1, N + 1)]
+    kb = [lay.key_bytes[n] for n in range(N)]
+    stats = 8 * w.B * N
+    return {
+        "pack": 4 * T + sum(k * g for k, g in zip(kb, G)),
+        "dictionary": sum((k + 4) * g for k, g in zip(kb, G)),
+        "count_clip": 4 * sum(G) + stats,
+        "finalize": stats + 4 * w.B * (1 + w.R) + 4 * w.B,
+        "fused": 4 * T + 4 * w.B + stats,
+    }
+
+
+def time_region(fn, iters, torch):
+    """Average milliseconds of `fn` over `iters` back-to-back enqueues, timed with HIP events
+    recorded on the stream the kernels are launched on (torch's current stream)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def cpu_baseline(w, run, budget_s=12.0):
+    """The oracle, as it stands, on the host cores: sentences/s on a bounded sample."""
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    threads = min(cores, 16)
+    sample = w.subset(min(w.B, 256))
+    args = dict(max_n=w.max_n, weights=w.weights, smoothing=run.smoothing,
+                smooth_param=run.smooth_param)
+    best, reps, t_end = None, 0, time.time() + budget_s
+    while reps < 3 and (reps == 0 or time.time() < t_end):
+        t0 = time.time()
+        oracle.bleu(sample.cand, sample.cand_len, sample.refs, sample.ref_len, threads=threads,
+                    **args)
+        dt = time.time() - t0
+        best = dt if best is None else min(best, dt)
+        reps += 1
+    return {"value": sample.B / best, "unit": "sentences/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample.B} sentence groups of the workload, best of {reps}, "
+                      f"{threads} std::threads over sentences"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
+    ap.add_argument("--path", default="auto", choices=["auto", "fused", "global"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); sentence groups are "
+              "independent, so N GPUs would each score B/N groups with no exchange",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_05485_amd as tb
+    import synth_inputs as syn
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    tb.load_library()
+    dev = "cuda:0"
+    w = syn.make(a.config)
+    run = [r for r in w.runs if not r.corpus][-1]
+    N = w.max_n
+    to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    cand, cl, refs, rl = to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len)
+    cs, rs = int(w.cand.shape[1]), int(w.refs.shape[2])
+
+    def config(path):
+        return tb.make_config(max_n=N, weights=w.weights, smoothing=run.smoothing,
+                              smooth_param=run.smooth_param, vocab_size=w.vocab, path=path)
+
+    cfg = config(a.path)
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, cs, rs, cfg)
+    path = {1: "fused", 2: "global"}[lay.path]
+    ws = tb.allocate_workspace(w.B, w.R, cs, rs, cfg, dev)
+    out = torch.empty(w.B, dtype=torch.float32, device=dev)
+    stats = tb.Stats.allocate(w.B, N, dev)
+
+    def step():
+        tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out, stats=stats, workspace=ws)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    ev_ms = time_region(step, a.steps, torch)
+    ms = max(wall_ms, ev_ms)    # enqueue-bound runs show up in wall time, GPU-bound in events
+
+    # per-kernel durations, each kernel on its own between HIP events
+    alg = algorithmic_bytes(w, lay, N)
+    passes = []
+    if path == "global":
+        gcfg = config("global")
+        stages = [
+            ("pack", lambda: tb.tensorbleu_pack(cand, cl, refs, rl, gcfg, ws, stats)),
+            ("dictionary", lambda: tb.tensorbleu_dictionary(cl, rl, cs, rs, gcfg, ws, stats)),
+            ("count_clip", lambda: tb.tensorbleu_count_clip(cl, rl, cs, rs, gcfg, ws, stats)),
+            ("finalize", lambda: tb.tensorbleu_finalize(cl, rl, cs, rs, gcfg, False, out, ws,
+                                                        stats)),
+        ]
+    else:
+        stages = [("fused", step)]
+    for name, fn in stages:
+        for _ in range(3):
+            fn()
+        t_ms = time_region(fn, a.steps, torch)
+        gbps = alg[name] / (t_ms * 1e-3) / 1e9
+        passes.append({"kernel": name, "us": round(t_ms * 1e3, 2), "alg_bytes": int(alg[name]),
+                       "GBps": round(gbps, 1), "frac_hbm": round(gbps / HBM_PEAK_GBPS, 4)})
+    dom = max(passes, key=lambda p: p["us"])
+    roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["GBps"],
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_hbm"],
+                "traffic": a.traffic_bytes}
+
+    result = {
+        "metric": "per-sentence BLEU sentences/sec at B=512, L=1024; % HBM roofline",
+        "value": round(w.B / (ms * 1e-3), 1), "unit": "sentences/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64 keys / u32 counts / f32 scores", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "R": w.R, "cand_len": cs, "ref_stride": rs,
+                   "vocab": w.vocab, "max_n": N, "smoothing": run.smoothing, "path": path,
+                   "tokens": w.tokens},
+        "ms_per_step_events": round(ev_ms, 5), "ms_per_step_wall": round(wall_ms, 5),
+        "roofline": roofline, "passes": passes,
+    }
+    if not a.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, run)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
