@@ -114,7 +114,7 @@ def main():
     path = {1: "fused", 2: "global"}[lay.path]
     ws = tb.allocate_workspace(w.B, w.R, cs, rs, cfg, dev)
     out = torch.empty(w.B, dtype=torch.float32, device=dev)
-    stats = tb.Stats.allocate(w.B, N, dev)
+    stats = tb.Stats.allocate(w.B, N, dev, corpus_stats=False)
 
     def step():
         tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out, stats=stats, workspace=ws)

@@ -92,9 +92,10 @@ typedef struct tb_stats {
 
 /* Where the GLOBAL path keeps its intermediates inside the workspace (byte offsets).  Slot
  * numbering of the per-order key / inverse-index arrays: sentence group g owns slots
- * [g*group_cap, (g+1)*group_cap); the candidate's n-gram starting at token p is slot
- * g*group_cap + p, reference j's is g*group_cap + cand_stride + j*ref_stride + p.  A slot is
- * written only when its window lies inside the row's length. */
+ * [g*group_cap, (g+1)*group_cap) and fills them compactly from the front with its valid n-grams
+ * of that order: the candidate's (in position order), then reference 0's, reference 1's, ...
+ * Sequence s of the group therefore starts at g*group_cap + sum over earlier sequences of
+ * max(len - n + 1, 0).  Slots past the group's last n-gram are never written. */
 typedef struct tb_layout {
   int32_t path;            /* path AUTO resolves to for this shape (TB_PATH_FUSED / TB_PATH_GLOBAL) */
   int32_t bits;            /* ceil(log2(vocab_size)), at least 1 */

@@ -122,27 +122,29 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
 
 @dataclass
 class Stats:
-    """Device tensors behind a tb_stats_t (allocated by `Stats.allocate`)."""
-    clipped: torch.Tensor
-    total: torch.Tensor
-    closest_ref_len: torch.Tensor
-    group_distinct: torch.Tensor
-    corpus_stats: torch.Tensor
-    device_status: torch.Tensor
+    """Device tensors behind a tb_stats_t (allocated by `Stats.allocate`); None = not wanted."""
+    clipped: Optional[torch.Tensor] = None
+    total: Optional[torch.Tensor] = None
+    closest_ref_len: Optional[torch.Tensor] = None
+    group_distinct: Optional[torch.Tensor] = None
+    corpus_stats: Optional[torch.Tensor] = None
+    device_status: Optional[torch.Tensor] = None
 
     @staticmethod
-    def allocate(B: int, N: int, device) -> "Stats":
+    def allocate(B: int, N: int, device, corpus_stats: bool = True) -> "Stats":
         z = lambda *s, dt=torch.int32: torch.zeros(*s, dtype=dt, device=device)
-        return Stats(z(B, N), z(B, N), z(B), z(B, N), z(2 * N + 2, dt=torch.int64), z(1))
+        return Stats(z(B, N), z(B, N), z(B), z(B, N),
+                     z(2 * N + 2, dt=torch.int64) if corpus_stats else None, z(1))
 
     def as_struct(self) -> tb_stats_t:
+        ptr = lambda t: t.data_ptr() if t is not None else None
         s = tb_stats_t()
-        s.clipped = self.clipped.data_ptr()
-        s.total = self.total.data_ptr()
-        s.closest_ref_len = self.closest_ref_len.data_ptr()
-        s.group_distinct = self.group_distinct.data_ptr()
-        s.corpus_stats = self.corpus_stats.data_ptr()
-        s.device_status = self.device_status.data_ptr()
+        s.clipped = ptr(self.clipped)
+        s.total = ptr(self.total)
+        s.closest_ref_len = ptr(self.closest_ref_len)
+        s.group_distinct = ptr(self.group_distinct)
+        s.corpus_stats = ptr(self.corpus_stats)
+        s.device_status = ptr(self.device_status)
         return s
 
 

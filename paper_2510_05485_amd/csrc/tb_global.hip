@@ -3,7 +3,7 @@
 // Mapping to the paper (Sections 3.1-3.3):
 //   pack_kernel        n-gram extraction and the flattened list of valid n-grams, stored as
 //                      packed integer keys instead of (total_ngrams, n) token rows;
-//   dictionary_kernel  the compact dictionary + inverse indices (the role of torch.unique with
+//   dictionary_*       the compact dictionary + inverse indices (the role of torch.unique with
 //                      return_inverse), built per sentence group in an LDS hash table;
 //   count_clip_kernel  offset ids -> counts (the batched bincount), maximum over references,
 //                      minimum with the candidate counts, summed per sentence and order.
@@ -11,9 +11,50 @@
 // its references) gets its own dictionary; the group's offset g*group_cap keeps id ranges
 // disjoint exactly like the paper's i*num_unique offset, with an a-priori bound in place of the
 // data-dependent num_unique so that no size ever travels back to the host.
+//
+// Key / id arrays are group-compact: group g owns slots [g*group_cap, (g+1)*group_cap) and its
+// valid n-grams of one order are stored back to back (candidate first, then each reference), so
+// the dictionary and count kernels read one contiguous range per workgroup.
 #include "tb_kernels.h"
 
 namespace tb {
+
+// Clamped length of sequence j of group g (j = 0: candidate, j >= 1: reference j-1).
+__device__ __forceinline__ int seq_len(const Problem& pb, int g, int j) {
+  return j == 0 ? clamped_len(pb.cand_len[g], pb.cand_stride, nullptr)
+                : clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
+}
+
+// Where each sequence of group g starts inside the group's compact slot range for order n.
+// With at most 64 sequences per group every wavefront loads all lengths with one vector load
+// (lane j takes sequence j) and prefix-sums the n-gram counts with cross-lane shuffles, so no
+// chain of dependent scalar loads sits in front of the kernel's real work.  Larger groups fall
+// back to a loop.  Must be constructed and queried in wave-uniform control flow.
+class GroupIndex {
+ public:
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g, int n)
+      : pb_(pb), g_(g), n_(n), fast_(pb.R < kWave), incl_(0) {
+    if (fast_) {
+      const int lane = threadIdx.x & (kWave - 1);
+      const int cnt = (lane <= pb.R) ? max(seq_len(pb, g, lane) - n + 1, 0) : 0;
+      incl_ = wave_inclusive_scan(cnt);
+    }
+  }
+  // First slot of sequence j (0 = candidate); j = R + 1 gives the group's n-gram count.
+  __device__ __forceinline__ int start(int j) const {
+    if (j == 0) return 0;
+    if (fast_) return __shfl(incl_, j - 1, kWave);
+    int s = 0;
+    for (int jj = 0; jj < j; ++jj) s += max(seq_len(pb_, g_, jj) - n_ + 1, 0);
+    return s;
+  }
+
+ private:
+  const Problem& pb_;
+  int g_, n_;
+  bool fast_;
+  int incl_;
+};
 
 // ---------------------------------------------------------------------------------- pack
 
@@ -45,22 +86,25 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
   const int g = blockIdx.x / per_group;
   int rem = blockIdx.x % per_group;
   const int32_t* row;
-  int len, chunk;
-  int64_t slot_base = int64_t(g) * pb.group_cap;
+  int len, chunk, j;
   if (rem < a.cand_chunks) {
+    j = 0;
     chunk = rem;
     row = pb.cand + int64_t(g) * pb.cand_stride;
     len = clamped_len(pb.cand_len[g], pb.cand_stride, pb.status);
   } else {
     rem -= a.cand_chunks;
-    const int j = rem / a.ref_chunks;
+    j = 1 + rem / a.ref_chunks;
     chunk = rem % a.ref_chunks;
-    row = pb.refs + (int64_t(g) * pb.R + j) * pb.ref_stride;
-    len = clamped_len(pb.ref_len[int64_t(g) * pb.R + j], pb.ref_stride, pb.status);
-    slot_base += pb.cand_stride + int64_t(j) * pb.ref_stride;
+    row = pb.refs + (int64_t(g) * pb.R + j - 1) * pb.ref_stride;
+    len = clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, pb.status);
   }
   const int p0 = chunk * kPackTile;
   if (p0 >= len) return;  // uniform over the workgroup
+  // where this sequence's n-grams start inside the group's compact range, per order
+  int base[4];
+#pragma unroll
+  for (int n = 1; n <= 4; ++n) base[n - 1] = GroupIndex(pb, g, n).start(j);
   const int ntok = min(kPackTile + 3, len - p0);
   bool bad = false;
   for (int i = threadIdx.x; i < ntok; i += kPackThreads) {
@@ -71,20 +115,20 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
   if (bad && pb.status) atomicOr(pb.status, TB_DEV_TOKEN_RANGE);
   __syncthreads();
   const int bits = pb.bits;
+  const int64_t gslot = int64_t(g) * pb.group_cap + p0;
 #pragma unroll
   for (int k = 0; k < kPackTile / kPackThreads; ++k) {
     const int q = threadIdx.x + k * kPackThreads;
     if (q >= ntok) break;
-    const int avail = ntok - q;  // tokens available from this start, capped at tile + 3
-    const int64_t slot = slot_base + p0 + q;
+    const int avail = ntok - q;  // tokens from this start that lie inside the row (capped)
     uint64_t lo = uint32_t(tok[q]), hi = 0;
-    store_key(a.ws.keys[0], a.ws.wide[0], slot, lo, hi);
+    store_key(a.ws.keys[0], a.ws.wide[0], gslot + base[0] + q, lo, hi);
 #pragma unroll
     for (int n = 2; n <= 4; ++n) {
       if (n > pb.N || n > avail) break;
       hi = (hi << bits) | (lo >> (64 - bits));
       lo = (lo << bits) | uint32_t(tok[q + n - 1]);
-      store_key(a.ws.keys[n - 1], a.ws.wide[n - 1], slot, lo, hi);
+      store_key(a.ws.keys[n - 1], a.ws.wide[n - 1], gslot + base[n - 1] + q, lo, hi);
     }
   }
 }
@@ -103,116 +147,235 @@ hipError_t launch_pack(const Problem& pb, const GlobalWs& ws, hipStream_t s) {
 
 // ---------------------------------------------------------------------------- dictionary
 
+constexpr uint64_t kEmpty64 = ~uint64_t(0);
+
 struct DictArgs {
   Problem pb;
   GlobalWs ws;
   int32_t* distinct;
   int table_slots;
-  uint32_t lds_table_off, lds_slot_off;
+  uint32_t lds_table_off;
+  int orders[4];
+  int num_orders;
 };
 
 bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan) {
-  if (group_cap < 1 || group_cap > 65535) return false;  // positions are 16-bit in table words
-  int kb = 8;
-  for (int n = 0; n < N; ++n) kb = key_bytes[n] > kb ? key_bytes[n] : kb;
-  plan->key_bytes = kb;
-  plan->threads = group_cap > 2048 ? 1024 : (group_cap > 768 ? 512 : 256);
-  int slots = 1;
-  while (slots < 2 * group_cap) slots <<= 1;
-  if (slots < plan->threads) slots = plan->threads;
-  plan->table_slots = slots;
-  size_t off = size_t(group_cap) * kb;
-  off = (off + 15) & ~size_t(15);
-  plan->lds_table_off = off;
-  off += size_t(slots) * 4;
-  plan->lds_slot_off = off;
-  off += ((size_t(group_cap) * 2 + 15) & ~size_t(15));
-  plan->lds_bytes = off;
-  return off + 256 <= size_t(kLdsBudget);  // 256 B head-room for the static scan scratch
+  if (group_cap < 1 || group_cap > 12 * 1024) return false;
+  int t = 256;
+  while (t < 1024 && group_cap > 4 * t) t *= 2;
+  plan->threads = t;
+  const int need = int((group_cap + t - 1) / t);
+  plan->items = need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : 12;
+  plan->n_narrow = plan->n_wide = 0;
+  for (int n = 1; n <= N; ++n) {
+    if (key_bytes[n - 1] == 16)
+      plan->wide_orders[plan->n_wide++] = n;
+    else
+      plan->narrow_orders[plan->n_narrow++] = n;
+  }
+  int slots = 256;
+  while (int64_t(slots) * 3 < group_cap * 4) slots <<= 1;
+  plan->narrow_slots = plan->wide_slots = slots;
+  plan->narrow_lds = size_t(slots + 1) * 8;
+  plan->wide_table_off = size_t(group_cap) * 16;
+  plan->wide_lds = plan->wide_table_off + size_t(slots) * 4;
+  bool ok = true;
+  if (plan->n_narrow) ok = ok && plan->narrow_lds + 256 <= size_t(kLdsBudget);
+  if (plan->n_wide) ok = ok && plan->wide_lds + 256 <= size_t(kLdsBudget) && group_cap <= 65535;
+  return ok;
 }
 
-// One workgroup builds the dictionary of one (group, order): stage the group's keys in LDS,
-// insert every occurrence into an open-addressing table whose words are fingerprint:position,
-// number the occupied slots densely, and write each occurrence's offset id.
-template <typename KeyT>
-__device__ __forceinline__ void dictionary_block(const DictArgs& a, int g, int n,
-                                                 unsigned char* smem, int* scan_scratch) {
-  const Problem& pb = a.pb;
+// Number the occupied table entries densely (any bijection onto 0..U-1 is a valid dictionary)
+// and leave each entry's id in the table.  Thread t owns entries t, t+nt, ... so that the LDS
+// accesses are bank-conflict free.  Returns U in every thread.
+template <typename WordT>
+__device__ __forceinline__ int number_entries(WordT* table, int entries, WordT empty,
+                                              int* scan_scratch) {
   const int nt = blockDim.x, tid = threadIdx.x;
-  KeyT* skeys = reinterpret_cast<KeyT*>(smem);
-  uint32_t* table = reinterpret_cast<uint32_t*>(smem + a.lds_table_off);
-  uint16_t* slot_of = reinterpret_cast<uint16_t*>(smem + a.lds_slot_off);
-  const uint32_t mask = uint32_t(a.table_slots) - 1u;
-  const KeyT* gkeys = reinterpret_cast<const KeyT*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
-  uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
-
-  for (int i = tid; i < a.table_slots; i += nt) table[i] = kEmpty;
-
-  // stage keys, compacted over the group's sequences (candidate first, then references)
-  int count = 0;
-  for (int j = 0; j <= pb.R; ++j) {
-    const int len = (j == 0)
-        ? clamped_len(pb.cand_len[g], pb.cand_stride, nullptr)
-        : clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
-    const int cnt = max(len - n + 1, 0);
-    const int64_t off = (j == 0) ? 0 : pb.cand_stride + int64_t(j - 1) * pb.ref_stride;
-    for (int p = tid; p < cnt; p += nt) skeys[count + p] = gkeys[off + p];
-    count += cnt;
-  }
-  __syncthreads();
-
-  for (int k = tid; k < count; k += nt) {
-    const KeyT key = skeys[k];
-    const uint32_t h = key_hash(key);
-    const uint32_t fp = h >> 16;
-    const uint32_t mine = (fp << 16) | uint32_t(k);
-    uint32_t slot = h & mask;
-    while (true) {
-      uint32_t w = table[slot];
-      if (w == kEmpty) {
-        w = atomicCAS(&table[slot], kEmpty, mine);
-        if (w == kEmpty) break;  // this occurrence now represents its n-gram
-      }
-      if ((w >> 16) == fp && key_eq(skeys[w & 0xFFFFu], key)) break;
-      slot = (slot + 1) & mask;
-    }
-    slot_of[k] = uint16_t(slot);
-  }
-  __syncthreads();
-
-  // dense ids: thread t numbers slots t, t+nt, ... (bank-conflict free); any bijection will do
   int occupied = 0;
-  for (int sidx = tid; sidx < a.table_slots; sidx += nt) occupied += (table[sidx] != kEmpty);
+  for (int s = tid; s < entries; s += nt) occupied += (table[s] != empty);
   int U = 0;
   int id = block_exclusive_scan(occupied, scan_scratch, &U);
-  for (int sidx = tid; sidx < a.table_slots; sidx += nt)
-    if (table[sidx] != kEmpty) table[sidx] = uint32_t(id++);
+  for (int s = tid; s < entries; s += nt)
+    if (table[s] != empty) table[s] = WordT(id++);
+  __syncthreads();
+  return U;
+}
+
+// 8-byte keys.  The open-addressing table holds the keys themselves; an insertion is one 64-bit
+// LDS compare-and-swap per probe (double hashing).  All-ones is the empty marker, so the one
+// key with that bit pattern owns the extra entry at index `table_slots`.
+template <int ITEMS>
+__global__ __launch_bounds__(1024) void dictionary_narrow_kernel(DictArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int scan_scratch[17];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int g = blockIdx.x / a.num_orders;
+  const int n = a.orders[blockIdx.x % a.num_orders];
+  unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
+  const int T = a.table_slots;
+  const uint32_t mask = uint32_t(T) - 1u;
+  const int count = min(GroupIndex(pb, g, n).start(pb.R + 1), ITEMS * nt);
+  const uint64_t* gkeys =
+      reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+  uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
+
+  uint64_t key[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    key[i] = (k < count) ? gkeys[k] : 0;
+  }
+  for (int s = tid; s <= T; s += nt) table[s] = kEmpty64;
   __syncthreads();
 
+  uint32_t slot[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    slot[i] = 0;
+    if (k < count) {
+      if (key[i] == kEmpty64) {
+        table[T] = 0;
+        slot[i] = uint32_t(T);
+      } else {
+        const uint32_t h = key_hash(key[i]);
+        const uint32_t step = (h >> 16) | 1u;
+        uint32_t s = h & mask;
+        while (true) {
+          const unsigned long long old = atomicCAS(&table[s], kEmpty64, key[i]);
+          if (old == kEmpty64 || old == key[i]) break;
+          s = (s + step) & mask;
+        }
+        slot[i] = s;
+      }
+    }
+  }
+  __syncthreads();
+
+  const int U = number_entries<unsigned long long>(table, T + 1, kEmpty64, scan_scratch);
   const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
-  count = 0;
-  for (int j = 0; j <= pb.R; ++j) {
-    const int len = (j == 0)
-        ? clamped_len(pb.cand_len[g], pb.cand_stride, nullptr)
-        : clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
-    const int cnt = max(len - n + 1, 0);
-    const int64_t off = (j == 0) ? 0 : pb.cand_stride + int64_t(j - 1) * pb.ref_stride;
-    for (int p = tid; p < cnt; p += nt) ginv[off + p] = gbase + table[slot_of[count + p]];
-    count += cnt;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    if (k < count) ginv[k] = gbase + uint32_t(table[slot[i]]);
   }
   if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = U;
 }
 
-__global__ __launch_bounds__(1024) void dictionary_kernel(DictArgs a) {
+// 16-byte keys (n*bits > 64): no 128-bit LDS atomic exists, so the keys are staged in LDS and the
+// table holds fingerprint:position words claimed with a 32-bit compare-and-swap; a fingerprint
+// match is confirmed by comparing the full keys.
+template <int ITEMS>
+__global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int scan_scratch[17];
-  const int g = blockIdx.x / a.pb.N;
-  const int n = blockIdx.x % a.pb.N + 1;
-  if (a.ws.wide[n - 1])
-    dictionary_block<Key128>(a, g, n, smem, scan_scratch);
-  else
-    dictionary_block<uint64_t>(a, g, n, smem, scan_scratch);
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int g = blockIdx.x / a.num_orders;
+  const int n = a.orders[blockIdx.x % a.num_orders];
+  Key128* skeys = reinterpret_cast<Key128*>(smem);
+  uint32_t* table = reinterpret_cast<uint32_t*>(smem + a.lds_table_off);
+  const int T = a.table_slots;
+  const uint32_t mask = uint32_t(T) - 1u;
+  const int count =
+      min(min(GroupIndex(pb, g, n).start(pb.R + 1), ITEMS * nt), int(pb.group_cap));
+  const Key128* gkeys =
+      reinterpret_cast<const Key128*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+  uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
+
+  Key128 key[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    if (k < count) {
+      key[i] = gkeys[k];
+    } else {
+      key[i].lo = 0;
+      key[i].hi = 0;
+    }
+  }
+  for (int s = tid; s < T; s += nt) table[s] = kEmpty;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    if (k < count) skeys[k] = key[i];
+  }
+  __syncthreads();
+
+  uint32_t slot[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    slot[i] = 0;
+    if (k < count) {
+      const uint32_t h = key_hash(key[i]);
+      const uint32_t fp = h >> 16;
+      const uint32_t step = (h >> 8) | 1u;
+      const uint32_t mine = (fp << 16) | uint32_t(k);
+      uint32_t s = h & mask;
+      while (true) {
+        uint32_t w = table[s];
+        if (w == kEmpty) {
+          w = atomicCAS(&table[s], kEmpty, mine);
+          if (w == kEmpty) break;  // this occurrence now represents its n-gram
+        }
+        if ((w >> 16) == fp && key_eq(skeys[w & 0xFFFFu], key[i])) break;
+        s = (s + step) & mask;
+      }
+      slot[i] = s;
+    }
+  }
+  __syncthreads();
+
+  const int U = number_entries<uint32_t>(table, T, kEmpty, scan_scratch);
+  const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    if (k < count) ginv[k] = gbase + table[slot[i]];
+  }
+  if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = U;
 }
+
+template <template <int> class Launcher, typename... Args>
+hipError_t dispatch_items(int items, Args&&... args) {
+  switch (items) {
+    case 2: return Launcher<2>::run(args...);
+    case 4: return Launcher<4>::run(args...);
+    case 6: return Launcher<6>::run(args...);
+    case 8: return Launcher<8>::run(args...);
+    case 12: return Launcher<12>::run(args...);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <typename Kernel, typename ArgT>
+hipError_t launch_with_lds(Kernel kernel, const ArgT& a, int64_t blocks, int threads, size_t lds,
+                           hipStream_t s) {
+  if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kernel, dim3(uint32_t(blocks)), dim3(threads), lds, s, a);
+  return hipGetLastError();
+}
+
+template <int ITEMS>
+struct NarrowLauncher {
+  static hipError_t run(const DictArgs& a, int64_t blocks, int threads, size_t lds,
+                        hipStream_t s) {
+    return launch_with_lds(dictionary_narrow_kernel<ITEMS>, a, blocks, threads, lds, s);
+  }
+};
+template <int ITEMS>
+struct WideLauncher {
+  static hipError_t run(const DictArgs& a, int64_t blocks, int threads, size_t lds,
+                        hipStream_t s) {
+    return launch_with_lds(dictionary_wide_kernel<ITEMS>, a, blocks, threads, lds, s);
+  }
+};
 
 hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPlan& plan,
                              int32_t* distinct, hipStream_t s) {
@@ -220,18 +383,25 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
   a.pb = pb;
   a.ws = ws;
   a.distinct = distinct;
-  a.table_slots = plan.table_slots;
-  a.lds_table_off = uint32_t(plan.lds_table_off);
-  a.lds_slot_off = uint32_t(plan.lds_slot_off);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dictionary_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     int(plan.lds_bytes));
-  if (e != hipSuccess) return e;
-  const int64_t blocks = int64_t(pb.B) * pb.N;
-  if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(dictionary_kernel, dim3(uint32_t(blocks)), dim3(plan.threads),
-                     plan.lds_bytes, s, a);
-  return hipGetLastError();
+  if (plan.n_narrow) {
+    a.table_slots = plan.narrow_slots;
+    a.lds_table_off = 0;
+    a.num_orders = plan.n_narrow;
+    for (int k = 0; k < 4; ++k) a.orders[k] = plan.narrow_orders[k];
+    hipError_t e = dispatch_items<NarrowLauncher>(plan.items, a, int64_t(pb.B) * plan.n_narrow,
+                                                  plan.threads, plan.narrow_lds, s);
+    if (e != hipSuccess) return e;
+  }
+  if (plan.n_wide) {
+    a.table_slots = plan.wide_slots;
+    a.lds_table_off = uint32_t(plan.wide_table_off);
+    a.num_orders = plan.n_wide;
+    for (int k = 0; k < 4; ++k) a.orders[k] = plan.wide_orders[k];
+    hipError_t e = dispatch_items<WideLauncher>(plan.items, a, int64_t(pb.B) * plan.n_wide,
+                                                plan.threads, plan.wide_lds, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------- count + clip
@@ -243,16 +413,24 @@ struct CountArgs {
 };
 
 bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, CountPlan* plan) {
-  // reference counters are 16-bit fields (current | maximum) of one LDS word
-  if (group_cap < 1 || ref_stride > 65535 || cand_stride > 0x7FFFFFFF) return false;
-  plan->threads = group_cap > 2048 ? 1024 : (group_cap > 768 ? 512 : 256);
+  // every counter is a 16-bit field of an LDS word
+  if (group_cap < 1 || group_cap > 12 * 1024 || ref_stride > 65535 || cand_stride > 65535)
+    return false;
+  int t = 256;
+  while (t < 1024 && group_cap > 4 * t) t *= 2;
+  plan->threads = t;
+  const int need = int((group_cap + t - 1) / t);
+  plan->items = need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : 12;
   plan->lds_bytes = size_t(group_cap) * 8;
   return plan->lds_bytes + 256 <= size_t(kLdsBudget);
 }
 
-// One workgroup per (group, order): histogram the candidate's ids and, reference by reference,
-// the reference's ids over the group's dictionary range with LDS atomics; fold each reference
-// into a running maximum; sum min(candidate, maximum).
+// One workgroup per (group, order).  All of the group's offset ids are fetched into registers in
+// one round trip; LDS holds two words per dictionary entry:
+//   acc[u] = candidate count (low 16 bits) | maximum reference count so far (high 16 bits)
+//   cur[u] = counts of the two references being histogrammed (16 bits each)
+// References are histogrammed two at a time with LDS atomic adds and folded into the maximum.
+template <int ITEMS>
 __global__ __launch_bounds__(1024) void count_clip_kernel(CountArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int red_scratch[17];
@@ -261,47 +439,60 @@ __global__ __launch_bounds__(1024) void count_clip_kernel(CountArgs a) {
   const int g = blockIdx.x / pb.N;
   const int n = blockIdx.x % pb.N + 1;
   const int cap = int(pb.group_cap);
-  uint32_t* cand_cnt = reinterpret_cast<uint32_t*>(smem);
-  uint32_t* ref_cnt = cand_cnt + cap;  // low 16 bits: current reference, high 16: maximum so far
+  uint32_t* acc = reinterpret_cast<uint32_t*>(smem);
+  uint32_t* cur = acc + cap;
   const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
   const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
   const int U = min(max(a.st.distinct[int64_t(g) * pb.N + n - 1], 0), cap);
+  const GroupIndex gi(pb, g, n);
+  const int count = min(gi.start(pb.R + 1), ITEMS * nt);
 
+  uint32_t id[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    id[i] = (k < count) ? ginv[k] - gbase : 0xFFFFFFFFu;
+  }
   for (int u = tid; u < U; u += nt) {
-    cand_cnt[u] = 0;
-    ref_cnt[u] = 0;
+    acc[u] = 0;
+    cur[u] = 0;
   }
   __syncthreads();
 
-  const int c = clamped_len(pb.cand_len[g], pb.cand_stride, nullptr);
-  const int ccnt = max(c - n + 1, 0);
-  for (int p = tid; p < ccnt; p += nt) {
-    const uint32_t id = ginv[p] - gbase;
-    if (id < uint32_t(U)) atomicAdd(&cand_cnt[id], 1u);
+  const int ccnt = gi.start(1);
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int k = tid + i * nt;
+    if (k < ccnt && id[i] < uint32_t(U)) atomicAdd(&acc[id[i]], 1u);
   }
-  for (int j = 0; j < pb.R; ++j) {
-    const int len = clamped_len(pb.ref_len[int64_t(g) * pb.R + j], pb.ref_stride, nullptr);
-    const int rcnt = max(len - n + 1, 0);
-    const uint32_t* rinv = ginv + pb.cand_stride + int64_t(j) * pb.ref_stride;
-    for (int p = tid; p < rcnt; p += nt) {
-      const uint32_t id = rinv[p] - gbase;
-      if (id < uint32_t(U)) atomicAdd(&ref_cnt[id], 1u);
+  int lo = ccnt;  // first slot of the reference pair being processed
+  for (int j = 0; j < pb.R; j += 2) {
+    const int mid = gi.start(j + 2);
+    const int hi = (j + 1 < pb.R) ? gi.start(j + 3) : mid;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int k = tid + i * nt;
+      if (k >= lo && k < hi && id[i] < uint32_t(U))
+        atomicAdd(&cur[id[i]], (k < mid) ? 1u : 0x10000u);
     }
+    lo = hi;
     __syncthreads();
-    if (j + 1 < pb.R) {
+    if (j + 2 < pb.R) {
       for (int u = tid; u < U; u += nt) {
-        const uint32_t w = ref_cnt[u];
-        const uint32_t cur = w & 0xFFFFu, mx = w >> 16;
-        ref_cnt[u] = max(cur, mx) << 16;
+        const uint32_t w = cur[u];
+        const uint32_t m = max(w & 0xFFFFu, w >> 16);
+        const uint32_t x = acc[u];
+        acc[u] = (x & 0xFFFFu) | (max(x >> 16, m) << 16);
+        cur[u] = 0;
       }
       __syncthreads();
     }
   }
   int part = 0;
   for (int u = tid; u < U; u += nt) {
-    const uint32_t w = ref_cnt[u];
-    const uint32_t mx = max(w & 0xFFFFu, w >> 16);
-    part += int(min(cand_cnt[u], mx));
+    const uint32_t w = cur[u], x = acc[u];
+    const uint32_t m = max(max(w & 0xFFFFu, w >> 16), x >> 16);
+    part += int(min(x & 0xFFFFu, m));
   }
   const int clipped = block_sum(part, red_scratch);
   if (tid == 0) {
@@ -310,21 +501,22 @@ __global__ __launch_bounds__(1024) void count_clip_kernel(CountArgs a) {
   }
 }
 
+template <int ITEMS>
+struct CountLauncher {
+  static hipError_t run(const CountArgs& a, int64_t blocks, int threads, size_t lds,
+                        hipStream_t s) {
+    return launch_with_lds(count_clip_kernel<ITEMS>, a, blocks, threads, lds, s);
+  }
+};
+
 hipError_t launch_count_clip(const Problem& pb, const GlobalWs& ws, const CountPlan& plan,
                              const StatPtrs& st, hipStream_t s) {
   CountArgs a;
   a.pb = pb;
   a.ws = ws;
   a.st = st;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(count_clip_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     int(plan.lds_bytes));
-  if (e != hipSuccess) return e;
-  const int64_t blocks = int64_t(pb.B) * pb.N;
-  if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(count_clip_kernel, dim3(uint32_t(blocks)), dim3(plan.threads),
-                     plan.lds_bytes, s, a);
-  return hipGetLastError();
+  return dispatch_items<CountLauncher>(plan.items, a, int64_t(pb.B) * pb.N, plan.threads,
+                                       plan.lds_bytes, s);
 }
 
 }  // namespace tb

@@ -21,15 +21,22 @@ struct StatPtrs {
   int64_t* corpus;    // [2N+2]
 };
 
+// Launch shape shared by the dictionary and count/clip kernels: every thread keeps up to
+// `items` of its group's n-grams in registers (threads * items >= group_cap).
 struct DictPlan {
-  int threads;        // workgroup size
-  int table_slots;    // power of two, >= 2 * group_cap and >= threads
-  int key_bytes;      // widest key among the orders (8 or 16)
-  size_t lds_bytes;   // dynamic LDS of the dictionary kernel
-  size_t lds_table_off, lds_slot_off;
+  int threads;          // workgroup size (256, 512 or 1024)
+  int items;            // register-resident n-grams per thread: 2, 4, 6, 8 or 12
+  int narrow_orders[4]; // orders with 8-byte keys, and how many
+  int n_narrow;
+  int narrow_slots;     // hash-table slots (power of two, >= 4/3 group_cap), 8-byte entries
+  size_t narrow_lds;
+  int wide_orders[4];   // orders with 16-byte keys
+  int n_wide;
+  int wide_slots;       // 4-byte fingerprint:position entries
+  size_t wide_lds, wide_table_off;
 };
 struct CountPlan {
-  int threads;
+  int threads, items;
   size_t lds_bytes;
 };
 struct FusedPlan {

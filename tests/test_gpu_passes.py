@@ -59,22 +59,22 @@ def expected_key(tokens, bits):
 def test_pack_dictionary_count_passes(seed, B, R, V, L):
     w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=L // 2)
     lay, wsb, stats, out = stage_all(w)
-    cap, cs, rs = lay.group_cap, w.cand.shape[1], w.refs.shape[2]
+    cap = lay.group_cap
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
     for n in range(1, 5):
         keys = read_keys(wsb, lay, n, B * cap)
         inv = wsb[lay.inv_off[n - 1]: lay.inv_off[n - 1] + B * cap * 4].view(np.uint32)
         for g in range(B):
-            rows = [(0, w.cand[g], w.cand_len[g])] + [
-                (cs + j * rs, w.refs[g, j], w.ref_len[g, j]) for j in range(R)]
-            seen = {}
-            for off, row, ln in rows:
+            rows = [(w.cand[g], w.cand_len[g])] + [
+                (w.refs[g, j], w.ref_len[g, j]) for j in range(R)]
+            seen, slot = {}, g * cap          # group-compact: sequences stored back to back
+            for row, ln in rows:
                 for p in range(max(ln - n + 1, 0)):
-                    slot = g * cap + off + p
                     gram = tuple(int(t) for t in row[p:p + n])
-                    assert keys[slot] == expected_key(gram, lay.bits), (n, g, off, p)
+                    assert keys[slot] == expected_key(gram, lay.bits), (n, g, p)
                     local = int(inv[slot]) - g * cap
                     assert seen.setdefault(gram, local) == local      # equal n-gram -> equal id
+                    slot += 1
             ids = sorted(seen.values())
             assert ids == list(range(len(ids)))                        # dense and injective
             assert len(ids) == ref.group_distinct[g, n - 1]
