@@ -39,7 +39,8 @@ def needs_build() -> bool:
 
 def build(verbose: bool = True) -> str:
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [HIPCC, *FLAGS, "-I", INCLUDE, "-I", CSRC, "-o", tmp, *sources()]
+    extra = os.environ.get("TB_HIPCC_EXTRA", "").split()   # e.g. -DTB_PHASE_CLOCKS for profiling
+    cmd = [HIPCC, *FLAGS, *extra, "-I", INCLUDE, "-I", CSRC, "-o", tmp, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

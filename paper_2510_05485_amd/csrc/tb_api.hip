@@ -49,7 +49,7 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
   L.global_ok = ids_fit && plan_dictionary(L.group_cap, L.key_bytes, N, &p->dict) &&
                 plan_count(L.group_cap, cand_stride, ref_stride, &p->count);
-  L.fused_ok = plan_fused(cand_stride, ref_stride, R, &p->fused);
+  L.fused_ok = plan_fused(cand_stride, ref_stride, R, N, L.bits, &p->fused);
   int path = cfg->force_path;
   if (path == TB_PATH_AUTO) path = L.fused_ok ? TB_PATH_FUSED : TB_PATH_GLOBAL;
   if (path == TB_PATH_FUSED && !L.fused_ok) return TB_ERR_UNSUPPORTED;

@@ -39,20 +39,36 @@ __device__ __forceinline__ uint32_t key_hash(const Key128& k) {
   return fmix(key_hash(k.lo) ^ (key_hash(k.hi) * 0xC2B2AE3Du + 0x27D4EB2Fu));
 }
 
-// Inclusive scan / sum across the 64 lanes of a wavefront with cross-lane shuffles.
-__device__ __forceinline__ int wave_inclusive_scan(int v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    int o = __shfl_up(v, d, kWave);
-    if (lane >= d) v += o;
-  }
-  return v;
+// Cross-lane data movement inside the VALU (DPP): no LDS round trip, unlike ds_bpermute-based
+// shuffles.  Lanes whose source is masked off or out of range receive 0.
+template <int kCtrl, int kRowMask, int kBankMask>
+__device__ __forceinline__ int dpp_or_zero(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, kCtrl, kRowMask, kBankMask, false);
 }
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.  All 64 lanes must be active.
+// Row-local shifts build the scan inside each row of 16 lanes; two row broadcasts (lane 15 of a
+// row into the next row, lane 31 into the upper half) carry it across rows.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  int x = v;
+  x += dpp_or_zero<0x111, 0xf, 0xf>(v);  // row_shr:1
+  x += dpp_or_zero<0x112, 0xf, 0xf>(v);  // row_shr:2
+  x += dpp_or_zero<0x113, 0xf, 0xf>(v);  // row_shr:3
+  x += dpp_or_zero<0x114, 0xf, 0xe>(x);  // row_shr:4, lanes 4..15 of each row
+  x += dpp_or_zero<0x118, 0xf, 0xc>(x);  // row_shr:8, lanes 8..15 of each row
+  x += dpp_or_zero<0x142, 0xa, 0xf>(x);  // row_bcast:15 into rows 1 and 3
+  x += dpp_or_zero<0x143, 0xc, 0xf>(x);  // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
+// Sum over the wavefront, returned in every lane (wave-uniform).  All 64 lanes must be active.
 __device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_down(v, d, kWave);
-  return v;  // valid in lane 0
+  return __builtin_amdgcn_readlane(wave_inclusive_scan(v), kWave - 1);
+}
+
+// Value of `v` in lane `src` (wave-uniform index), as a scalar.
+__device__ __forceinline__ int lane_value(int v, int src) {
+  return __builtin_amdgcn_readlane(v, src);
 }
 
 // Exclusive scan of one int per thread over the workgroup (up to 1024 threads); also returns

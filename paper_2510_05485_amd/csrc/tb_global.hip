@@ -43,7 +43,7 @@ class GroupIndex {
   // First slot of sequence j (0 = candidate); j = R + 1 gives the group's n-gram count.
   __device__ __forceinline__ int start(int j) const {
     if (j == 0) return 0;
-    if (fast_) return __shfl(incl_, j - 1, kWave);
+    if (fast_) return lane_value(incl_, j - 1);
     int s = 0;
     for (int jj = 0; jj < j; ++jj) s += max(seq_len(pb_, g_, jj) - n_ + 1, 0);
     return s;

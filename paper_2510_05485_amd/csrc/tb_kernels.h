@@ -40,16 +40,17 @@ struct CountPlan {
   size_t lds_bytes;
 };
 struct FusedPlan {
-  int threads;
-  int table_slots;     // power of two >= 2 * cand_stride
-  int ref_batch;       // references counted per sweep (2 per 32-bit counter word)
-  size_t lds_bytes;
-  size_t off_table, off_cand_cnt, off_ref_cnt;
+  int threads, items;  // workgroup size; token positions kept per thread
+  int table_slots;     // power of two >= 4/3 * cand_stride
+  int words;           // 32-bit counter words per slot (two 16-bit sequence fields each)
+  int key_bytes;       // 4 when log2(table_slots) + bits <= 31, else 8
+  size_t lds_bytes, off_cnt, off_tok;
 };
 
 bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan);
 bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, CountPlan* plan);
-bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, FusedPlan* plan);
+bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
+                FusedPlan* plan);
 
 hipError_t launch_pack(const Problem& pb, const GlobalWs& ws, hipStream_t s);
 hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPlan& plan,
