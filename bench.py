@@ -4,7 +4,7 @@
 A "step" is one pass of the whole hot path (n-gram extraction .. geometric mean) over one
 synthetic batch already resident in HBM.  The default workload is the headline configuration
 (B=512 candidates of 1024 tokens, 4 references each, vocabulary 50257).  One JSON line is
-printed; see the README section of the design doc for the meaning of every field.
+printed; the design doc (measurement contract) gives the meaning of every field.
 """
 from __future__ import annotations
 
@@ -70,6 +70,17 @@ def cpu_baseline(w, run, budget_s=12.0):
                       f"{threads} std::threads over sentences"}
 
 
+# HBM traffic per launch (fetch + write bytes) of the dominant kernel, from the rocprofv3 --pmc
+# runs summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters'
+# reading for a plain copy of known size).  Keyed by (workload name, kernel); None = not measured.
+MEASURED_TRAFFIC = {
+    ("cfg3_B512_L1024_R4", "fused"): 11.30e6,
+    ("cfg3_B512_L1024_R4", "pack"): 94.86e6,
+    ("cfg3_B512_L1024_R4", "dictionary"): 125.75e6,
+    ("cfg3_B512_L1024_R4", "count_clip"): 42.33e6,
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +89,11 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "global"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-global-passes", action="store_true",
+                    help="skip the per-pass timing of the GLOBAL path")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="launch one plain device copy of this many MiB first (a known-size "
+                         "reference for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc")
     a = ap.parse_args()
@@ -98,6 +114,13 @@ def main():
         sys.exit(3)
     tb.load_library()
     dev = "cuda:0"
+    if a.calib_copy_mib:
+        src = torch.ones(a.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     w = syn.make(a.config)
     run = [r for r in w.runs if not r.corpus][-1]
     N = w.max_n
@@ -130,44 +153,69 @@ def main():
     ev_ms = time_region(step, a.steps, torch)
     ms = max(wall_ms, ev_ms)    # enqueue-bound runs show up in wall time, GPU-bound in events
 
+    def time_stages(stages, alg):
+        rows = []
+        for name, fn in stages:
+            for _ in range(3):
+                fn()
+            t_ms = time_region(fn, a.steps, torch)
+            gbps = alg[name] / (t_ms * 1e-3) / 1e9
+            rows.append({"kernel": name, "us": round(t_ms * 1e3, 2),
+                         "alg_bytes": int(alg[name]), "GBps": round(gbps, 1),
+                         "frac_hbm": round(gbps / HBM_PEAK_GBPS, 4)})
+        return rows
+
     # per-kernel durations, each kernel on its own between HIP events
-    alg = algorithmic_bytes(w, lay, N)
-    passes = []
-    if path == "global":
+    glay = tb.tensorbleu_workspace_layout(w.B, w.R, cs, rs, config("global")) \
+        if lay.global_ok else None
+    alg = algorithmic_bytes(w, glay or lay, N)
+    global_section = None
+    if glay is not None and not (a.no_global_passes and path != "global"):
         gcfg = config("global")
-        stages = [
-            ("pack", lambda: tb.tensorbleu_pack(cand, cl, refs, rl, gcfg, ws, stats)),
-            ("dictionary", lambda: tb.tensorbleu_dictionary(cl, rl, cs, rs, gcfg, ws, stats)),
-            ("count_clip", lambda: tb.tensorbleu_count_clip(cl, rl, cs, rs, gcfg, ws, stats)),
-            ("finalize", lambda: tb.tensorbleu_finalize(cl, rl, cs, rs, gcfg, False, out, ws,
+        gws = ws if path == "global" else tb.allocate_workspace(w.B, w.R, cs, rs, gcfg, dev)
+        gstages = [
+            ("pack", lambda: tb.tensorbleu_pack(cand, cl, refs, rl, gcfg, gws, stats)),
+            ("dictionary", lambda: tb.tensorbleu_dictionary(cl, rl, cs, rs, gcfg, gws, stats)),
+            ("count_clip", lambda: tb.tensorbleu_count_clip(cl, rl, cs, rs, gcfg, gws, stats)),
+            ("finalize", lambda: tb.tensorbleu_finalize(cl, rl, cs, rs, gcfg, False, out, gws,
                                                         stats)),
         ]
+        grows = time_stages(gstages, alg)
+
+        def gstep():
+            tb.tensorbleu_sentence(cand, cl, refs, rl, gcfg, out=out, stats=stats, workspace=gws)
+        gstep()
+        g_ms = time_region(gstep, a.steps, torch)
+        global_section = {"ms_per_step": round(g_ms, 5),
+                          "sentences_per_s": round(w.B / (g_ms * 1e-3), 1), "passes": grows}
+    if path == "global":
+        passes = global_section["passes"]
     else:
-        stages = [("fused", step)]
-    for name, fn in stages:
-        for _ in range(3):
-            fn()
-        t_ms = time_region(fn, a.steps, torch)
-        gbps = alg[name] / (t_ms * 1e-3) / 1e9
-        passes.append({"kernel": name, "us": round(t_ms * 1e3, 2), "alg_bytes": int(alg[name]),
-                       "GBps": round(gbps, 1), "frac_hbm": round(gbps / HBM_PEAK_GBPS, 4)})
+        passes = time_stages([("fused", step)], alg)
     dom = max(passes, key=lambda p: p["us"])
+    traffic = a.traffic_bytes
+    if traffic is None:
+        traffic = MEASURED_TRAFFIC.get((w.name, dom["kernel"]))
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["GBps"],
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_hbm"],
-                "traffic": a.traffic_bytes}
+                "traffic": traffic}
 
     result = {
         "metric": "per-sentence BLEU sentences/sec at B=512, L=1024; % HBM roofline",
         "value": round(w.B / (ms * 1e-3), 1), "unit": "sentences/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u64 keys / u32 counts / f32 scores", "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "R": w.R, "cand_len": cs, "ref_stride": rs,
+        "dtype": "u32 keys / u16 counts / f32 scores" if path == "fused"
+                 else "u64 keys / u16 counts / f32 scores",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "R": w.R, "cand_stride": cs, "ref_stride": rs,
                    "vocab": w.vocab, "max_n": N, "smoothing": run.smoothing, "path": path,
                    "tokens": w.tokens},
         "ms_per_step_events": round(ev_ms, 5), "ms_per_step_wall": round(wall_ms, 5),
         "roofline": roofline, "passes": passes,
     }
+    if global_section is not None and path != "global":
+        result["global_path"] = global_section
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, run)
     print(json.dumps(result), flush=True)
