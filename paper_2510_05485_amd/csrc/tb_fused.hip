@@ -1,16 +1,16 @@
 // FUSED path: the whole per-sentence pipeline in one kernel, one workgroup per sentence group.
 //
-// Tokens of the candidate and its references are read from HBM once and staged in LDS; for each
-// order n the workgroup
-//   1. extends every position's packed key by one token (n-gram extraction, Section 3.1),
-//   2. inserts the candidate's keys into an LDS open-addressing table (the dictionary of Section
-//      3.2, restricted to the candidate: an n-gram that the candidate lacks cannot contribute to
-//      min(candidate count, reference count)),
-//   3. looks every reference n-gram up and bumps that reference's 16-bit counter of the slot
-//      (the slot index is the compact id; one counter field per sequence keeps the sequences'
-//      counts apart, which is what the offset of Section 3.3 step 1 achieves),
-//   4. sweeps the slots: maximum over the reference fields, minimum with the candidate field,
-//      summed (Section 3.3 step 3),
+// Tokens of the candidate and its references are read from HBM once and staged in LDS; then, for
+// each order n, the workgroup
+//   1. inserts the candidate's n-grams into an LDS open-addressing table (the dictionary of
+//      Section 3.2, restricted to the candidate: an n-gram that the candidate lacks cannot
+//      contribute to min(candidate count, reference count)); the id of a distinct n-gram is the
+//      candidate position whose insertion created its entry,
+//   2. looks the reference n-grams up and bumps the 16-bit counter field that belongs to
+//      (id, reference) -- one field per sequence keeps the sequences' counts apart, which is what
+//      the offset of Section 3.3 step 1 achieves,
+//   3. lets the thread that created an entry take the maximum over the reference fields and the
+//      minimum with the candidate field (Section 3.3 step 3) and sum it,
 // and finally lane 0 forms the brevity penalty, smoothing and geometric mean (Section 3.4).
 // HBM traffic is the tokens in and one score (plus optional integer statistics) out.
 #include "tb_kernels.h"
@@ -19,91 +19,172 @@
 namespace tb {
 
 constexpr int kMaxFusedSeqs = kWave;  // candidate + references handled by one lane each
+constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
+constexpr size_t kLdsForTwoWorkgroups = 78 * 1024;  // per workgroup, so that two share a CU
 
 struct FusedArgs {
   Problem pb;
   StatPtrs st;
   ScoreParams sp;
-  float* out;          // per-sentence scores, or null
-  int table_slots;     // power of two
-  int table_shift;     // 32 - log2(table_slots)
-  int words;           // 32-bit counter words per slot: ceil((R + 1) / 2)
-  uint32_t off_cnt, off_tok;
+  float* out;           // per-sentence scores, or null
+  int table_slots;      // power of two
+  int table_shift;      // 32 - log2(table_slots)
+  int words;            // 32-bit counter words per id: ceil((R + 1) / 2)
+  int list_per_wave;    // work-list entries reserved for each wavefront
+  uint32_t off_ids, off_cnt, off_cstate, off_tok, off_list;
 };
+
+static size_t fused_layout(int slots, int64_t cand_stride, int64_t cap, int list_total, int words,
+                           int tok_bytes, FusedPlan* plan) {
+  size_t off = size_t(slots) * 4;
+  plan->off_ids = off;
+  off += size_t(slots) * 2;
+  plan->off_cnt = off;
+  off += size_t(cand_stride) * words * 4;
+  plan->off_cstate = off;
+  off += size_t(cand_stride) * 4;
+  plan->off_tok = off;
+  off += (size_t(cap + 4) * tok_bytes + 3) & ~size_t(3);
+  plan->off_list = off;
+  off += size_t(list_total) * 4;
+  return off;
+}
 
 bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
                 FusedPlan* plan) {
   (void)N;
   if (R + 1 > kMaxFusedSeqs) return false;
-  if (cand_stride > 65535 || ref_stride > 65535) return false;  // 16-bit counter fields
   const int64_t cap = cand_stride + int64_t(R) * ref_stride;
-  if (cap > 12 * 1024) return false;
+  // list entries pack position (14 bits), id (12 bits) and sequence index (6 bits)
+  if (cap > 12 * 1024 || cand_stride > 4096 || ref_stride > 65535) return false;
+  int id_bits = 1;
+  while ((int64_t(1) << id_bits) < cand_stride) ++id_bits;
+  if (id_bits + bits > 31) return false;  // key = id * 2^bits + token must stay below 2^31
   int t = 256;
   while (t < 1024 && cap > 4 * t) t *= 2;
   plan->threads = t;
-  const int need = int((cap + t - 1) / t);
-  plan->items = need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : 12;
-  int slots = 256, lg = 8;
-  while (int64_t(slots) * 3 < cand_stride * 4) {
-    slots <<= 1;
-    ++lg;
-  }
-  plan->table_slots = slots;
-  // a key is (slot of the (n-1)-gram prefix) * 2^bits + last token
-  plan->key_bytes = (lg + bits <= 31) ? 4 : 8;
   plan->words = (R + 2) / 2;
-  size_t off = size_t(slots) * plan->key_bytes;
-  plan->off_cnt = off;
-  off += size_t(slots) * plan->words * 4;
-  off = (off + 15) & ~size_t(15);
-  plan->off_tok = off;
-  off += size_t(cap) * 4;
-  plan->lds_bytes = off;
-  return off + 1024 <= size_t(kLdsBudget);
+  plan->tok_bytes = bits <= 16 ? 2 : 4;
+  const int nwaves = t / kWave;
+  const int64_t list_cap = int64_t(R) * ref_stride;
+  plan->list_per_wave = int((list_cap + nwaves - 1) / nwaves);
+  plan->list_per_wave = (plan->list_per_wave + kWave - 1) / kWave * kWave;
+  const int list_total = plan->list_per_wave * nwaves;
+  int base = 256;
+  while (int64_t(base) * 3 < cand_stride * 4) base <<= 1;
+  // the emptier the table the fewer probes; take the largest of 4x, 2x, 1x the minimum size
+  // that still lets two workgroups share a compute unit, else the minimum size
+  plan->table_slots = base;
+  plan->lds_bytes =
+      fused_layout(base, cand_stride, cap, list_total, plan->words, plan->tok_bytes, plan);
+  for (int mult = 4; mult >= 2; mult >>= 1) {
+    FusedPlan trial = *plan;
+    const size_t bytes = fused_layout(base * mult, cand_stride, cap, list_total, plan->words,
+                                      plan->tok_bytes, &trial);
+    if (bytes + 1024 <= kLdsForTwoWorkgroups && base * mult <= 65536) {
+      *plan = trial;
+      plan->table_slots = base * mult;
+      plan->lds_bytes = bytes;
+      break;
+    }
+  }
+  return plan->lds_bytes + 1024 <= size_t(kLdsBudget);
 }
 
-template <typename KeyT> struct KeyTraits;
-template <> struct KeyTraits<uint32_t> {
-  using Word = unsigned int;
-  static constexpr Word kEmpty = 0xFFFFFFFFu;
-  // One 32-bit multiply; the top bits of the product pick the slot, lower bits the probe step.
-  static __device__ __forceinline__ uint32_t hash(Word k) { return k * 0x9E3779B1u; }
-};
-template <> struct KeyTraits<uint64_t> {
-  using Word = unsigned long long;
-  static constexpr Word kEmpty = ~0ull;
-  static __device__ __forceinline__ uint32_t hash(Word k) {
-    const uint32_t lo = uint32_t(k), hi = uint32_t(k >> 32);
-    return (lo ^ ((hi << 15) | (hi >> 17))) * 0x9E3779B1u;
+// The candidate's dictionary of one order: an open-addressing table of 32-bit keys with double
+// hashing.  One 32-bit multiply hashes the key: the top bits of the product pick the slot, lower
+// bits the (odd) probe step, so a probe sequence reaches every slot of the power-of-two table.
+//
+// Both probe loops are written without branches inside: every lane of the wavefront runs the
+// same number of rounds (until no lane is pending, at most `slots` rounds), lanes that are done
+// or inactive keep reading but ignore what they read.  On this hardware the exec-mask
+// bookkeeping of a divergent loop with several exits costs several times more scalar
+// instructions than the probe itself.
+struct ProbeTable {
+  uint32_t* slots;
+  uint32_t mask;  // slots - 1
+  int shift;      // 32 - log2(slots)
+
+  static constexpr uint32_t kNotFound = 0xFFFFFFFFu;
+
+  // Slot of `key`, or kNotFound.  Lanes with active == false return kNotFound.
+  __device__ __forceinline__ uint32_t find(uint32_t key, bool active) const {
+    const uint32_t h = key * 0x9E3779B1u;
+    const uint32_t step = (h >> 3) | 1u;
+    uint32_t s = h >> shift;
+    uint32_t found = kNotFound;
+    bool pending = active;
+    for (uint32_t round = 0; round <= mask && __builtin_amdgcn_ballot_w64(pending) != 0;
+         ++round) {
+      const uint32_t e = slots[s];
+      const bool hit = e == key;
+      found = (pending && hit) ? s : found;
+      pending = pending && !hit && e != kEmptySlot;
+      s = (s + step) & mask;
+    }
+    return found;
+  }
+
+  // Claim-or-find for active lanes.  Returns the slot; *won is set where this call created
+  // the entry.
+  __device__ __forceinline__ uint32_t insert(uint32_t key, bool active, bool* won) const {
+    const uint32_t h = key * 0x9E3779B1u;
+    const uint32_t step = (h >> 3) | 1u;
+    uint32_t s = h >> shift;
+    uint32_t slot = 0;
+    bool created = false;
+    bool pending = active;
+    for (uint32_t round = 0; round <= mask && __builtin_amdgcn_ballot_w64(pending) != 0;
+         ++round) {
+      // a plain read first: duplicates and collisions never pay for the compare-and-swap
+      uint32_t old = slots[s];
+      if (pending && old == kEmptySlot) old = atomicCAS(&slots[s], kEmptySlot, key);
+      const bool claimed = pending && old == kEmptySlot;
+      const bool done = claimed || (pending && old == key);
+      created = created || claimed;
+      slot = done ? s : slot;
+      pending = pending && !done;
+      s = (s + step) & mask;
+    }
+    *won = created;
+    return slot;
   }
 };
 
-// One workgroup per sentence group.  Each thread owns up to ITEMS token positions of the group's
-// sequences (candidate first, then the references, back to back).
+// One workgroup per sentence group.
 //
-// Keys are hierarchical: the order-n key of a position is (slot that its (n-1)-gram prefix
-// occupied in the order-(n-1) table) * 2^bits + the n-th token.  Two positions carry the same
-// order-n key exactly when their n-grams are equal, because by induction a slot of the previous
-// table stands for one distinct (n-1)-gram of the candidate.  The key therefore never needs more
-// than log2(slots) + bits bits whatever n is, and a reference position whose prefix was not
-// found in the candidate's table is dropped from all higher orders: no candidate n-gram can
-// extend a prefix the candidate does not contain.
-template <int ITEMS, typename KeyT>
-__global__ __launch_bounds__(1024, (ITEMS <= 6 ? 8 : 4)) void fused_kernel(FusedArgs a) {
-  using Traits = KeyTraits<KeyT>;
-  using Word = typename Traits::Word;
+// Keys are hierarchical: the order-n key of a position is (id of its (n-1)-gram prefix) * 2^bits
+// + the n-th token, where the id of a distinct candidate n-gram is the candidate position that
+// created its table entry (order-0 ids are 0).  By induction two positions carry the same
+// order-n key exactly when their n-grams are equal, so the key never needs more than
+// log2(cand_stride) + bits bits whatever n is, and one 32-bit LDS compare-and-swap claims a slot.
+//
+// A reference position whose n-gram is not in the candidate's table cannot match at any higher
+// order either (a candidate n-gram extends only prefixes the candidate contains), so it is
+// dropped.  Each wavefront owns a slice of the reference positions and keeps the survivors --
+// position, id, sequence index packed in one word -- compacted in its own LDS work list, so the
+// next order runs over full wavefronts; reading and appending stay inside the wavefront and
+// need neither atomics nor extra barriers.
+template <typename TokT>
+__global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int red[16][4];
-  __shared__ int s_len[kMaxFusedSeqs];
+  __shared__ int s_part[4];              // per order: clipped sum (low 16) | distinct count (high 16)
+  __shared__ int s_len[kMaxFusedSeqs];   // length of each sequence
+  __shared__ int s_end[kMaxFusedSeqs];   // end of each sequence in back-to-back token indices
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
-  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int lane = tid & (kWave - 1), wave = tid / kWave, nwaves = nt / kWave;
   const int g = blockIdx.x;
-  const int R = pb.R, N = pb.N, T = a.table_slots, W = a.words;
-  Word* table = reinterpret_cast<Word*>(smem);
+  const int R = pb.R, N = pb.N, T = a.table_slots;
+  const uint32_t W = uint32_t(a.words);
+  uint32_t* table = reinterpret_cast<uint32_t*>(smem);
+  uint16_t* ids = reinterpret_cast<uint16_t*>(smem + a.off_ids);
   uint32_t* cnt = reinterpret_cast<uint32_t*>(smem + a.off_cnt);
-  int32_t* tok = reinterpret_cast<int32_t*>(smem + a.off_tok);
-  const uint32_t mask = uint32_t(T) - 1u;
+  uint32_t* cstate = reinterpret_cast<uint32_t*>(smem + a.off_cstate);
+  TokT* tok = reinterpret_cast<TokT*>(smem + a.off_tok);
+  uint32_t* my_list = reinterpret_cast<uint32_t*>(smem + a.off_list) + wave * a.list_per_wave;
+  const ProbeTable dict{table, uint32_t(T) - 1u, a.table_shift};
+  const int bits = pb.bits;
 #ifdef TB_PHASE_CLOCKS
   long long ts[14];
   int nts = 0;
@@ -119,217 +200,197 @@ __global__ __launch_bounds__(1024, (ITEMS <= 6 ? 8 : 4)) void fused_kernel(Fused
                       wave == 0 ? pb.status : nullptr);
   }
   const int incl = wave_inclusive_scan(my_len);
-  if (wave == 0 && lane <= R) s_len[lane] = my_len;
-  const int total_tokens = min(lane_value(incl, R), ITEMS * nt);
+  if (wave == 0 && lane <= R) {
+    s_len[lane] = my_len;
+    s_end[lane] = incl;
+  }
+  if (tid < 4) s_part[tid] = 0;
+  const int total_tokens = lane_value(incl, R);
+  const int cand_len = lane_value(my_len, 0);
 
-  // clear the table and the counters once (afterwards each order resets the slots it created)
-  for (int s = tid; s < T; s += nt) table[s] = Traits::kEmpty;
-  for (int s = tid; s < T * W; s += nt) cnt[s] = 0;
+  for (int s = tid; s < T; s += nt) table[s] = kEmptySlot;
+  for (int s = tid; s < cand_len * int(W); s += nt) cnt[s] = 0;
+  for (int s = tid; s < cand_len; s += nt) cstate[s] = 0;
 
-  // which sequence each of this thread's token positions belongs to (boundaries are scalars)
-  uint32_t info[ITEMS];  // tokens left in the sequence from this position (<= 255) | field << 8
-  uint32_t cur[ITEMS];   // order 1: the token; later: slot of the position's current n-gram
+  // stage the tokens back to back: candidate, reference 0, reference 1, ...
   {
-    int begin[ITEMS], end[ITEMS];
-    const int e0 = lane_value(incl, 0);
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      info[i] = 0;
-      begin[i] = 0;
-      end[i] = e0;
-    }
-    for (int m = 1; m <= R; ++m) {
-      const int bm = lane_value(incl, m - 1), em = lane_value(incl, m);
-#pragma unroll
-      for (int i = 0; i < ITEMS; ++i) {
-        const bool ge = tid + i * nt >= bm;
-        info[i] = ge ? uint32_t(m) : info[i];
-        begin[i] = ge ? bm : begin[i];
-        end[i] = ge ? em : end[i];
-      }
-    }
-    // stage tokens in LDS
     const int32_t* cand_row = pb.cand + int64_t(g) * pb.cand_stride;
     const int32_t* ref_rows = pb.refs + int64_t(g) * R * pb.ref_stride;
     bool bad = false;
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      const int k = tid + i * nt;
-      const uint32_t j = info[i];
-      cur[i] = 0;
-      info[i] = 0;
-      if (k < total_tokens) {
-        const int p = k - begin[i];
-        const int32_t t =
-            (j == 0) ? cand_row[p] : ref_rows[int64_t(j - 1) * pb.ref_stride + p];
-        tok[k] = t;
-        bad |= (uint32_t(t) >= uint32_t(pb.vocab));
-        cur[i] = uint32_t(t);
-        info[i] = uint32_t(min(end[i] - k, 255)) | (j << 8);
+    for (int k = tid; k < total_tokens; k += nt) {
+      int j = 0, begin = 0;
+      for (int m = 1; m <= R; ++m) {
+        const int bm = lane_value(incl, m - 1);
+        const bool ge = k >= bm;
+        j = ge ? m : j;
+        begin = ge ? bm : begin;
       }
+      const int p = k - begin;
+      const int32_t t = (j == 0) ? cand_row[p] : ref_rows[int64_t(j - 1) * pb.ref_stride + p];
+      tok[k] = TokT(t);
+      bad |= (uint32_t(t) >= uint32_t(pb.vocab));
     }
     if (bad && pb.status) atomicOr(pb.status, TB_DEV_TOKEN_RANGE);
+  }
+  // this wavefront's slice of the reference positions (order 1 reads it directly), and the
+  // range of sequences the slice touches
+  const int nref = total_tokens - cand_len;
+  const int slice = min((nref + nwaves - 1) / nwaves, a.list_per_wave);
+  const int slice_begin = cand_len + wave * slice;
+  int todo = max(min(slice, total_tokens - slice_begin), 0);  // entries in this wave's list
+  int f_lo = 0, f_hi = 0;
+  for (int m = 1; m <= R; ++m) {
+    const int bm = lane_value(incl, m - 1);
+    f_lo += (slice_begin >= bm) ? 1 : 0;
+    f_hi += (slice_begin + todo - 1 >= bm) ? 1 : 0;
   }
   __syncthreads();
 #ifdef TB_PHASE_CLOCKS
   ts[nts++] = clock64();
 #endif
 
-  int part[4] = {0, 0, 0, 0};  // per order: clipped sum (low 16 bits) | distinct count (high 16)
-  const int bits = pb.bits;
-#pragma unroll
-  for (int n = 1; n <= 4; ++n) {
-    if (n > N) break;
-    if (n >= 2) __syncthreads();  // the previous order's slots have all been reset
+#pragma unroll 1
+  for (int n = 1; n <= N; ++n) {
+    if (n >= 2) __syncthreads();  // every slot of the previous order has been emptied
 
-    // candidate n-grams: claim or find the slot, count in field 0
-    uint32_t win = 0;  // bit i: this thread's item i created its slot
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      if (int(info[i] & 0xFFu) >= n && (info[i] >> 8) == 0) {
-        Word key = cur[i];
-        if (n >= 2) key = (key << bits) | Word(uint32_t(tok[tid + i * nt + n - 1]));
-        const uint32_t h = Traits::hash(key);
-        const uint32_t step = (h >> 3) | 1u;
-        uint32_t s = h >> a.table_shift;
-        for (int guard = T; guard > 0; --guard) {  // T probes visit every slot
-          const Word old = atomicCAS(&table[s], Traits::kEmpty, key);
-          if (old == Traits::kEmpty) win |= 1u << i;
-          if (old == Traits::kEmpty || old == key) break;
-          s = (s + step) & mask;
-        }
-        atomicAdd(&cnt[__umul24(s, uint32_t(W))], 1u);
-        cur[i] = s;
-      }
+    // ---- A: candidate n-grams claim or find their entry
+    for (int k0 = 0; k0 + n <= cand_len; k0 += nt) {
+      const int k = k0 + tid;
+      const bool active = k + n <= cand_len;
+      const int kk = active ? k : 0;
+      const uint32_t pid = (cstate[kk] >> 16) & 0xFFFu;
+      const uint32_t key = (pid << bits) | uint32_t(tok[kk + n - 1]);
+      bool won;
+      const uint32_t s = dict.insert(key, active, &won);
+      if (won) ids[s] = uint16_t(k);
+      if (active) cstate[k] = s | (won ? 0x80000000u : 0u);
     }
     __syncthreads();
 #ifdef TB_PHASE_CLOCKS
-    ts[nts++] = clock64();
+    if (n <= 4) ts[nts++] = clock64();
 #endif
 
-    // reference n-grams: look up; count in the reference's own 16-bit field, or retire the
-    // position when the candidate has no such n-gram
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      const uint32_t f = info[i] >> 8;
-      if (int(info[i] & 0xFFu) >= n && f != 0) {
-        Word key = cur[i];
-        if (n >= 2) key = (key << bits) | Word(uint32_t(tok[tid + i * nt + n - 1]));
-        const uint32_t h = Traits::hash(key);
-        const uint32_t step = (h >> 3) | 1u;
-        uint32_t s = h >> a.table_shift;
-        bool found = false;
-        for (int guard = T; guard > 0; --guard) {
-          const Word w = table[s];
-          found = (w == key);
-          if (found || w == Traits::kEmpty) break;
-          s = (s + step) & mask;
-        }
-        if (found) {
-          atomicAdd(&cnt[__umul24(s, uint32_t(W)) + (f >> 1)], (f & 1u) ? 0x10000u : 1u);
-          cur[i] = s;
-        } else {
-          info[i] = 0;
-        }
-      }
+    // ---- B: candidate counts (field 0 of the entry's id) ...
+    for (int k = tid; k + n <= cand_len; k += nt) {
+      const uint32_t st = cstate[k];
+      const uint32_t id = ids[st & 0xFFFFu];
+      atomicAdd(&cnt[__umul24(id, W)], 1u);
+      cstate[k] = (st & 0x8000FFFFu) | (id << 16);
     }
+    // ... and this wavefront's reference positions: look up, count in the reference's field,
+    // keep the ones that can still match at the next order
+    int kept = 0;
+    for (int e0 = 0; e0 < todo; e0 += kWave) {
+      const int e = e0 + lane;
+      const bool active = e < todo;
+      uint32_t q, pid, f;
+      if (n == 1) {
+        q = uint32_t(min(slice_begin + e, total_tokens - 1));
+        pid = 0;
+        f = uint32_t(f_lo);
+        for (int m = f_lo + 1; m <= f_hi; ++m)
+          f += (q >= uint32_t(lane_value(incl, m - 1))) ? 1u : 0u;
+      } else {
+        const uint32_t ent = my_list[active ? e : 0];
+        q = ent & 0x3FFFu;
+        pid = (ent >> 14) & 0xFFFu;
+        f = ent >> 26;
+      }
+      const uint32_t key = (pid << bits) | uint32_t(tok[q + uint32_t(n) - 1]);
+      const uint32_t s = dict.find(key, active);
+      uint32_t next = 0xFFFFFFFFu;
+      if (s != ProbeTable::kNotFound) {
+        const uint32_t id = ids[s];
+        atomicAdd(&cnt[__umul24(id, W) + (f >> 1)], (f & 1u) ? 0x10000u : 1u);
+        const bool more = n < N && uint32_t(s_end[f]) >= q + uint32_t(n) + 1u;
+        next = more ? (q | (id << 14) | (f << 26)) : next;
+      }
+      // in-place compaction: the write cursor never passes the entries still to be read
+      const unsigned long long m = __builtin_amdgcn_ballot_w64(next != 0xFFFFFFFFu);
+      const uint32_t rank =
+          __builtin_amdgcn_mbcnt_hi(uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), 0u));
+      if (next != 0xFFFFFFFFu) my_list[kept + int(rank)] = next;
+      kept += int(__builtin_popcountll(m));
+    }
+    todo = kept;
     __syncthreads();
 #ifdef TB_PHASE_CLOCKS
-    ts[nts++] = clock64();
+    if (n <= 4) ts[nts++] = clock64();
 #endif
 
-    // the thread that created a slot clips it (max over reference fields, min with the
-    // candidate field) and resets it for the next order
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      if (win & (1u << i)) {
-        const uint32_t base = __umul24(cur[i], uint32_t(W));
+    // ---- C: the position that created an entry clips it (max over the reference fields, min
+    // with the candidate field), zeroes its counters and empties its slot
+    int part = 0;
+    for (int k = tid; k + n <= cand_len; k += nt) {
+      const uint32_t st = cstate[k];
+      if (st >> 31) {
+        const uint32_t base = __umul24(uint32_t(k), W);
         const uint32_t w0 = cnt[base];
-        uint32_t m = w0 >> 16;
+        uint32_t mx = w0 >> 16;
         cnt[base] = 0;
-        for (int w = 1; w < W; ++w) {
+        for (uint32_t w = 1; w < W; ++w) {
           const uint32_t x = cnt[base + w];
-          m = max(m, max(x & 0xFFFFu, x >> 16));
+          mx = max(mx, max(x & 0xFFFFu, x >> 16));
           cnt[base + w] = 0;
         }
-        part[n - 1] += int(min(w0 & 0xFFFFu, m)) + 0x10000;
-        table[cur[i]] = Traits::kEmpty;
+        part += int(min(w0 & 0xFFFFu, mx)) + 0x10000;
+        table[st & 0xFFFFu] = kEmptySlot;
       }
     }
+    part = wave_sum(part);
+    if (lane == 0 && part != 0) atomicAdd(&s_part[n - 1], part);
 #ifdef TB_PHASE_CLOCKS
-    ts[nts++] = clock64();
+    if (n <= 4) ts[nts++] = clock64();
 #endif
-  }
-
-  // reduce the packed per-thread partial sums of all orders
-#pragma unroll
-  for (int n = 0; n < 4; ++n) {
-    const int p = wave_sum(part[n]);
-    if (lane == 0) red[wave][n] = p;
   }
   __syncthreads();
-  if (wave == 0) {
-    const int nwaves = nt / kWave;
-    int sums[4];
+
+  if (tid == 0) {
+    int clipped[4] = {0, 0, 0, 0}, total[4] = {0, 0, 0, 0};
+    const int c = cand_len;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) sums[n] = wave_sum(lane < nwaves ? red[lane][n] : 0);
-    if (lane == 0) {
-      int clipped[4] = {0, 0, 0, 0}, total[4] = {0, 0, 0, 0};
-      const int c = s_len[0];
-#pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        if (n < N) {
-          clipped[n] = sums[n] & 0xFFFF;
-          total[n] = max(c - n, 0);
-          a.st.clipped[int64_t(g) * N + n] = clipped[n];
-          a.st.total[int64_t(g) * N + n] = total[n];
-          a.st.distinct[int64_t(g) * N + n] = int(uint32_t(sums[n]) >> 16);
-        }
+    for (int n = 0; n < 4; ++n) {
+      if (n < N) {
+        const int sum = s_part[n];
+        clipped[n] = sum & 0xFFFF;
+        total[n] = max(c - n, 0);
+        a.st.clipped[int64_t(g) * N + n] = clipped[n];
+        a.st.total[int64_t(g) * N + n] = total[n];
+        a.st.distinct[int64_t(g) * N + n] = int(uint32_t(sum) >> 16);
       }
-      int best = s_len[1], bd = abs(best - c);
-      for (int j = 2; j <= R; ++j) {
-        const int l = s_len[j], d = abs(l - c);
-        if (d < bd || (d == bd && l < best)) {
-          best = l;
-          bd = d;
-        }
-      }
-      a.st.closest[g] = best;
-      if (a.out) a.out[g] = bleu_from_stats<int>(clipped, total, c, best, a.sp);
-#ifdef TB_PHASE_CLOCKS
-      for (int q = 0; q < 4; ++q) {
-        a.st.clipped[int64_t(g) * N + q] = int(ts[2 + 3 * q] - ts[1 + 3 * q]);
-        a.st.total[int64_t(g) * N + q] = int(ts[3 + 3 * q] - ts[2 + 3 * q]);
-        a.st.distinct[int64_t(g) * N + q] = int(ts[4 + 3 * q] - ts[3 + 3 * q]);
-      }
-      a.st.closest[g] = int(ts[1] - ts[0]);
-      a.out[g] = float(clock64() - ts[0]);
-#endif
     }
+    int best = s_len[1], bd = abs(best - c);
+    for (int j = 2; j <= R; ++j) {
+      const int l = s_len[j], d = abs(l - c);
+      if (d < bd || (d == bd && l < best)) {
+        best = l;
+        bd = d;
+      }
+    }
+    a.st.closest[g] = best;
+    if (a.out) a.out[g] = bleu_from_stats<int>(clipped, total, c, best, a.sp);
+#ifdef TB_PHASE_CLOCKS
+    for (int q = 0; q < 4; ++q) {
+      a.st.clipped[int64_t(g) * N + q] = int(ts[2 + 3 * q] - ts[1 + 3 * q]);
+      a.st.total[int64_t(g) * N + q] = int(ts[3 + 3 * q] - ts[2 + 3 * q]);
+      a.st.distinct[int64_t(g) * N + q] = int(ts[4 + 3 * q] - ts[3 + 3 * q]);
+    }
+    a.st.closest[g] = int(ts[1] - ts[0]);
+    a.out[g] = float(clock64() - ts[0]);
+#endif
   }
 }
 
-template <int ITEMS, typename KeyT>
-hipError_t launch_fused_items(const FusedArgs& a, int blocks, int threads, size_t lds,
-                              hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<ITEMS, KeyT>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((fused_kernel<ITEMS, KeyT>), dim3(blocks), dim3(threads), lds, s, a);
-  return hipGetLastError();
-}
-
-template <typename KeyT>
-hipError_t launch_fused_key(const FusedArgs& a, const FusedPlan& plan, int blocks,
+template <typename TokT>
+hipError_t launch_fused_tok(const FusedArgs& a, const FusedPlan& plan, int blocks,
                             hipStream_t s) {
-  switch (plan.items) {
-    case 2: return launch_fused_items<2, KeyT>(a, blocks, plan.threads, plan.lds_bytes, s);
-    case 4: return launch_fused_items<4, KeyT>(a, blocks, plan.threads, plan.lds_bytes, s);
-    case 6: return launch_fused_items<6, KeyT>(a, blocks, plan.threads, plan.lds_bytes, s);
-    case 8: return launch_fused_items<8, KeyT>(a, blocks, plan.threads, plan.lds_bytes, s);
-    case 12: return launch_fused_items<12, KeyT>(a, blocks, plan.threads, plan.lds_bytes, s);
-    default: return hipErrorInvalidValue;
-  }
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<TokT>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     int(plan.lds_bytes));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((fused_kernel<TokT>), dim3(blocks), dim3(plan.threads), plan.lds_bytes, s,
+                     a);
+  return hipGetLastError();
 }
 
 hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs& st,
@@ -344,10 +405,14 @@ hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs
   while ((1 << lg) < plan.table_slots) ++lg;
   a.table_shift = 32 - lg;
   a.words = plan.words;
+  a.list_per_wave = plan.list_per_wave;
+  a.off_ids = uint32_t(plan.off_ids);
   a.off_cnt = uint32_t(plan.off_cnt);
+  a.off_cstate = uint32_t(plan.off_cstate);
   a.off_tok = uint32_t(plan.off_tok);
-  return plan.key_bytes == 4 ? launch_fused_key<uint32_t>(a, plan, pb.B, s)
-                             : launch_fused_key<uint64_t>(a, plan, pb.B, s);
+  a.off_list = uint32_t(plan.off_list);
+  return plan.tok_bytes == 2 ? launch_fused_tok<uint16_t>(a, plan, pb.B, s)
+                             : launch_fused_tok<int32_t>(a, plan, pb.B, s);
 }
 
 }  // namespace tb

@@ -40,11 +40,12 @@ struct CountPlan {
   size_t lds_bytes;
 };
 struct FusedPlan {
-  int threads, items;  // workgroup size; token positions kept per thread
-  int table_slots;     // power of two >= 4/3 * cand_stride
-  int words;           // 32-bit counter words per slot (two 16-bit sequence fields each)
-  int key_bytes;       // 4 when log2(table_slots) + bits <= 31, else 8
-  size_t lds_bytes, off_cnt, off_tok;
+  int threads;         // workgroup size
+  int table_slots;     // power of two >= 4/3 * cand_stride (larger when LDS allows)
+  int words;           // 32-bit counter words per id (two 16-bit sequence fields each)
+  int tok_bytes;       // staged tokens are 2 bytes when bits <= 16, else 4
+  int list_per_wave;   // work-list entries reserved per wavefront (multiple of 64)
+  size_t lds_bytes, off_ids, off_cnt, off_cstate, off_tok, off_list;
 };
 
 bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan);
