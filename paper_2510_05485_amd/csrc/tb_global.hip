@@ -443,16 +443,20 @@ __global__ __launch_bounds__(1024) void count_clip_kernel(CountArgs a) {
   uint32_t* cur = acc + cap;
   const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
   const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
-  const int U = min(max(a.st.distinct[int64_t(g) * pb.N + n - 1], 0), cap);
-  const GroupIndex gi(pb, g, n);
-  const int count = min(gi.start(pb.R + 1), ITEMS * nt);
-
+  // The loads go out before the group's n-gram count is known (that needs the lengths, another
+  // round trip to memory): every slot of the group's range exists, slots past the count hold
+  // stale bytes that are never used.
   uint32_t id[ITEMS];
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
-    id[i] = (k < count) ? ginv[k] - gbase : 0xFFFFFFFFu;
+    id[i] = (k < cap) ? ginv[k] : 0u;
   }
+  const int U = min(max(a.st.distinct[int64_t(g) * pb.N + n - 1], 0), cap);
+  const GroupIndex gi(pb, g, n);
+  const int count = min(gi.start(pb.R + 1), ITEMS * nt);
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) id[i] = (tid + i * nt < count) ? id[i] - gbase : 0xFFFFFFFFu;
   for (int u = tid; u < U; u += nt) {
     acc[u] = 0;
     cur[u] = 0;

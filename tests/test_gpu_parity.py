@@ -103,6 +103,7 @@ def test_config1_all_smoothing_modes(path, run):
     (105, 64, 5, 2, 40),        # binary vocabulary, five references
     (106, 3, 1, 2 ** 31 - 1, 90),  # widest ids: 31 bits per token, 124-bit 4-grams
     (107, 40, 2, 1000, 3),      # candidates shorter than the highest order
+    (108, 3, 40, 500, 200),     # forty references: counters no longer fit one field per sequence
 ])
 def test_random_ragged_batches(path, seed, B, R, V, L):
     w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L)
