@@ -154,6 +154,7 @@ struct DictArgs {
   GlobalWs ws;
   int32_t* distinct;
   int table_slots;
+  int table_shift;  // 32 - log2(table_slots)
   uint32_t lds_table_off;
   int orders[4];
   int num_orders;
@@ -240,10 +241,11 @@ __global__ __launch_bounds__(1024) void dictionary_narrow_kernel(DictArgs a) {
         table[T] = 0;
         slot[i] = uint32_t(T);
       } else {
-        const uint32_t h = key_hash(key[i]);
-        const uint32_t step = (h >> 16) | 1u;
-        uint32_t s = h & mask;
-        while (true) {
+        const uint32_t lo = uint32_t(key[i]), hi = uint32_t(key[i] >> 32);
+        const uint32_t h = (lo ^ ((hi << 15) | (hi >> 17))) * 0x9E3779B1u;
+        const uint32_t step = (h >> 3) | 1u;
+        uint32_t s = h >> a.table_shift;
+        for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
           const unsigned long long old = atomicCAS(&table[s], kEmpty64, key[i]);
           if (old == kEmpty64 || old == key[i]) break;
           s = (s + step) & mask;
@@ -383,8 +385,14 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
   a.pb = pb;
   a.ws = ws;
   a.distinct = distinct;
+  auto shift_of = [](int slots) {
+    int lg = 0;
+    while ((1 << lg) < slots) ++lg;
+    return 32 - lg;
+  };
   if (plan.n_narrow) {
     a.table_slots = plan.narrow_slots;
+    a.table_shift = shift_of(plan.narrow_slots);
     a.lds_table_off = 0;
     a.num_orders = plan.n_narrow;
     for (int k = 0; k < 4; ++k) a.orders[k] = plan.narrow_orders[k];
@@ -394,6 +402,7 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
   }
   if (plan.n_wide) {
     a.table_slots = plan.wide_slots;
+    a.table_shift = shift_of(plan.wide_slots);
     a.lds_table_off = uint32_t(plan.wide_table_off);
     a.num_orders = plan.n_wide;
     for (int k = 0; k < 4; ++k) a.orders[k] = plan.wide_orders[k];

@@ -30,6 +30,17 @@ class Device:
         self.refs, self.ref_len = dev(w.refs), dev(w.ref_len)
 
 
+_WORKLOADS = {}
+
+
+def cached_small(*args, **kw):
+    """random_small, memoised (both paths of a test reuse the batch)."""
+    key = (args, tuple(sorted(kw.items())))
+    if key not in _WORKLOADS:
+        _WORKLOADS[key] = syn.random_small(*args, **kw)
+    return _WORKLOADS[key]
+
+
 def path_supported(w, path, max_n=4):
     cfg = tb.make_config(max_n=max_n, vocab_size=w.vocab, path="global")
     lay = tb.binding.tb_layout_t()
@@ -192,6 +203,35 @@ def test_device_status_reports_bad_tokens_and_lengths(path):
     w.ref_len[1, 0] = -3
     _, st = run_gpu(Device(w), syn.Run("none"), path)
     assert st.device_status.item() & tb.binding.TB_DEV_LENGTH_RANGE
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_largest_supported_group(path):
+    # cand_stride + R * ref_stride = 12288 n-gram slots: the limit of both LDS plans
+    w = syn.random_small(140, B=3, R=2, vocab=5000, max_len=4096, min_len=3000)
+    check(w, syn.Run("exp"), path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_many_tiny_sentences_and_a_single_one(path):
+    w = cached_small(141, B=70000, R=1, vocab=11, max_len=9)         # grid beyond 65535 groups
+    check(w, syn.Run("floor", 0.1), path)
+    w = syn.random_small(142, B=1, R=1, vocab=100, max_len=33, min_len=33)
+    check(w, syn.Run("add-k", 1.0), path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_sixty_three_references(path):
+    w = syn.random_small(143, B=2, R=63, vocab=40, max_len=90)
+    check(w, syn.Run("none"), path)
+
+
+def test_oversize_group_is_rejected_not_miscomputed():
+    w = syn.random_small(144, B=1, R=3, vocab=50, max_len=4100, min_len=4000)
+    d = Device(w)
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    with pytest.raises(tb.TensorBLEUError):
+        tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg)
 
 
 def test_determinism_of_integer_statistics():
