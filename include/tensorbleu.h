@@ -17,7 +17,9 @@
  *     synchronised by the caller.
  *   - Layout: candidate i is the row `cand + i*cand_stride`, valid for `cand_len[i]` tokens;
  *     reference j of candidate i is the row `refs + (i*R + j)*ref_stride`, valid for
- *     `ref_len[i*R + j]` tokens.  Strides are in elements (int32) and bound the lengths; cells
+ *     `ref_len[i*R + j]` tokens.  Token ids are int32, or int64 when cfg->token_bytes == 8 (the
+ *     usual dtype of tokenizer output; read directly, no conversion pass).  Strides are in
+ *     elements and bound the lengths; lengths are always int32; cells
  *     at or beyond a row's length are never interpreted (token id 0 inside the length is an
  *     ordinary token).  Lengths found outside [0, stride] on the device are clamped and
  *     reported through TB_DEV_LENGTH_RANGE.
@@ -73,6 +75,9 @@ typedef struct tb_config {
                            bits = ceil(log2(vocab_size)), order-n keys take n*bits bits and are
                            stored in 8 bytes, or 16 bytes when n*bits > 64 */
   int32_t force_path;   /* tb_path_t; TB_PATH_AUTO picks FUSED when a group fits its LDS budget */
+  int32_t token_bytes;  /* element size of `cand` / `refs`: 4 (int32; 0 means 4) or 8 (int64).
+                           An int64 id outside [0, vocab_size) is reported like any other
+                           out-of-range token */
 } tb_config_t;
 
 /* Optional integer outputs (each pointer may be NULL).  These are what the parity tests compare
@@ -123,8 +128,8 @@ int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64
 
 /* One BLEU score per candidate: out_bleu[B] float32 (device).  Implements Sections 3.1-3.4 with
  * the brevity penalty BP = 1 if c > r else exp(1 - r/c) and BLEU = BP * exp(sum_n w_n log p_n). */
-int tensorbleu_sentence(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                        const int32_t* refs, int64_t ref_stride, const int32_t* ref_len,
+int tensorbleu_sentence(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                        const void* refs, int64_t ref_stride, const int32_t* ref_len,
                         int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
                         const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                         void* hip_stream);
@@ -132,8 +137,8 @@ int tensorbleu_sentence(const int32_t* cand, int64_t cand_stride, const int32_t*
 /* One score for the whole batch: numerators, denominators, candidate lengths and closest
  * reference lengths are summed over the batch before the precisions are formed (Section 3.4,
  * second paragraph).  out_bleu[1] float32 (device). */
-int tensorbleu_corpus(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                      const int32_t* refs, int64_t ref_stride, const int32_t* ref_len,
+int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                      const void* refs, int64_t ref_stride, const int32_t* ref_len,
                       int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
                       const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                       void* hip_stream);
@@ -145,8 +150,8 @@ int tensorbleu_corpus(const int32_t* cand, int64_t cand_stride, const int32_t* c
 
 /* Section 3.1 + 3.2 step 1: every valid n-gram, n = 1..N, packed big-endian into a key
  * (first token in the most significant bits) and written to its slot in keys_off[n-1]. */
-int tensorbleu_pack(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                    const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+int tensorbleu_pack(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                    const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
                     int32_t R, const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
                     size_t workspace_bytes, void* hip_stream);
 

@@ -9,3 +9,4 @@ from .binding import (  # noqa: F401
     tensorbleu_pack, tensorbleu_sentence, tensorbleu_status_string, tensorbleu_workspace_bytes,
     tensorbleu_workspace_layout,
 )
+from .api import BleuScorer, corpus_bleu, sentence_bleu  # noqa: F401

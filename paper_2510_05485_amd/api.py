@@ -1,0 +1,79 @@
+"""Convenience layer over the C-ABI binding for PyTorch callers (e.g. an RL reward function).
+
+Nothing is computed here: the functions build the config struct, allocate (or reuse) output and
+workspace tensors, and call `tensorbleu_sentence` / `tensorbleu_corpus`.  Token-ID tensors may be
+int32 or int64 (the usual tokenizer dtype); lengths are int32.  Everything lives on the GPU and
+runs on the current stream without synchronising.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence
+
+import torch
+
+from . import binding as _b
+
+
+def _refs3d(references) -> torch.Tensor:
+    if isinstance(references, (list, tuple)):
+        return torch.stack(list(references), dim=1)     # R tensors [B, L] -> [B, R, L]
+    return references if references.dim() == 3 else references.unsqueeze(1)
+
+
+def _len32(t: torch.Tensor) -> torch.Tensor:
+    return t if t.dtype == torch.int32 else t.to(torch.int32)
+
+
+class BleuScorer:
+    """Per-sentence / corpus token-ID BLEU for one batch shape, with buffers allocated once.
+
+    scorer = BleuScorer(B, R, cand_stride, ref_stride, vocab_size=50257, smoothing="exp")
+    reward = scorer(cand, cand_len, refs, ref_len)          # float32 [B], on the GPU
+    """
+
+    def __init__(self, B: int, R: int, cand_stride: int, ref_stride: int, *, vocab_size: int,
+                 max_n: int = 4, weights: Optional[Sequence[float]] = None,
+                 smoothing: str = "none", smooth_param: float = 0.0, path: str = "auto",
+                 device="cuda:0", want_stats: bool = False):
+        self.shape = (int(B), int(R), int(cand_stride), int(ref_stride))
+        self.cfg = _b.make_config(max_n=max_n, weights=weights, smoothing=smoothing,
+                                  smooth_param=smooth_param, vocab_size=vocab_size, path=path)
+        self.workspace = _b.allocate_workspace(B, R, cand_stride, ref_stride, self.cfg, device)
+        self.out = torch.empty(B, dtype=torch.float32, device=device)
+        self.corpus_out = torch.zeros(1, dtype=torch.float32, device=device)
+        self.stats = _b.Stats.allocate(B, max_n, device) if want_stats else None
+
+    def _check(self, cand, refs):
+        B, R, cs, rs = self.shape
+        if tuple(cand.shape) != (B, cs) or tuple(refs.shape) != (B, R, rs):
+            raise _b.TensorBLEUError(f"scorer was built for cand {(B, cs)} / refs {(B, R, rs)}, "
+                                     f"got {tuple(cand.shape)} / {tuple(refs.shape)}")
+
+    def __call__(self, cand, cand_len, refs, ref_len) -> torch.Tensor:
+        refs = _refs3d(refs)
+        self._check(cand, refs)
+        return _b.tensorbleu_sentence(cand, _len32(cand_len), refs, _len32(ref_len), self.cfg,
+                                      out=self.out, stats=self.stats, workspace=self.workspace)
+
+    def corpus(self, cand, cand_len, refs, ref_len) -> torch.Tensor:
+        refs = _refs3d(refs)
+        self._check(cand, refs)
+        return _b.tensorbleu_corpus(cand, _len32(cand_len), refs, _len32(ref_len), self.cfg,
+                                    out=self.corpus_out, stats=self.stats,
+                                    workspace=self.workspace)
+
+
+def sentence_bleu(cand, cand_len, refs, ref_len, *, vocab_size: int, **kw) -> torch.Tensor:
+    """One-shot per-sentence BLEU (allocates its buffers; use BleuScorer inside a loop)."""
+    refs = _refs3d(refs)
+    s = BleuScorer(cand.shape[0], refs.shape[1], cand.shape[1], refs.shape[2],
+                   vocab_size=vocab_size, device=cand.device, **kw)
+    return s(cand, cand_len, refs, ref_len).clone()
+
+
+def corpus_bleu(cand, cand_len, refs, ref_len, *, vocab_size: int, **kw) -> torch.Tensor:
+    """One-shot corpus-level BLEU over the batch."""
+    refs = _refs3d(refs)
+    s = BleuScorer(cand.shape[0], refs.shape[1], cand.shape[1], refs.shape[2],
+                   vocab_size=vocab_size, device=cand.device, **kw)
+    return s.corpus(cand, cand_len, refs, ref_len).clone()

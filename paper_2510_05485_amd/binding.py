@@ -32,7 +32,8 @@ EXPORTS = [
 class tb_config_t(ctypes.Structure):
     _fields_ = [("max_n", ctypes.c_int32), ("weights", ctypes.c_float * 4),
                 ("smoothing", ctypes.c_int32), ("smooth_param", ctypes.c_float),
-                ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32)]
+                ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32),
+                ("token_bytes", ctypes.c_int32)]
 
 
 class tb_stats_t(ctypes.Structure):
@@ -117,6 +118,7 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
     cfg.smooth_param = float(smooth_param)
     cfg.vocab_size = int(vocab_size)
     cfg.force_path = PATHS[path] if isinstance(path, str) else int(path)
+    cfg.token_bytes = 4
     return cfg
 
 
@@ -160,12 +162,18 @@ class _Batch:
     ref_stride: int
 
 
-def _batch(cand, cand_len, refs, ref_len) -> _Batch:
+def _batch(cand, cand_len, refs, ref_len, cfg: Optional[tb_config_t] = None) -> _Batch:
     for t, name in ((cand, "cand"), (cand_len, "cand_len"), (refs, "refs"), (ref_len, "ref_len")):
         if not t.is_cuda:
             raise TensorBLEUError(f"{name} must live on the GPU (got {t.device})")
+    for t, name in ((cand_len, "cand_len"), (ref_len, "ref_len")):
         if t.dtype != torch.int32:
             raise TensorBLEUError(f"{name} must be int32 (got {t.dtype})")
+    if cand.dtype not in (torch.int32, torch.int64) or refs.dtype != cand.dtype:
+        raise TensorBLEUError("cand and refs must both be int32 or both int64 "
+                              f"(got {cand.dtype}, {refs.dtype})")
+    if cfg is not None:
+        cfg.token_bytes = 8 if cand.dtype == torch.int64 else 4
     if cand.dim() != 2 or refs.dim() != 3 or refs.shape[0] != cand.shape[0]:
         raise TensorBLEUError("expected cand [B, Lc] and refs [B, R, Lr]")
     B, R = int(cand.shape[0]), int(refs.shape[1])
@@ -205,7 +213,7 @@ def allocate_workspace(B: int, R: int, cand_stride: int, ref_stride: int, cfg: t
 
 
 def _full(entry: str, cand, cand_len, refs, ref_len, cfg, out, stats, workspace, stream):
-    b = _batch(cand, cand_len, refs, ref_len)
+    b = _batch(cand, cand_len, refs, ref_len, cfg)
     if workspace is None:
         workspace = allocate_workspace(b.B, b.R, b.cand_stride, b.ref_stride, cfg, b.cand.device)
     st = stats.as_struct() if stats is not None else None
@@ -239,7 +247,7 @@ def tensorbleu_corpus(cand, cand_len, refs, ref_len, cfg: tb_config_t,
 
 
 def tensorbleu_pack(cand, cand_len, refs, ref_len, cfg, workspace, stats=None, stream=None):
-    b = _batch(cand, cand_len, refs, ref_len)
+    b = _batch(cand, cand_len, refs, ref_len, cfg)
     st = stats.as_struct() if stats is not None else None
     rc = load_library().tensorbleu_pack(
         b.cand.data_ptr(), b.cand_stride, b.cand_len.data_ptr(), b.refs.data_ptr(), b.ref_stride,

@@ -23,6 +23,7 @@ bool config_ok(const tb_config_t* cfg) {
   if (cfg->vocab_size < 1) return false;
   if (cfg->smoothing < TB_SMOOTH_NONE || cfg->smoothing > TB_SMOOTH_EXP) return false;
   if (cfg->force_path < TB_PATH_AUTO || cfg->force_path > TB_PATH_GLOBAL) return false;
+  if (cfg->token_bytes != 0 && cfg->token_bytes != 4 && cfg->token_bytes != 8) return false;
   return true;
 }
 
@@ -88,8 +89,8 @@ struct Call {
   bool want_corpus_stats;
 };
 
-int prepare(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-            const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
+int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+            const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
             const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
             size_t workspace_bytes, void* hip_stream, bool need_tokens, int forced_path,
             Call* c) {
@@ -121,6 +122,7 @@ int prepare(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
   pb.N = cfg->max_n;
   pb.bits = L.bits;
   pb.vocab = cfg->vocab_size;
+  pb.tok64 = cfg->token_bytes == 8;
   pb.status = stats ? stats->device_status : nullptr;
   for (int n = 0; n < 4; ++n) {
     c->ws.keys[n] = (L.path == TB_PATH_GLOBAL && n < pb.N) ? w + L.keys_off[n] : nullptr;
@@ -153,8 +155,8 @@ int prepare(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 
-int run_all(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-            const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
+int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+            const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
             const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats, void* workspace,
             size_t workspace_bytes, void* hip_stream, bool corpus) {
   Call c;
@@ -203,8 +205,8 @@ int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64
   return rc;
 }
 
-int tensorbleu_sentence(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                        const int32_t* refs, int64_t ref_stride, const int32_t* ref_len,
+int tensorbleu_sentence(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                        const void* refs, int64_t ref_stride, const int32_t* ref_len,
                         int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
                         const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                         void* hip_stream) {
@@ -212,16 +214,16 @@ int tensorbleu_sentence(const int32_t* cand, int64_t cand_stride, const int32_t*
                  stats, workspace, workspace_bytes, hip_stream, false);
 }
 
-int tensorbleu_corpus(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                      const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                      const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
                       int32_t R, const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats,
                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   return run_all(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, out_bleu,
                  stats, workspace, workspace_bytes, hip_stream, true);
 }
 
-int tensorbleu_pack(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                    const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+int tensorbleu_pack(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                    const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
                     int32_t R, const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
   Call c;

@@ -109,17 +109,28 @@ __device__ __forceinline__ int block_sum(int v, int* scratch) {
 
 // Problem description handed to every kernel (device pointers + shapes).
 struct Problem {
-  const int32_t* cand;
+  const void* cand;      // int32 or int64 token ids (tok64)
   const int32_t* cand_len;
-  const int32_t* refs;
+  const void* refs;
   const int32_t* ref_len;
   int64_t cand_stride, ref_stride;
   int64_t group_cap;  // cand_stride + R * ref_stride
   int32_t B, R, N;
   int32_t bits;       // ceil(log2(vocab)), >= 1
   int32_t vocab;
+  int32_t tok64;      // token ids are int64
   int32_t* status;    // may be null
 };
+
+// Token `idx` of a token array.  An int64 id that does not fit int32 becomes -1, which every
+// range check reports.
+__device__ __forceinline__ int32_t load_token(const void* base, int64_t idx, int tok64) {
+  if (tok64) {
+    const long long v = static_cast<const long long*>(base)[idx];
+    return (v < 0 || v > 0x7FFFFFFFll) ? -1 : int32_t(v);
+  }
+  return static_cast<const int32_t*>(base)[idx];
+}
 
 // Length of a row as the kernels use it: clamped into [0, stride].
 __device__ __forceinline__ int clamped_len(int len, int64_t stride, int32_t* status) {

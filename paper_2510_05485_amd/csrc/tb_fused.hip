@@ -214,8 +214,8 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
 
   // stage the tokens back to back: candidate, reference 0, reference 1, ...
   {
-    const int32_t* cand_row = pb.cand + int64_t(g) * pb.cand_stride;
-    const int32_t* ref_rows = pb.refs + int64_t(g) * R * pb.ref_stride;
+    const int64_t cand_row = int64_t(g) * pb.cand_stride;
+    const int64_t ref_rows = int64_t(g) * R * pb.ref_stride;
     bool bad = false;
     for (int k = tid; k < total_tokens; k += nt) {
       int j = 0, begin = 0;
@@ -226,7 +226,9 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
         begin = ge ? bm : begin;
       }
       const int p = k - begin;
-      const int32_t t = (j == 0) ? cand_row[p] : ref_rows[int64_t(j - 1) * pb.ref_stride + p];
+      const int32_t t =
+          (j == 0) ? load_token(pb.cand, cand_row + p, pb.tok64)
+                   : load_token(pb.refs, ref_rows + int64_t(j - 1) * pb.ref_stride + p, pb.tok64);
       tok[k] = TokT(t);
       bad |= (uint32_t(t) >= uint32_t(pb.vocab));
     }

@@ -85,18 +85,21 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
   const int per_group = a.cand_chunks + pb.R * a.ref_chunks;
   const int g = blockIdx.x / per_group;
   int rem = blockIdx.x % per_group;
-  const int32_t* row;
+  const void* rows;   // token array and first element of this sequence's row
+  int64_t row;
   int len, chunk, j;
   if (rem < a.cand_chunks) {
     j = 0;
     chunk = rem;
-    row = pb.cand + int64_t(g) * pb.cand_stride;
+    rows = pb.cand;
+    row = int64_t(g) * pb.cand_stride;
     len = clamped_len(pb.cand_len[g], pb.cand_stride, pb.status);
   } else {
     rem -= a.cand_chunks;
     j = 1 + rem / a.ref_chunks;
     chunk = rem % a.ref_chunks;
-    row = pb.refs + (int64_t(g) * pb.R + j - 1) * pb.ref_stride;
+    rows = pb.refs;
+    row = (int64_t(g) * pb.R + j - 1) * pb.ref_stride;
     len = clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, pb.status);
   }
   const int p0 = chunk * kPackTile;
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
   const int ntok = min(kPackTile + 3, len - p0);
   bool bad = false;
   for (int i = threadIdx.x; i < ntok; i += kPackThreads) {
-    const int32_t t = row[p0 + i];
+    const int32_t t = load_token(rows, row + p0 + i, pb.tok64);
     tok[i] = t;
     bad |= (uint32_t(t) >= uint32_t(pb.vocab));
   }

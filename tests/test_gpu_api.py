@@ -1,0 +1,83 @@
+"""GPU tests of int64 token ingestion and of the PyTorch-facing convenience layer."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_05485_amd as tb
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t.to(dtype) if dtype is not None else t
+
+
+@pytest.mark.parametrize("path", ["fused", "global"])
+@pytest.mark.parametrize("config", [1, 4])
+def test_int64_tokens_give_the_same_bits_as_int32(config, path):
+    w = syn.make(config) if config == 1 else syn.config4(B=32)
+    run = w.runs[0]
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing=run.smoothing,
+                      smooth_param=run.smooth_param, threads=8)
+    outs = []
+    for dt in (torch.int32, torch.int64):
+        cfg = tb.make_config(smoothing=run.smoothing, smooth_param=run.smooth_param,
+                             vocab_size=w.vocab, path=path)
+        st = tb.Stats.allocate(w.B, 4, DEV)
+        out = tb.tensorbleu_sentence(dev(w.cand, dt), dev(w.cand_len), dev(w.refs, dt),
+                                     dev(w.ref_len), cfg, stats=st)
+        torch.cuda.synchronize()
+        assert st.device_status.item() == 0
+        np.testing.assert_array_equal(st.clipped.cpu().numpy(), ref.clipped)
+        assert np.abs(out.cpu().numpy() - ref.bleu).max() <= 1e-5
+        outs.append(out.cpu().numpy())
+    np.testing.assert_array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("path", ["fused", "global"])
+def test_int64_ids_beyond_int32_are_flagged(path):
+    w = syn.random_small(301, B=4, R=1, vocab=100, max_len=30, min_len=10)
+    cand = dev(w.cand, torch.int64)
+    cand[1, 2] = 2 ** 40 + 5          # low 32 bits would be a valid id: must not be truncated
+    cfg = tb.make_config(vocab_size=w.vocab, path=path)
+    st = tb.Stats.allocate(w.B, 4, DEV)
+    tb.tensorbleu_sentence(cand, dev(w.cand_len), dev(w.refs, torch.int64), dev(w.ref_len), cfg,
+                           stats=st)
+    torch.cuda.synchronize()
+    assert st.device_status.item() & tb.binding.TB_DEV_TOKEN_RANGE
+
+
+def test_mixed_token_dtypes_are_rejected():
+    w = syn.random_small(302, B=2, R=1, vocab=50, max_len=12, min_len=6)
+    cfg = tb.make_config(vocab_size=w.vocab)
+    with pytest.raises(tb.TensorBLEUError):
+        tb.tensorbleu_sentence(dev(w.cand, torch.int64), dev(w.cand_len), dev(w.refs),
+                               dev(w.ref_len), cfg)
+
+
+def test_scorer_reuses_its_buffers_and_matches_the_oracle():
+    w = syn.config3(B=24)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp", threads=8)
+    scorer = tb.BleuScorer(w.B, w.R, w.cand.shape[1], w.refs.shape[2], vocab_size=w.vocab,
+                           smoothing="exp", device=DEV)
+    cand, refs = dev(w.cand, torch.int64), dev(w.refs, torch.int64)
+    cl, rl = dev(w.cand_len), dev(w.ref_len)
+    first = scorer(cand, cl, refs, rl)
+    ptr = first.data_ptr()
+    for _ in range(3):
+        again = scorer(cand, cl, list(refs.unbind(dim=1)), rl.to(torch.int64))
+    torch.cuda.synchronize()
+    assert again.data_ptr() == ptr
+    assert np.abs(again.cpu().numpy() - ref.bleu).max() <= 1e-5
+    c = scorer.corpus(cand, cl, refs, rl)
+    assert abs(float(c.item()) - ref.corpus_bleu) <= 1e-5
+    one_shot = tb.sentence_bleu(cand, cl, refs, rl, vocab_size=w.vocab, smoothing="exp")
+    np.testing.assert_array_equal(one_shot.cpu().numpy(), again.cpu().numpy())
+    assert abs(float(tb.corpus_bleu(cand, cl, refs, rl, vocab_size=w.vocab,
+                                    smoothing="exp").item()) - ref.corpus_bleu) <= 1e-5
+    with pytest.raises(tb.TensorBLEUError):
+        scorer(cand[:, :100], cl, refs, rl)
