@@ -113,6 +113,9 @@ typedef struct tb_layout {
   size_t  bytes;           /* total workspace size for this path */
   int32_t fused_ok;        /* 1 if the FUSED path supports this shape */
   int32_t global_ok;       /* 1 if the GLOBAL path supports this shape */
+  int32_t global_tables_in_hbm; /* 1 if the group is too large for the LDS kernels: the GLOBAL
+                              path then keeps its hash tables and counters at tables_off */
+  size_t  tables_off;
 } tb_layout_t;
 
 /* Workspace size in bytes for a problem shape (pure host function of the shapes; 0 on invalid

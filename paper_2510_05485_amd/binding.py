@@ -49,7 +49,8 @@ class tb_layout_t(ctypes.Structure):
                 ("clipped_off", ctypes.c_size_t), ("total_off", ctypes.c_size_t),
                 ("closest_off", ctypes.c_size_t), ("distinct_off", ctypes.c_size_t),
                 ("corpus_off", ctypes.c_size_t), ("bytes", ctypes.c_size_t),
-                ("fused_ok", ctypes.c_int32), ("global_ok", ctypes.c_int32)]
+                ("fused_ok", ctypes.c_int32), ("global_ok", ctypes.c_int32),
+                ("global_tables_in_hbm", ctypes.c_int32), ("tables_off", ctypes.c_size_t)]
 
 
 class TensorBLEUError(RuntimeError):

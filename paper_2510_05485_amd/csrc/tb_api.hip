@@ -32,6 +32,8 @@ struct Plans {
   DictPlan dict;
   CountPlan count;
   FusedPlan fused;
+  BigPlan big;
+  bool use_big;  // GLOBAL path with tables in the workspace (group too large for LDS)
 };
 
 // Everything that depends on shapes only.  Returns TB_OK or an error.
@@ -48,8 +50,11 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     return TB_ERR_UNSUPPORTED;
   L.group_cap = cand_stride + int64_t(R) * ref_stride;
   const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
-  L.global_ok = ids_fit && plan_dictionary(L.group_cap, L.key_bytes, N, &p->dict) &&
-                plan_count(L.group_cap, cand_stride, ref_stride, &p->count);
+  const bool lds_ok = plan_dictionary(L.group_cap, L.key_bytes, N, &p->dict) &&
+                      plan_count(L.group_cap, cand_stride, ref_stride, &p->count);
+  p->use_big = !lds_ok && plan_big(L.group_cap, N, &p->big);
+  L.global_ok = ids_fit && (lds_ok || p->use_big);
+  L.global_tables_in_hbm = p->use_big ? 1 : 0;
   L.fused_ok = plan_fused(cand_stride, ref_stride, R, N, L.bits, &p->fused);
   int path = cfg->force_path;
   if (path == TB_PATH_AUTO) path = L.fused_ok ? TB_PATH_FUSED : TB_PATH_GLOBAL;
@@ -73,6 +78,10 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     for (int n = 0; n < N; ++n) {
       L.inv_off[n] = off;
       off = align_up(off + slots * 4);
+    }
+    if (p->use_big) {
+      L.tables_off = off;
+      off = align_up(off + size_t(B) * N * size_t(p->big.table_entries) * 8);
     }
   }
   L.bytes = off < kAlign ? kAlign : off;
@@ -130,6 +139,7 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                        ? reinterpret_cast<uint32_t*>(w + L.inv_off[n]) : nullptr;
     c->ws.wide[n] = L.key_bytes[n] == 16;
   }
+  c->ws.tables = (L.path == TB_PATH_GLOBAL && c->plans.use_big) ? w + L.tables_off : nullptr;
   StatPtrs& st = c->st;
   st.clipped = (stats && stats->clipped) ? stats->clipped
                                          : reinterpret_cast<int32_t*>(w + L.clipped_off);
@@ -155,6 +165,15 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 
+hipError_t run_dictionary(const Call& c) {
+  return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
+                         : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
+}
+hipError_t run_count_clip(const Call& c) {
+  return c.plans.use_big ? launch_big_count_clip(c.pb, c.ws, c.plans.big, c.st, c.stream)
+                         : launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream);
+}
+
 int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
             const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
             const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats, void* workspace,
@@ -177,10 +196,8 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
     return TB_OK;
   }
   if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
-  if ((rc = hip_rc(launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream))) != TB_OK)
-    return rc;
-  if ((rc = hip_rc(launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream))) != TB_OK)
-    return rc;
+  if ((rc = hip_rc(run_dictionary(c))) != TB_OK) return rc;
+  if ((rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
   return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
                                 out_bleu, c.stream));
 }
@@ -241,7 +258,7 @@ int tensorbleu_dictionary(const int32_t* cand_len, const int32_t* ref_len, int64
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
-  return hip_rc(launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream));
+  return hip_rc(run_dictionary(c));
 }
 
 int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,
@@ -252,7 +269,7 @@ int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
-  return hip_rc(launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream));
+  return hip_rc(run_count_clip(c));
 }
 
 int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t B, int32_t R,

@@ -10,6 +10,7 @@ struct GlobalWs {
   void* keys[4];      // packed keys per order, B * group_cap entries of 8 or 16 bytes
   uint32_t* inv[4];   // offset dictionary ids per order, B * group_cap entries
   int32_t wide[4];    // 1 when the order uses 16-byte keys
+  void* tables;       // hash tables / counters in HBM (groups too large for LDS), else null
 };
 
 // Integer statistics (either the caller's arrays or workspace scratch; never null).
@@ -47,6 +48,17 @@ struct FusedPlan {
   int list_per_wave;   // work-list entries reserved per wavefront (multiple of 64)
   size_t lds_bytes, off_ids, off_cnt, off_cstate, off_tok, off_list;
 };
+
+// Groups beyond the LDS plans: table and counters live in the workspace.
+struct BigPlan {
+  int64_t slots;          // hash-table slots per (group, order): power of two >= 2 * group_cap
+  int64_t table_entries;  // slots + padding, 8 bytes each
+};
+bool plan_big(int64_t group_cap, int N, BigPlan* plan);
+hipError_t launch_big_dictionary(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
+                                 const StatPtrs& st, hipStream_t s);
+hipError_t launch_big_count_clip(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
+                                 const StatPtrs& st, hipStream_t s);
 
 bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan);
 bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, CountPlan* plan);

@@ -85,9 +85,15 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.tensorbleu_sentence(*args) == 0
 
 
-def test_group_too_large_for_lds_is_unsupported_not_wrong(lib):
+def test_group_too_large_for_lds_falls_back_to_tables_in_the_workspace(lib):
     cfg = tb.make_config(vocab_size=50257, path="global")
     lay = binding.tb_layout_t()
     rc = lib.tensorbleu_workspace_layout(2, 8, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
-    assert rc == 3 and lay.global_ok == 0
-    assert tb.tensorbleu_workspace_bytes(2, 8, 8192, 8192, cfg) == 0
+    assert rc == 0 and lay.global_ok == 1 and lay.global_tables_in_hbm == 1
+    cap = 9 * 8192
+    slots = 1 << (2 * cap - 1).bit_length()
+    assert lay.bytes >= lay.tables_off + 2 * 4 * (slots + 8) * 8
+    fused = tb.make_config(vocab_size=50257, path="fused")
+    assert lib.tensorbleu_workspace_layout(2, 8, 8192, 8192, ctypes.byref(fused),
+                                           ctypes.byref(lay)) == 3
+    assert tb.tensorbleu_workspace_bytes(2, 8, 8192, 8192, fused) == 0

@@ -226,12 +226,17 @@ def test_sixty_three_references(path):
     check(w, syn.Run("none"), path)
 
 
-def test_oversize_group_is_rejected_not_miscomputed():
-    w = syn.random_small(144, B=1, R=3, vocab=50, max_len=4100, min_len=4000)
-    d = Device(w)
+@pytest.mark.parametrize("vocab", [50, 50257, 262144])
+def test_group_too_large_for_lds_is_scored_with_tables_in_hbm(vocab):
+    # cand_stride + R * ref_stride = 16400 > 12288: neither LDS plan applies
+    w = cached_small(144, B=3, R=3, vocab=vocab, max_len=4100, min_len=3500)
     cfg = tb.make_config(vocab_size=w.vocab, path="auto")
-    with pytest.raises(tb.TensorBLEUError):
-        tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg)
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.fused_ok == 0 and lay.global_ok == 1 and lay.global_tables_in_hbm == 1
+    assert lay.path == 2
+    d = Device(w)
+    for run in (syn.Run("exp"), syn.Run("add-k", 1.0)):
+        check(w, run, "auto", d=d)
 
 
 def test_determinism_of_integer_statistics():
