@@ -81,3 +81,32 @@ def test_scorer_reuses_its_buffers_and_matches_the_oracle():
                                     smoothing="exp").item()) - ref.corpus_bleu) <= 1e-5
     with pytest.raises(tb.TensorBLEUError):
         scorer(cand[:, :100], cl, refs, rl)
+
+
+@pytest.mark.parametrize("path", ["fused", "global"])
+def test_hip_graph_capture_and_replay(path):
+    """The call allocates nothing and never synchronises, so it can be captured in a HIP graph.
+    Every replay (with the inputs rewritten in place between replays) must equal the oracle."""
+    w1 = syn.random_small(401, B=48, R=2, vocab=300, max_len=120, min_len=20)
+    w2 = syn.random_small(402, B=48, R=2, vocab=300, max_len=120, min_len=20)
+    scorer = tb.BleuScorer(w1.B, w1.R, w1.cand.shape[1], w1.refs.shape[2], vocab_size=300,
+                           smoothing="floor", smooth_param=0.1, path=path, device=DEV)
+    cand, cl = dev(w1.cand), dev(w1.cand_len)
+    refs, rl = dev(w1.refs), dev(w1.ref_len)
+    scorer(cand, cl, refs, rl)                      # warm-up outside capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = scorer(cand, cl, refs, rl)
+    for rep, w in enumerate([w1, w2, w1, w2]):
+        cand.copy_(dev(w.cand)); cl.copy_(dev(w.cand_len))
+        refs.copy_(dev(w.refs)); rl.copy_(dev(w.ref_len))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="floor",
+                          smooth_param=0.1)
+        assert np.abs(out.cpu().numpy() - ref.bleu).max() <= 1e-5, (path, rep)
+        eager = tb.sentence_bleu(cand, cl, refs, rl, vocab_size=300, smoothing="floor",
+                                 smooth_param=0.1, path=path)
+        np.testing.assert_array_equal(out.cpu().numpy(), eager.cpu().numpy())
