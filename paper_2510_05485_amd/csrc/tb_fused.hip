@@ -94,12 +94,10 @@ bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
 // The candidate's dictionary of one order: an open-addressing table of 32-bit keys with double
 // hashing.  One 32-bit multiply hashes the key: the top bits of the product pick the slot, lower
 // bits the (odd) probe step, so a probe sequence reaches every slot of the power-of-two table.
-//
-// Both probe loops are written without branches inside: every lane of the wavefront runs the
-// same number of rounds (until no lane is pending, at most `slots` rounds), lanes that are done
-// or inactive keep reading but ignore what they read.  On this hardware the exec-mask
-// bookkeeping of a divergent loop with several exits costs several times more scalar
-// instructions than the probe itself.
+// A probe loop ends at the key or at an empty slot; the table is at most 3/4 full and the probe
+// count is capped at the table size.  (Measured on this hardware: plain divergent loops beat
+// variants that keep all lanes in lock step until the slowest is done, and probing slot pairs
+// or 4-slot buckets with wider LDS reads did not pay either.)
 struct ProbeTable {
   uint32_t* slots;
   uint32_t mask;  // slots - 1
@@ -109,18 +107,20 @@ struct ProbeTable {
 
   // Slot of `key`, or kNotFound.  Lanes with active == false return kNotFound.
   __device__ __forceinline__ uint32_t find(uint32_t key, bool active) const {
-    const uint32_t h = key * 0x9E3779B1u;
-    const uint32_t step = (h >> 3) | 1u;
-    uint32_t s = h >> shift;
     uint32_t found = kNotFound;
-    bool pending = active;
-    for (uint32_t round = 0; round <= mask && __builtin_amdgcn_ballot_w64(pending) != 0;
-         ++round) {
-      const uint32_t e = slots[s];
-      const bool hit = e == key;
-      found = (pending && hit) ? s : found;
-      pending = pending && !hit && e != kEmptySlot;
-      s = (s + step) & mask;
+    if (active) {
+      const uint32_t h = key * 0x9E3779B1u;
+      const uint32_t step = (h >> 3) | 1u;
+      uint32_t s = h >> shift;
+      for (uint32_t round = 0; round <= mask; ++round) {
+        const uint32_t e = slots[s];
+        if (e == key) {
+          found = s;
+          break;
+        }
+        if (e == kEmptySlot) break;
+        s = (s + step) & mask;
+      }
     }
     return found;
   }
@@ -128,23 +128,19 @@ struct ProbeTable {
   // Claim-or-find for active lanes.  Returns the slot; *won is set where this call created
   // the entry.
   __device__ __forceinline__ uint32_t insert(uint32_t key, bool active, bool* won) const {
-    const uint32_t h = key * 0x9E3779B1u;
-    const uint32_t step = (h >> 3) | 1u;
-    uint32_t s = h >> shift;
     uint32_t slot = 0;
     bool created = false;
-    bool pending = active;
-    for (uint32_t round = 0; round <= mask && __builtin_amdgcn_ballot_w64(pending) != 0;
-         ++round) {
-      // a plain read first: duplicates and collisions never pay for the compare-and-swap
-      uint32_t old = slots[s];
-      if (pending && old == kEmptySlot) old = atomicCAS(&slots[s], kEmptySlot, key);
-      const bool claimed = pending && old == kEmptySlot;
-      const bool done = claimed || (pending && old == key);
-      created = created || claimed;
-      slot = done ? s : slot;
-      pending = pending && !done;
-      s = (s + step) & mask;
+    if (active) {
+      const uint32_t h = key * 0x9E3779B1u;
+      const uint32_t step = (h >> 3) | 1u;
+      uint32_t s = h >> shift;
+      for (uint32_t round = 0; round <= mask; ++round) {
+        const uint32_t old = atomicCAS(&slots[s], kEmptySlot, key);
+        created = old == kEmptySlot;
+        if (created || old == key) break;
+        s = (s + step) & mask;
+      }
+      slot = s;
     }
     *won = created;
     return slot;
@@ -256,16 +252,13 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
     if (n >= 2) __syncthreads();  // every slot of the previous order has been emptied
 
     // ---- A: candidate n-grams claim or find their entry
-    for (int k0 = 0; k0 + n <= cand_len; k0 += nt) {
-      const int k = k0 + tid;
-      const bool active = k + n <= cand_len;
-      const int kk = active ? k : 0;
-      const uint32_t pid = (cstate[kk] >> 16) & 0xFFFu;
-      const uint32_t key = (pid << bits) | uint32_t(tok[kk + n - 1]);
+    for (int k = tid; k + n <= cand_len; k += nt) {
+      const uint32_t pid = (cstate[k] >> 16) & 0xFFFu;
+      const uint32_t key = (pid << bits) | uint32_t(tok[k + n - 1]);
       bool won;
-      const uint32_t s = dict.insert(key, active, &won);
+      const uint32_t s = dict.insert(key, true, &won);
       if (won) ids[s] = uint16_t(k);
-      if (active) cstate[k] = s | (won ? 0x80000000u : 0u);
+      cstate[k] = s | (won ? 0x80000000u : 0u);
     }
     __syncthreads();
 #ifdef TB_PHASE_CLOCKS
