@@ -63,6 +63,8 @@ bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
   int t = 256;
   while (t < 1024 && cap > 4 * t) t *= 2;
   plan->threads = t;
+  const int need = int((cap + t - 1) / t);
+  plan->items = need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : 12;
   plan->words = (R + 2) / 2;
   plan->tok_bytes = bits <= 16 ? 2 : 4;
   const int nwaves = t / kWave;
@@ -161,7 +163,8 @@ struct ProbeTable {
 // position, id, sequence index packed in one word -- compacted in its own LDS work list, so the
 // next order runs over full wavefronts; reading and appending stay inside the wavefront and
 // need neither atomics nor extra barriers.
-template <typename TokT>
+// SITEMS: token positions per thread (workgroup size * SITEMS >= tokens of a group).
+template <typename TokT, int SITEMS>
 __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_part[4];              // per order: clipped sum (low 16) | distinct count (high 16)
@@ -201,32 +204,54 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
     s_end[lane] = incl;
   }
   if (tid < 4) s_part[tid] = 0;
-  const int total_tokens = lane_value(incl, R);
+  const int total_tokens = min(lane_value(incl, R), SITEMS * nt);
   const int cand_len = lane_value(my_len, 0);
 
   for (int s = tid; s < T; s += nt) table[s] = kEmptySlot;
   for (int s = tid; s < cand_len * int(W); s += nt) cnt[s] = 0;
   for (int s = tid; s < cand_len; s += nt) cstate[s] = 0;
 
-  // stage the tokens back to back: candidate, reference 0, reference 1, ...
+  // stage the tokens back to back: candidate, reference 0, reference 1, ...  All of a thread's
+  // loads are issued before the first one is consumed (one round trip to memory, not one per
+  // position).
   {
+    int seq[SITEMS], begin[SITEMS];
+#pragma unroll
+    for (int i = 0; i < SITEMS; ++i) {
+      seq[i] = 0;
+      begin[i] = 0;
+    }
+    for (int m = 1; m <= R; ++m) {
+      const int bm = lane_value(incl, m - 1);
+#pragma unroll
+      for (int i = 0; i < SITEMS; ++i) {
+        const bool ge = tid + i * nt >= bm;
+        seq[i] = ge ? m : seq[i];
+        begin[i] = ge ? bm : begin[i];
+      }
+    }
     const int64_t cand_row = int64_t(g) * pb.cand_stride;
     const int64_t ref_rows = int64_t(g) * R * pb.ref_stride;
-    bool bad = false;
-    for (int k = tid; k < total_tokens; k += nt) {
-      int j = 0, begin = 0;
-      for (int m = 1; m <= R; ++m) {
-        const int bm = lane_value(incl, m - 1);
-        const bool ge = k >= bm;
-        j = ge ? m : j;
-        begin = ge ? bm : begin;
+    int32_t t[SITEMS];
+#pragma unroll
+    for (int i = 0; i < SITEMS; ++i) {
+      const int k = tid + i * nt;
+      t[i] = 0;
+      if (k < total_tokens) {
+        const int p = k - begin[i];
+        t[i] = (seq[i] == 0)
+            ? load_token(pb.cand, cand_row + p, pb.tok64)
+            : load_token(pb.refs, ref_rows + int64_t(seq[i] - 1) * pb.ref_stride + p, pb.tok64);
       }
-      const int p = k - begin;
-      const int32_t t =
-          (j == 0) ? load_token(pb.cand, cand_row + p, pb.tok64)
-                   : load_token(pb.refs, ref_rows + int64_t(j - 1) * pb.ref_stride + p, pb.tok64);
-      tok[k] = TokT(t);
-      bad |= (uint32_t(t) >= uint32_t(pb.vocab));
+    }
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < SITEMS; ++i) {
+      const int k = tid + i * nt;
+      if (k < total_tokens) {
+        tok[k] = TokT(t[i]);
+        bad |= (uint32_t(t[i]) >= uint32_t(pb.vocab));
+      }
     }
     if (bad && pb.status) atomicOr(pb.status, TB_DEV_TOKEN_RANGE);
   }
@@ -376,16 +401,29 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   }
 }
 
-template <typename TokT>
-hipError_t launch_fused_tok(const FusedArgs& a, const FusedPlan& plan, int blocks,
-                            hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<TokT>),
+template <typename TokT, int SITEMS>
+hipError_t launch_fused_items(const FusedArgs& a, const FusedPlan& plan, int blocks,
+                              hipStream_t s) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<TokT, SITEMS>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                      int(plan.lds_bytes));
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((fused_kernel<TokT>), dim3(blocks), dim3(plan.threads), plan.lds_bytes, s,
-                     a);
+  hipLaunchKernelGGL((fused_kernel<TokT, SITEMS>), dim3(blocks), dim3(plan.threads),
+                     plan.lds_bytes, s, a);
   return hipGetLastError();
+}
+
+template <typename TokT>
+hipError_t launch_fused_tok(const FusedArgs& a, const FusedPlan& plan, int blocks,
+                            hipStream_t s) {
+  switch (plan.items) {
+    case 2: return launch_fused_items<TokT, 2>(a, plan, blocks, s);
+    case 4: return launch_fused_items<TokT, 4>(a, plan, blocks, s);
+    case 6: return launch_fused_items<TokT, 6>(a, plan, blocks, s);
+    case 8: return launch_fused_items<TokT, 8>(a, plan, blocks, s);
+    case 12: return launch_fused_items<TokT, 12>(a, plan, blocks, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs& st,

@@ -42,6 +42,7 @@ struct CountPlan {
 };
 struct FusedPlan {
   int threads;         // workgroup size
+  int items;           // token positions staged per thread: 2, 4, 6, 8 or 12
   int table_slots;     // power of two >= 4/3 * cand_stride (larger when LDS allows)
   int words;           // 32-bit counter words per id (two 16-bit sequence fields each)
   int tok_bytes;       // staged tokens are 2 bytes when bits <= 16, else 4
