@@ -50,8 +50,8 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     return TB_ERR_UNSUPPORTED;
   L.group_cap = cand_stride + int64_t(R) * ref_stride;
   const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
-  const bool lds_ok = plan_dictionary(L.group_cap, L.key_bytes, N, &p->dict) &&
-                      plan_count(L.group_cap, cand_stride, ref_stride, &p->count);
+  const bool lds_ok = plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
+                      plan_count(L.group_cap, cand_stride, ref_stride, R, &p->count);
   p->use_big = !lds_ok && plan_big(L.group_cap, N, &p->big);
   L.global_ok = ids_fit && (lds_ok || p->use_big);
   L.global_tables_in_hbm = p->use_big ? 1 : 0;

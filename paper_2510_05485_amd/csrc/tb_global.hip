@@ -32,12 +32,31 @@ __device__ __forceinline__ int seq_len(const Problem& pb, int g, int j) {
 // back to a loop.  Must be constructed and queried in wave-uniform control flow.
 class GroupIndex {
  public:
-  __device__ __forceinline__ GroupIndex(const Problem& pb, int g, int n)
-      : pb_(pb), g_(g), n_(n), fast_(pb.R < kWave), incl_(0) {
+  // Issues the loads of the lengths and nothing else: the values are first touched by
+  // set_order(), so loads that the caller issues in between are in flight together with them.
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g)
+      : pb_(pb), g_(g), n_(1), fast_(pb.R < kWave), raw_(0), incl_(0) {
+    if (fast_) load_raw();
+  }
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g, int n) : GroupIndex(pb, g) {
+    set_order(n);
+  }
+  // For kernels that are only launched with fewer than 64 sequences per group: no loop fallback.
+  struct WaveOnly {};
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g, WaveOnly)
+      : pb_(pb), g_(g), n_(1), fast_(true), raw_(0), incl_(0) {
+    load_raw();
+  }
+  __device__ __forceinline__ void set_order(int n) {
+    n_ = n;
     if (fast_) {
       const int lane = threadIdx.x & (kWave - 1);
-      const int cnt = (lane <= pb.R) ? max(seq_len(pb, g, lane) - n + 1, 0) : 0;
-      incl_ = wave_inclusive_scan(cnt);
+      // (readfirstlane keeps the two strides in scalar registers: a select between the two
+      // fields would otherwise be turned into one vector load from a selected address)
+      const int cs = __builtin_amdgcn_readfirstlane(int(min(pb_.cand_stride, int64_t(1) << 30)));
+      const int rs = __builtin_amdgcn_readfirstlane(int(min(pb_.ref_stride, int64_t(1) << 30)));
+      const int len = clamped_len(raw_, lane == 0 ? cs : rs, nullptr);
+      incl_ = wave_inclusive_scan(max(len - n + 1, 0));
     }
   }
   // First slot of sequence j (0 = candidate); j = R + 1 gives the group's n-gram count.
@@ -48,12 +67,23 @@ class GroupIndex {
     for (int jj = 0; jj < j; ++jj) s += max(seq_len(pb_, g_, jj) - n_ + 1, 0);
     return s;
   }
+  // Lane j <= R: one past the last slot of sequence j.  Only when the group has < 64 sequences.
+  __device__ __forceinline__ int end_in_lane() const { return incl_; }
 
  private:
+  // lane j <= R: the stored length of sequence j; other lanes: 0
+  __device__ __forceinline__ void load_raw() {
+    const int lane = threadIdx.x & (kWave - 1);
+    raw_ = 0;
+    if (lane == 0)
+      raw_ = pb_.cand_len[g_];
+    else if (lane <= pb_.R)
+      raw_ = pb_.ref_len[int64_t(g_) * pb_.R + lane - 1];
+  }
   const Problem& pb_;
   int g_, n_;
   bool fast_;
-  int incl_;
+  int raw_, incl_;
 };
 
 // ---------------------------------------------------------------------------------- pack
@@ -150,20 +180,20 @@ hipError_t launch_pack(const Problem& pb, const GlobalWs& ws, hipStream_t s) {
 
 // ---------------------------------------------------------------------------- dictionary
 
-constexpr uint64_t kEmpty64 = ~uint64_t(0);
-
 struct DictArgs {
   Problem pb;
   GlobalWs ws;
   int32_t* distinct;
-  int table_slots;
+  int table_slots;  // 8-byte entries (narrow) or 4-byte entries (wide); power of two
   int table_shift;  // 32 - log2(table_slots)
   uint32_t lds_table_off;
+  int slot32_mask;  // bit n: the keys of order n fit 32 bits
   int orders[4];
   int num_orders;
 };
 
-bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan) {
+bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, int bits,
+                     DictPlan* plan) {
   if (group_cap < 1 || group_cap > 12 * 1024) return false;
   int t = 256;
   while (t < 1024 && group_cap > 4 * t) t *= 2;
@@ -171,11 +201,14 @@ bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPla
   const int need = int((group_cap + t - 1) / t);
   plan->items = need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : 12;
   plan->n_narrow = plan->n_wide = 0;
+  plan->slot32_mask = 0;
   for (int n = 1; n <= N; ++n) {
-    if (key_bytes[n - 1] == 16)
+    if (key_bytes[n - 1] == 16) {
       plan->wide_orders[plan->n_wide++] = n;
-    else
+    } else {
       plan->narrow_orders[plan->n_narrow++] = n;
+      if (n * bits <= 32) plan->slot32_mask |= 1 << n;
+    }
   }
   int slots = 256;
   while (int64_t(slots) * 3 < group_cap * 4) slots <<= 1;
@@ -189,93 +222,114 @@ bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPla
   return ok;
 }
 
-// Number the occupied table entries densely (any bijection onto 0..U-1 is a valid dictionary)
-// and leave each entry's id in the table.  Thread t owns entries t, t+nt, ... so that the LDS
-// accesses are bank-conflict free.  Returns U in every thread.
-template <typename WordT>
-__device__ __forceinline__ int number_entries(WordT* table, int entries, WordT empty,
-                                              int* scan_scratch) {
-  const int nt = blockDim.x, tid = threadIdx.x;
-  int occupied = 0;
-  for (int s = tid; s < entries; s += nt) occupied += (table[s] != empty);
-  int U = 0;
-  int id = block_exclusive_scan(occupied, scan_scratch, &U);
-  for (int s = tid; s < entries; s += nt)
-    if (table[s] != empty) table[s] = WordT(id++);
-  __syncthreads();
-  return U;
+// Dense ids for the table entries this thread created (any bijection onto 0..U-1 is a valid
+// dictionary): every wavefront reserves a block of ids with one LDS atomic, lanes take their
+// share in lane order.  Returns the first id of this thread.  All 64 lanes must be active.
+__device__ __forceinline__ uint32_t reserve_ids(int created, int* next_id) {
+  const int incl = wave_inclusive_scan(created);
+  const int total = lane_value(incl, kWave - 1);
+  int base = 0;
+  if ((threadIdx.x & (kWave - 1)) == 0 && total) base = atomicAdd(next_id, total);
+  return uint32_t(lane_value(base, 0) + incl - created);
 }
 
-// 8-byte keys.  The open-addressing table holds the keys themselves; an insertion is one 64-bit
-// LDS compare-and-swap per probe (double hashing).  All-ones is the empty marker, so the one
-// key with that bit pattern owns the extra entry at index `table_slots`.
-template <int ITEMS>
-__global__ __launch_bounds__(1024) void dictionary_narrow_kernel(DictArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int scan_scratch[17];
+// Keys of at most 64 bits.  The open-addressing table holds the keys themselves, as 4-byte
+// entries when the order's keys fit 32 bits (twice the slots in the same LDS, cheaper atomics)
+// and as 8-byte entries otherwise; an insertion is one LDS compare-and-swap per probe (double
+// hashing).  All-ones is the empty marker, so the one key with that bit pattern owns the extra
+// entry at index T.  The thread whose compare-and-swap created an entry gives it a dense id
+// and, once every insertion is done, replaces the key in the table by that id.
+template <int ITEMS, typename SlotT>
+__device__ __forceinline__ void narrow_dictionary(const DictArgs& a, unsigned char* smem,
+                                                  int* next_id, int g, int n) {
+  constexpr bool kSmall = sizeof(SlotT) == 4;
+  const SlotT kFree = ~SlotT(0);
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
-  const int g = blockIdx.x / a.num_orders;
-  const int n = a.orders[blockIdx.x % a.num_orders];
-  unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
-  const int T = a.table_slots;
+  SlotT* table = reinterpret_cast<SlotT*>(smem);
+  const int T = kSmall ? 2 * a.table_slots : a.table_slots;
+  const int shift = kSmall ? a.table_shift - 1 : a.table_shift;
   const uint32_t mask = uint32_t(T) - 1u;
   const int count = min(GroupIndex(pb, g, n).start(pb.R + 1), ITEMS * nt);
   const uint64_t* gkeys =
       reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
 
-  uint64_t key[ITEMS];
+  SlotT key[ITEMS];
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
-    key[i] = (k < count) ? gkeys[k] : 0;
+    key[i] = (k < count) ? SlotT(gkeys[k]) : SlotT(0);
   }
-  for (int s = tid; s <= T; s += nt) table[s] = kEmpty64;
+  for (int s = tid; s <= T; s += nt) table[s] = kFree;
+  if (tid == 0) *next_id = 0;
   __syncthreads();
 
   uint32_t slot[ITEMS];
+  uint32_t created = 0;  // bit i: this thread's item i created its table entry
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
     slot[i] = 0;
     if (k < count) {
-      if (key[i] == kEmpty64) {
-        table[T] = 0;
+      if (key[i] == kFree) {
+        if (atomicCAS(&table[T], kFree, SlotT(0)) == kFree) created |= 1u << i;
         slot[i] = uint32_t(T);
       } else {
-        const uint32_t lo = uint32_t(key[i]), hi = uint32_t(key[i] >> 32);
-        const uint32_t h = (lo ^ ((hi << 15) | (hi >> 17))) * 0x9E3779B1u;
+        uint32_t h;
+        if (kSmall) {
+          h = uint32_t(key[i]) * 0x9E3779B1u;
+        } else {
+          const uint32_t lo = uint32_t(key[i]), hi = uint32_t(uint64_t(key[i]) >> 32);
+          h = (lo ^ ((hi << 15) | (hi >> 17))) * 0x9E3779B1u;
+        }
         const uint32_t step = (h >> 3) | 1u;
-        uint32_t s = h >> a.table_shift;
+        uint32_t s = h >> shift;
         for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
-          const unsigned long long old = atomicCAS(&table[s], kEmpty64, key[i]);
-          if (old == kEmpty64 || old == key[i]) break;
+          const SlotT old = atomicCAS(&table[s], kFree, key[i]);
+          if (old == kFree) created |= 1u << i;
+          if (old == kFree || old == key[i]) break;
           s = (s + step) & mask;
         }
         slot[i] = s;
       }
     }
   }
+  uint32_t id = reserve_ids(__popc(created), next_id);
+  __syncthreads();  // nobody compares keys any more: entries may now hold ids
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+    if ((created >> i) & 1u) table[slot[i]] = SlotT(id++);
   __syncthreads();
 
-  const int U = number_entries<unsigned long long>(table, T + 1, kEmpty64, scan_scratch);
   const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
     if (k < count) ginv[k] = gbase + uint32_t(table[slot[i]]);
   }
-  if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = U;
+  if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = *next_id;
+}
+
+template <int ITEMS>
+__global__ __launch_bounds__(1024) void dictionary_narrow_kernel(DictArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int next_id;
+  const int g = blockIdx.x / a.num_orders;
+  const int n = a.orders[blockIdx.x % a.num_orders];
+  if ((a.slot32_mask >> n) & 1)
+    narrow_dictionary<ITEMS, uint32_t>(a, smem, &next_id, g, n);
+  else
+    narrow_dictionary<ITEMS, unsigned long long>(a, smem, &next_id, g, n);
 }
 
 // 16-byte keys (n*bits > 64): no 128-bit LDS atomic exists, so the keys are staged in LDS and the
 // table holds fingerprint:position words claimed with a 32-bit compare-and-swap; a fingerprint
-// match is confirmed by comparing the full keys.
+// match is confirmed by comparing the full keys.  Ids as in the narrow kernel.
 template <int ITEMS>
 __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int scan_scratch[17];
+  __shared__ int next_id;
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
   const int g = blockIdx.x / a.num_orders;
@@ -302,6 +356,7 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
     }
   }
   for (int s = tid; s < T; s += nt) table[s] = kEmpty;
+  if (tid == 0) next_id = 0;
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
@@ -310,6 +365,7 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
   __syncthreads();
 
   uint32_t slot[ITEMS];
+  uint32_t created = 0;
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
@@ -320,11 +376,14 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
       const uint32_t step = (h >> 8) | 1u;
       const uint32_t mine = (fp << 16) | uint32_t(k);
       uint32_t s = h & mask;
-      while (true) {
+      for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
         uint32_t w = table[s];
         if (w == kEmpty) {
           w = atomicCAS(&table[s], kEmpty, mine);
-          if (w == kEmpty) break;  // this occurrence now represents its n-gram
+          if (w == kEmpty) {  // this occurrence now represents its n-gram
+            created |= 1u << i;
+            break;
+          }
         }
         if ((w >> 16) == fp && key_eq(skeys[w & 0xFFFFu], key[i])) break;
         s = (s + step) & mask;
@@ -332,16 +391,20 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
       slot[i] = s;
     }
   }
+  uint32_t id = reserve_ids(__popc(created), &next_id);
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+    if ((created >> i) & 1u) table[slot[i]] = id++;
   __syncthreads();
 
-  const int U = number_entries<uint32_t>(table, T, kEmpty, scan_scratch);
   const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
     if (k < count) ginv[k] = gbase + table[slot[i]];
   }
-  if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = U;
+  if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = next_id;
 }
 
 template <template <int> class Launcher, typename... Args>
@@ -388,6 +451,7 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
   a.pb = pb;
   a.ws = ws;
   a.distinct = distinct;
+  a.slot32_mask = 0;
   auto shift_of = [](int slots) {
     int lg = 0;
     while ((1 << lg) < slots) ++lg;
@@ -397,6 +461,7 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
     a.table_slots = plan.narrow_slots;
     a.table_shift = shift_of(plan.narrow_slots);
     a.lds_table_off = 0;
+    a.slot32_mask = plan.slot32_mask;
     a.num_orders = plan.n_narrow;
     for (int k = 0; k < 4; ++k) a.orders[k] = plan.narrow_orders[k];
     hipError_t e = dispatch_items<NarrowLauncher>(plan.items, a, int64_t(pb.B) * plan.n_narrow,
@@ -422,9 +487,21 @@ struct CountArgs {
   Problem pb;
   GlobalWs ws;
   StatPtrs st;
+  int words;  // count_fields_kernel: 32-bit words per dictionary entry
+  int split;  // count_fields_kernel: workgroups per group; workgroup r of a group handles the
+              // orders r + 1, r + 1 + split, ...
 };
 
-bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, CountPlan* plan) {
+// Workgroups per group for a kernel that walks several orders: one when the groups alone fill
+// the GPU, more when the batch is small.
+static int order_split(int B, int N) {
+  int split = 1;
+  while (split < N && int64_t(B) * split < 384) split *= 2;
+  return split < N ? split : N;
+}
+
+bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R,
+                CountPlan* plan) {
   // every counter is a 16-bit field of an LDS word
   if (group_cap < 1 || group_cap > 12 * 1024 || ref_stride > 65535 || cand_stride > 65535)
     return false;
@@ -433,12 +510,144 @@ bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, Coun
   plan->threads = t;
   const int need = int((group_cap + t - 1) / t);
   plan->items = need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : 12;
-  plan->lds_bytes = size_t(group_cap) * 8;
+  // one field per sequence when that fits (and the wave-wide sequence lookup applies), else
+  // the two-references-at-a-time kernel
+  plan->words = (R + 2) / 2;
+  const size_t field_lds = (size_t(group_cap) * plan->words * 4 + 15) & ~size_t(15);
+  plan->fields = R < kWave - 1 && field_lds + 256 <= size_t(kLdsBudget) / 2;
+  plan->lds_bytes = plan->fields ? field_lds : size_t(group_cap) * 8;
   return plan->lds_bytes + 256 <= size_t(kLdsBudget);
 }
 
-// One workgroup per (group, order).  All of the group's offset ids are fetched into registers in
-// one round trip; LDS holds two words per dictionary entry:
+// One workgroup per group walks the orders n = first, first + split, ... (at most four).  Every
+// global load of the workgroup - lengths, dictionary sizes, the offset ids of all its orders -
+// is issued before the first one is consumed, so the workgroup waits for memory once.
+// A dictionary entry owns `words` LDS words holding one 16-bit counter per sequence of the
+// group (field 0: candidate, field 1 + j: reference j).  One LDS atomic add per n-gram
+// occurrence.  The candidate occurrence whose add finds its field at zero is the first of its
+// n-gram; after the barrier it alone clips the entry (maximum over the reference fields,
+// minimum with the candidate field), so no sweep over the table is needed.
+template <int ITEMS>
+__global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int clipped_sum[4];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int g = blockIdx.x / a.split;
+  const int first_order = blockIdx.x % a.split + 1;
+  const int cap = int(pb.group_cap);
+  const int W = a.words;
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
+  const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
+
+  GroupIndex gi(pb, g, GroupIndex::WaveOnly{});  // the loads of the lengths go out first
+  int U4[4], total4[4] = {0, 0, 0, 0};
+  uint32_t id[4][ITEMS];
+  // The id loads go out before the group's n-gram counts are known (those need the lengths):
+  // every slot of the group's range exists, slots past the count hold stale bytes that are never
+  // used.  They are unconditional (clamped slot, clamped order) so that the hardware's in-order
+  // load counter lets an order start as soon as its own ids have arrived; the ids of order o + 1
+  // are requested when order o starts, which spreads the memory traffic over the kernel.
+  auto request_ids = [&](int o) {
+    const int n = min(first_order + o * a.split, pb.N);
+    const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) id[o][i] = ginv[min(tid + i * nt, cap - 1)];
+  };
+  request_ids(0);
+#pragma unroll
+  for (int o = 0; o < 4; ++o)
+    U4[o] = a.st.distinct[int64_t(g) * pb.N + min(first_order + o * a.split, pb.N) - 1];
+  if (tid < 4) clipped_sum[tid] = 0;
+  const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
+
+#pragma unroll
+  for (int o = 0; o < 4; ++o) {
+    const int n = first_order + o * a.split;
+    if (n > pb.N) break;
+    if (o < 3) request_ids(o + 1);
+    const int U = min(max(U4[o], 0), cap);
+    gi.set_order(n);
+    const int count = min(gi.start(pb.R + 1), ITEMS * nt);
+    const int ccnt = gi.start(1);
+    if (o > 0) __syncthreads();  // the previous order's entries have been clipped
+    {
+      uint4* c4 = reinterpret_cast<uint4*>(cnt);
+      const int quads = (U * W + 3) / 4;
+      for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    __syncthreads();
+
+    // Sequence of a slot = number of sequences that end at or before it.  A wavefront's slots
+    // of one item are 64 consecutive ones, so that number is usually the same for all lanes and
+    // is found with one ballot over the lanes holding the sequence ends.
+    const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
+    uint32_t first = 0;  // bit i: item i is the first occurrence of its candidate n-gram
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int k0 = wave_first + i * nt;
+      if (k0 >= count) break;
+      const int f = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0));  // <= R: k0 < count
+      const int f_end = __builtin_amdgcn_readlane(seq_end, f);
+      const uint32_t u = id[o][i] - gbase;
+      if (k0 + kWave <= f_end) {  // the whole wavefront is inside sequence f
+        if (u < uint32_t(U)) {
+          uint32_t* word = &cnt[__umul24(u, uint32_t(W)) + uint32_t(f >> 1)];
+          if (f == 0) {
+            if ((atomicAdd(word, 1u) & 0xFFFFu) == 0u) first |= 1u << i;
+          } else {
+            atomicAdd(word, (f & 1) ? 0x10000u : 1u);
+          }
+        }
+      } else {  // the wavefront straddles sequences: sequence per lane
+        const int k = k0 + lane;
+        const int f_hi = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0 + kWave - 1));
+        int fl = f;
+        for (int j = f; j < f_hi; ++j) fl += (k >= __builtin_amdgcn_readlane(seq_end, j));
+        if (fl <= pb.R && u < uint32_t(U)) {
+          uint32_t* word = &cnt[__umul24(u, uint32_t(W)) + uint32_t(fl >> 1)];
+          if (fl == 0) {
+            if ((atomicAdd(word, 1u) & 0xFFFFu) == 0u) first |= 1u << i;
+          } else {
+            atomicAdd(word, (fl & 1) ? 0x10000u : 1u);
+          }
+        }
+      }
+    }
+    __syncthreads();
+
+    int part = 0;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      if ((first >> i) & 1u) {
+        const uint32_t* e = &cnt[__umul24(id[o][i] - gbase, uint32_t(W))];
+        const uint32_t w0 = e[0];
+        uint32_t m = w0 >> 16;
+        for (int q = 1; q < W; ++q) {
+          const uint32_t w = e[q];
+          m = max(m, max(w & 0xFFFFu, w >> 16));
+        }
+        part += int(min(w0 & 0xFFFFu, m));
+      }
+    }
+    part = wave_sum(part);
+    if (lane == 0 && part) atomicAdd(&clipped_sum[o], part);
+    total4[o] = ccnt;
+  }
+  __syncthreads();
+  if (tid < 4) {
+    const int n = first_order + tid * a.split;
+    if (n <= pb.N) {
+      a.st.clipped[int64_t(g) * pb.N + n - 1] = clipped_sum[tid];
+      a.st.total[int64_t(g) * pb.N + n - 1] =
+          tid == 0 ? total4[0] : tid == 1 ? total4[1] : tid == 2 ? total4[2] : total4[3];
+    }
+  }
+}
+
+// Fallback for groups whose per-sequence fields do not fit.  One workgroup per (group, order).
+// All of the group's offset ids are fetched into registers in one round trip; LDS holds two
+// words per dictionary entry:
 //   acc[u] = candidate count (low 16 bits) | maximum reference count so far (high 16 bits)
 //   cur[u] = counts of the two references being histogrammed (16 bits each)
 // References are histogrammed two at a time with LDS atomic adds and folded into the maximum.
@@ -518,6 +727,13 @@ __global__ __launch_bounds__(1024) void count_clip_kernel(CountArgs a) {
 }
 
 template <int ITEMS>
+struct FieldCountLauncher {
+  static hipError_t run(const CountArgs& a, int64_t blocks, int threads, size_t lds,
+                        hipStream_t s) {
+    return launch_with_lds(count_fields_kernel<ITEMS>, a, blocks, threads, lds, s);
+  }
+};
+template <int ITEMS>
 struct CountLauncher {
   static hipError_t run(const CountArgs& a, int64_t blocks, int threads, size_t lds,
                         hipStream_t s) {
@@ -531,6 +747,11 @@ hipError_t launch_count_clip(const Problem& pb, const GlobalWs& ws, const CountP
   a.pb = pb;
   a.ws = ws;
   a.st = st;
+  a.words = plan.words;
+  a.split = order_split(pb.B, pb.N);
+  if (plan.fields)
+    return dispatch_items<FieldCountLauncher>(plan.items, a, int64_t(pb.B) * a.split,
+                                              plan.threads, plan.lds_bytes, s);
   return dispatch_items<CountLauncher>(plan.items, a, int64_t(pb.B) * pb.N, plan.threads,
                                        plan.lds_bytes, s);
 }

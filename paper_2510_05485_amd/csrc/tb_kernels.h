@@ -29,6 +29,7 @@ struct DictPlan {
   int items;            // register-resident n-grams per thread: 2, 4, 6, 8 or 12
   int narrow_orders[4]; // orders with 8-byte keys, and how many
   int n_narrow;
+  int slot32_mask;      // bit n: order n's keys fit 32 bits (4-byte table entries, 2x the slots)
   int narrow_slots;     // hash-table slots (power of two, >= 4/3 group_cap), 8-byte entries
   size_t narrow_lds;
   int wide_orders[4];   // orders with 16-byte keys
@@ -38,6 +39,8 @@ struct DictPlan {
 };
 struct CountPlan {
   int threads, items;
+  int fields;   // 1: one 16-bit LDS field per sequence (count_fields_kernel); 0: pair phases
+  int words;    // 32-bit words per dictionary entry in the fields kernel
   size_t lds_bytes;
 };
 struct FusedPlan {
@@ -61,8 +64,10 @@ hipError_t launch_big_dictionary(const Problem& pb, const GlobalWs& ws, const Bi
 hipError_t launch_big_count_clip(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
                                  const StatPtrs& st, hipStream_t s);
 
-bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, DictPlan* plan);
-bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, CountPlan* plan);
+bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, int bits,
+                     DictPlan* plan);
+bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R,
+                CountPlan* plan);
 bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
                 FusedPlan* plan);
 
