@@ -188,8 +188,9 @@ struct DictArgs {
   int table_shift;  // 32 - log2(table_slots)
   uint32_t lds_table_off;
   int slot32_mask;  // bit n: the keys of order n fit 32 bits
-  int orders[4];
-  int num_orders;
+  int orders[8];   // wide kernel: its orders; narrow kernel: pairs (orders[2p], orders[2p + 1])
+  int num_orders;  // wide kernel
+  int num_pairs;   // narrow kernel: workgroups per group
 };
 
 bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, int bits,
@@ -214,7 +215,9 @@ bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, int bit
   while (int64_t(slots) * 3 < group_cap * 4) slots <<= 1;
   plan->narrow_slots = plan->wide_slots = slots;
   plan->narrow_lds = size_t(slots + 1) * 8;
-  plan->wide_table_off = size_t(group_cap) * 16;
+  // every 16-byte order within 64 + 18 bits and 13-bit positions: stage the low halves only
+  plan->wide_compact = group_cap <= 8192 && N * bits <= 64 + 18;
+  plan->wide_table_off = size_t(group_cap) * (plan->wide_compact ? 8 : 16);
   plan->wide_lds = plan->wide_table_off + size_t(slots) * 4;
   bool ok = true;
   if (plan->n_narrow) ok = ok && plan->narrow_lds + 256 <= size_t(kLdsBudget);
@@ -239,9 +242,12 @@ __device__ __forceinline__ uint32_t reserve_ids(int created, int* next_id) {
 // hashing).  All-ones is the empty marker, so the one key with that bit pattern owns the extra
 // entry at index T.  The thread whose compare-and-swap created an entry gives it a dense id
 // and, once every insertion is done, replaces the key in the table by that id.
+// `key` holds this thread's keys of the order (already in registers), `count` the group's
+// number of n-grams of the order.  Starts and ends with the table free for reuse.
 template <int ITEMS, typename SlotT>
 __device__ __forceinline__ void narrow_dictionary(const DictArgs& a, unsigned char* smem,
-                                                  int* next_id, int g, int n) {
+                                                  int* next_id, int g, int n,
+                                                  const uint64_t (&key64)[ITEMS], int count) {
   constexpr bool kSmall = sizeof(SlotT) == 4;
   const SlotT kFree = ~SlotT(0);
   const Problem& pb = a.pb;
@@ -250,17 +256,8 @@ __device__ __forceinline__ void narrow_dictionary(const DictArgs& a, unsigned ch
   const int T = kSmall ? 2 * a.table_slots : a.table_slots;
   const int shift = kSmall ? a.table_shift - 1 : a.table_shift;
   const uint32_t mask = uint32_t(T) - 1u;
-  const int count = min(GroupIndex(pb, g, n).start(pb.R + 1), ITEMS * nt);
-  const uint64_t* gkeys =
-      reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
 
-  SlotT key[ITEMS];
-#pragma unroll
-  for (int i = 0; i < ITEMS; ++i) {
-    const int k = tid + i * nt;
-    key[i] = (k < count) ? SlotT(gkeys[k]) : SlotT(0);
-  }
   for (int s = tid; s <= T; s += nt) table[s] = kFree;
   if (tid == 0) *next_id = 0;
   __syncthreads();
@@ -272,23 +269,24 @@ __device__ __forceinline__ void narrow_dictionary(const DictArgs& a, unsigned ch
     const int k = tid + i * nt;
     slot[i] = 0;
     if (k < count) {
-      if (key[i] == kFree) {
+      const SlotT key = SlotT(key64[i]);
+      if (key == kFree) {
         if (atomicCAS(&table[T], kFree, SlotT(0)) == kFree) created |= 1u << i;
         slot[i] = uint32_t(T);
       } else {
         uint32_t h;
         if (kSmall) {
-          h = uint32_t(key[i]) * 0x9E3779B1u;
+          h = uint32_t(key) * 0x9E3779B1u;
         } else {
-          const uint32_t lo = uint32_t(key[i]), hi = uint32_t(uint64_t(key[i]) >> 32);
+          const uint32_t lo = uint32_t(key), hi = uint32_t(uint64_t(key) >> 32);
           h = (lo ^ ((hi << 15) | (hi >> 17))) * 0x9E3779B1u;
         }
         const uint32_t step = (h >> 3) | 1u;
         uint32_t s = h >> shift;
         for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
-          const SlotT old = atomicCAS(&table[s], kFree, key[i]);
+          const SlotT old = atomicCAS(&table[s], kFree, key);
           if (old == kFree) created |= 1u << i;
-          if (old == kFree || old == key[i]) break;
+          if (old == kFree || old == key) break;
           s = (s + step) & mask;
         }
         slot[i] = s;
@@ -309,24 +307,68 @@ __device__ __forceinline__ void narrow_dictionary(const DictArgs& a, unsigned ch
     if (k < count) ginv[k] = gbase + uint32_t(table[slot[i]]);
   }
   if (tid == 0) a.distinct[int64_t(g) * pb.N + n - 1] = *next_id;
+  __syncthreads();  // ids read, next_id read: table and counter are free again
 }
 
+// One workgroup builds the dictionaries of up to two orders of one group, one after the other
+// in the same LDS.  The keys of both orders are requested together, so the second order never
+// waits for memory; the host pairs a cheap order with an expensive one.
 template <int ITEMS>
 __global__ __launch_bounds__(1024) void dictionary_narrow_kernel(DictArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int next_id;
-  const int g = blockIdx.x / a.num_orders;
-  const int n = a.orders[blockIdx.x % a.num_orders];
-  if ((a.slot32_mask >> n) & 1)
-    narrow_dictionary<ITEMS, uint32_t>(a, smem, &next_id, g, n);
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int g = blockIdx.x / a.num_pairs;
+  const int pair = blockIdx.x % a.num_pairs;
+  const int n0 = a.orders[2 * pair], n1 = a.orders[2 * pair + 1];  // n1 = 0: single order
+  GroupIndex gi(pb, g);
+  gi.set_order(n0);
+  const int count0 = min(gi.start(pb.R + 1), ITEMS * nt);
+  int count1 = 0;
+  if (n1) {
+    gi.set_order(n1);
+    count1 = min(gi.start(pb.R + 1), ITEMS * nt);
+  }
+  uint64_t key0[ITEMS], key1[ITEMS];
+  {
+    const uint64_t* gkeys =
+        reinterpret_cast<const uint64_t*>(a.ws.keys[n0 - 1]) + int64_t(g) * pb.group_cap;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int k = tid + i * nt;
+      key0[i] = (k < count0) ? gkeys[k] : 0;
+    }
+  }
+  {
+    const uint64_t* gkeys =
+        reinterpret_cast<const uint64_t*>(a.ws.keys[max(n1, 1) - 1]) + int64_t(g) * pb.group_cap;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int k = tid + i * nt;
+      key1[i] = (k < count1) ? gkeys[k] : 0;
+    }
+  }
+  if ((a.slot32_mask >> n0) & 1)
+    narrow_dictionary<ITEMS, uint32_t>(a, smem, &next_id, g, n0, key0, count0);
   else
-    narrow_dictionary<ITEMS, unsigned long long>(a, smem, &next_id, g, n);
+    narrow_dictionary<ITEMS, unsigned long long>(a, smem, &next_id, g, n0, key0, count0);
+  if (n1 == 0) return;
+  if ((a.slot32_mask >> n1) & 1)
+    narrow_dictionary<ITEMS, uint32_t>(a, smem, &next_id, g, n1, key1, count1);
+  else
+    narrow_dictionary<ITEMS, unsigned long long>(a, smem, &next_id, g, n1, key1, count1);
 }
 
 // 16-byte keys (n*bits > 64): no 128-bit LDS atomic exists, so the keys are staged in LDS and the
-// table holds fingerprint:position words claimed with a 32-bit compare-and-swap; a fingerprint
-// match is confirmed by comparing the full keys.  Ids as in the narrow kernel.
-template <int ITEMS>
+// table holds 32-bit words claimed with a compare-and-swap that name the position of the
+// occurrence representing the n-gram.  Ids as in the narrow kernel.
+//   COMPACT (keys of at most 64 + 18 bits, groups of at most 8192 n-grams): the word is the
+//     key's bits above 64 next to a 13-bit position, and only the low 64 bits are staged, which
+//     halves the LDS; a match compares those bits exactly and then the staged low halves.
+//   otherwise: a 16-bit fingerprint next to a 16-bit position; a fingerprint match is confirmed
+//     on the staged 128-bit keys.
+template <int ITEMS, bool COMPACT>
 __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int next_id;
@@ -335,6 +377,7 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
   const int g = blockIdx.x / a.num_orders;
   const int n = a.orders[blockIdx.x % a.num_orders];
   Key128* skeys = reinterpret_cast<Key128*>(smem);
+  uint64_t* slow = reinterpret_cast<uint64_t*>(smem);  // COMPACT: low halves only
   uint32_t* table = reinterpret_cast<uint32_t*>(smem + a.lds_table_off);
   const int T = a.table_slots;
   const uint32_t mask = uint32_t(T) - 1u;
@@ -360,7 +403,12 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
     const int k = tid + i * nt;
-    if (k < count) skeys[k] = key[i];
+    if (k < count) {
+      if (COMPACT)
+        slow[k] = key[i].lo;
+      else
+        skeys[k] = key[i];
+    }
   }
   __syncthreads();
 
@@ -372,9 +420,10 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
     slot[i] = 0;
     if (k < count) {
       const uint32_t h = key_hash(key[i]);
-      const uint32_t fp = h >> 16;
       const uint32_t step = (h >> 8) | 1u;
-      const uint32_t mine = (fp << 16) | uint32_t(k);
+      // COMPACT: the high bits are < 2^18, so the word never equals the empty marker
+      const uint32_t tag = COMPACT ? uint32_t(key[i].hi) : h >> 16;
+      const uint32_t mine = COMPACT ? (tag << 13) | uint32_t(k) : (tag << 16) | uint32_t(k);
       uint32_t s = h & mask;
       for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
         uint32_t w = table[s];
@@ -385,7 +434,11 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
             break;
           }
         }
-        if ((w >> 16) == fp && key_eq(skeys[w & 0xFFFFu], key[i])) break;
+        if (COMPACT) {
+          if ((w >> 13) == tag && slow[w & 0x1FFFu] == key[i].lo) break;
+        } else {
+          if ((w >> 16) == tag && key_eq(skeys[w & 0xFFFFu], key[i])) break;
+        }
         s = (s + step) & mask;
       }
       slot[i] = s;
@@ -441,7 +494,14 @@ template <int ITEMS>
 struct WideLauncher {
   static hipError_t run(const DictArgs& a, int64_t blocks, int threads, size_t lds,
                         hipStream_t s) {
-    return launch_with_lds(dictionary_wide_kernel<ITEMS>, a, blocks, threads, lds, s);
+    return launch_with_lds(dictionary_wide_kernel<ITEMS, false>, a, blocks, threads, lds, s);
+  }
+};
+template <int ITEMS>
+struct CompactWideLauncher {
+  static hipError_t run(const DictArgs& a, int64_t blocks, int threads, size_t lds,
+                        hipStream_t s) {
+    return launch_with_lds(dictionary_wide_kernel<ITEMS, true>, a, blocks, threads, lds, s);
   }
 };
 
@@ -462,9 +522,28 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
     a.table_shift = shift_of(plan.narrow_slots);
     a.lds_table_off = 0;
     a.slot32_mask = plan.slot32_mask;
-    a.num_orders = plan.n_narrow;
-    for (int k = 0; k < 4; ++k) a.orders[k] = plan.narrow_orders[k];
-    hipError_t e = dispatch_items<NarrowLauncher>(plan.items, a, int64_t(pb.B) * plan.n_narrow,
+    // Pairs of about equal cost (cost grows with the order): four orders -> (1st, 4th) and
+    // (2nd, 3rd).  An odd number of orders would leave workgroups of unequal length, which
+    // measured slower than one order per workgroup; a small batch keeps one order per workgroup
+    // so that the GPU still fills.
+    const int m = plan.n_narrow;
+    const bool pairs = int64_t(pb.B) * m >= 1024 && m % 2 == 0;
+    int np = 0;
+    auto add = [&](int first, int second) {
+      a.orders[2 * np] = plan.narrow_orders[first];
+      a.orders[2 * np + 1] = second >= 0 ? plan.narrow_orders[second] : 0;
+      ++np;
+    };
+    if (!pairs) {
+      for (int k = 0; k < m; ++k) add(k, -1);
+    } else if (m == 4) {
+      add(0, 3);
+      add(1, 2);
+    } else {
+      add(0, 1);
+    }
+    a.num_pairs = np;
+    hipError_t e = dispatch_items<NarrowLauncher>(plan.items, a, int64_t(pb.B) * a.num_pairs,
                                                   plan.threads, plan.narrow_lds, s);
     if (e != hipSuccess) return e;
   }
@@ -474,8 +553,12 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
     a.lds_table_off = uint32_t(plan.wide_table_off);
     a.num_orders = plan.n_wide;
     for (int k = 0; k < 4; ++k) a.orders[k] = plan.wide_orders[k];
-    hipError_t e = dispatch_items<WideLauncher>(plan.items, a, int64_t(pb.B) * plan.n_wide,
-                                                plan.threads, plan.wide_lds, s);
+    const int64_t blocks = int64_t(pb.B) * plan.n_wide;
+    hipError_t e = plan.wide_compact
+                       ? dispatch_items<CompactWideLauncher>(plan.items, a, blocks, plan.threads,
+                                                             plan.wide_lds, s)
+                       : dispatch_items<WideLauncher>(plan.items, a, blocks, plan.threads,
+                                                      plan.wide_lds, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

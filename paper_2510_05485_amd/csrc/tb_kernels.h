@@ -34,7 +34,8 @@ struct DictPlan {
   size_t narrow_lds;
   int wide_orders[4];   // orders with 16-byte keys
   int n_wide;
-  int wide_slots;       // 4-byte fingerprint:position entries
+  int wide_slots;       // 4-byte tag:position entries
+  int wide_compact;     // 1: keys within 64 + 18 bits, only their low halves are staged in LDS
   size_t wide_lds, wide_table_off;
 };
 struct CountPlan {
