@@ -602,9 +602,9 @@ bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int 
   return plan->lds_bytes + 256 <= size_t(kLdsBudget);
 }
 
-// One workgroup per group walks the orders n = first, first + split, ... (at most four).  Every
-// global load of the workgroup - lengths, dictionary sizes, the offset ids of all its orders -
-// is issued before the first one is consumed, so the workgroup waits for memory once.
+// One workgroup per group walks the orders n = first, first + split, ... (at most four); the
+// offset ids of the next order are requested while the current one is counted, so only the
+// first order of a workgroup waits for memory.
 // A dictionary entry owns `words` LDS words holding one 16-bit counter per sequence of the
 // group (field 0: candidate, field 1 + j: reference j).  One LDS atomic add per n-gram
 // occurrence.  The candidate occurrence whose add finds its field at zero is the first of its
