@@ -39,7 +39,7 @@ def needs_build() -> bool:
 
 def build(verbose: bool = True) -> str:
     tmp = LIB + f".tmp{os.getpid()}"
-    extra = os.environ.get("TB_HIPCC_EXTRA", "").split()   # e.g. -DTB_PHASE_CLOCKS for profiling
+    extra = os.environ.get("TB_HIPCC_EXTRA", "").split()   # extra hipcc flags for experiments
     cmd = [HIPCC, *FLAGS, *extra, "-I", INCLUDE, "-I", CSRC, "-o", tmp, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -172,7 +172,9 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   __shared__ int s_end[kMaxFusedSeqs];   // end of each sequence in back-to-back token indices
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
-  const int lane = tid & (kWave - 1), wave = tid / kWave, nwaves = nt / kWave;
+  const int lane = tid & (kWave - 1), nwaves = nt / kWave;
+  // the wavefront's index as a scalar: loop bounds derived from it stay in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int g = blockIdx.x;
   const int R = pb.R, N = pb.N, T = a.table_slots;
   const uint32_t W = uint32_t(a.words);
@@ -184,11 +186,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   uint32_t* my_list = reinterpret_cast<uint32_t*>(smem + a.off_list) + wave * a.list_per_wave;
   const ProbeTable dict{table, uint32_t(T) - 1u, a.table_shift};
   const int bits = pb.bits;
-#ifdef TB_PHASE_CLOCKS
-  long long ts[14];
-  int nts = 0;
-  ts[nts++] = clock64();
-#endif
 
   // lane j of every wavefront: length of sequence j and the inclusive prefix of lengths
   int my_len = 0;
@@ -268,9 +265,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
     f_hi += (slice_begin + todo - 1 >= bm) ? 1 : 0;
   }
   __syncthreads();
-#ifdef TB_PHASE_CLOCKS
-  ts[nts++] = clock64();
-#endif
 
 #pragma unroll 1
   for (int n = 1; n <= N; ++n) {
@@ -286,9 +280,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
       cstate[k] = s | (won ? 0x80000000u : 0u);
     }
     __syncthreads();
-#ifdef TB_PHASE_CLOCKS
-    if (n <= 4) ts[nts++] = clock64();
-#endif
 
     // ---- B: candidate counts (field 0 of the entry's id) ...
     for (int k = tid; k + n <= cand_len; k += nt) {
@@ -334,9 +325,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
     }
     todo = kept;
     __syncthreads();
-#ifdef TB_PHASE_CLOCKS
-    if (n <= 4) ts[nts++] = clock64();
-#endif
 
     // ---- C: the position that created an entry clips it (max over the reference fields, min
     // with the candidate field), zeroes its counters and empties its slot
@@ -359,9 +347,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
     }
     part = wave_sum(part);
     if (lane == 0 && part != 0) atomicAdd(&s_part[n - 1], part);
-#ifdef TB_PHASE_CLOCKS
-    if (n <= 4) ts[nts++] = clock64();
-#endif
   }
   __syncthreads();
 
@@ -389,15 +374,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
     }
     a.st.closest[g] = best;
     if (a.out) a.out[g] = bleu_from_stats<int>(clipped, total, c, best, a.sp);
-#ifdef TB_PHASE_CLOCKS
-    for (int q = 0; q < 4; ++q) {
-      a.st.clipped[int64_t(g) * N + q] = int(ts[2 + 3 * q] - ts[1 + 3 * q]);
-      a.st.total[int64_t(g) * N + q] = int(ts[3 + 3 * q] - ts[2 + 3 * q]);
-      a.st.distinct[int64_t(g) * N + q] = int(ts[4 + 3 * q] - ts[3 + 3 * q]);
-    }
-    a.st.closest[g] = int(ts[1] - ts[0]);
-    a.out[g] = float(clock64() - ts[0]);
-#endif
   }
 }
 
