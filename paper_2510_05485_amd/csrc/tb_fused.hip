@@ -114,15 +114,14 @@ struct ProbeTable {
       const uint32_t h = key * 0x9E3779B1u;
       const uint32_t step = (h >> 3) | 1u;
       uint32_t s = h >> shift;
-      for (uint32_t round = 0; round <= mask; ++round) {
-        const uint32_t e = slots[s];
-        if (e == key) {
-          found = s;
-          break;
-        }
-        if (e == kEmptySlot) break;
+      uint32_t e = slots[s];
+      int rounds = 0;  // the same in every lane still probing: kept in a scalar register
+      while (int(e != key) & int(e != kEmptySlot) & int(uint32_t(rounds) < mask)) {
         s = (s + step) & mask;
+        e = slots[s];
+        rounds = __builtin_amdgcn_readfirstlane(rounds) + 1;
       }
+      found = (e == key) ? s : kNotFound;
     }
     return found;
   }
@@ -136,12 +135,14 @@ struct ProbeTable {
       const uint32_t h = key * 0x9E3779B1u;
       const uint32_t step = (h >> 3) | 1u;
       uint32_t s = h >> shift;
-      for (uint32_t round = 0; round <= mask; ++round) {
-        const uint32_t old = atomicCAS(&slots[s], kEmptySlot, key);
-        created = old == kEmptySlot;
-        if (created || old == key) break;
+      uint32_t old = atomicCAS(&slots[s], kEmptySlot, key);
+      int rounds = 0;
+      while (int(old != kEmptySlot) & int(old != key) & int(uint32_t(rounds) < mask)) {
         s = (s + step) & mask;
+        old = atomicCAS(&slots[s], kEmptySlot, key);
+        rounds = __builtin_amdgcn_readfirstlane(rounds) + 1;
       }
+      created = old == kEmptySlot;
       slot = s;
     }
     *won = created;
