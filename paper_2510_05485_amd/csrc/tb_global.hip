@@ -283,12 +283,14 @@ __device__ __forceinline__ void narrow_dictionary(const DictArgs& a, unsigned ch
         }
         const uint32_t step = (h >> 3) | 1u;
         uint32_t s = h >> shift;
-        for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
-          const SlotT old = atomicCAS(&table[s], kFree, key);
-          if (old == kFree) created |= 1u << i;
-          if (old == kFree || old == key) break;
+        SlotT old = atomicCAS(&table[s], kFree, key);
+        int rounds = 0;  // equal in all lanes still probing (scalar); T probes reach every slot
+        while (int(old != kFree) & int(old != key) & int(rounds < T)) {
           s = (s + step) & mask;
+          old = atomicCAS(&table[s], kFree, key);
+          rounds = __builtin_amdgcn_readfirstlane(rounds) + 1;
         }
+        if (old == kFree) created |= 1u << i;
         slot[i] = s;
       }
     }
@@ -425,22 +427,23 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
       const uint32_t tag = COMPACT ? uint32_t(key[i].hi) : h >> 16;
       const uint32_t mine = COMPACT ? (tag << 13) | uint32_t(k) : (tag << 16) | uint32_t(k);
       uint32_t s = h & mask;
-      for (int probe = 0; probe < T; ++probe) {  // T probes reach every slot
+      int rounds = 0;  // equal in all lanes still probing (scalar); T probes reach every slot
+      bool won, more;
+      do {
         uint32_t w = table[s];
-        if (w == kEmpty) {
-          w = atomicCAS(&table[s], kEmpty, mine);
-          if (w == kEmpty) {  // this occurrence now represents its n-gram
-            created |= 1u << i;
-            break;
-          }
-        }
+        if (w == kEmpty) w = atomicCAS(&table[s], kEmpty, mine);
+        won = w == kEmpty;  // this occurrence now represents its n-gram
+        bool same = false;
         if (COMPACT) {
-          if ((w >> 13) == tag && slow[w & 0x1FFFu] == key[i].lo) break;
+          if (!won && (w >> 13) == tag) same = slow[w & 0x1FFFu] == key[i].lo;
         } else {
-          if ((w >> 16) == tag && key_eq(skeys[w & 0xFFFFu], key[i])) break;
+          if (!won && (w >> 16) == tag) same = key_eq(skeys[w & 0xFFFFu], key[i]);
         }
-        s = (s + step) & mask;
-      }
+        rounds = __builtin_amdgcn_readfirstlane(rounds) + 1;
+        more = !won && !same && rounds < T;
+        s = more ? (s + step) & mask : s;
+      } while (more);
+      if (won) created |= 1u << i;
       slot[i] = s;
     }
   }
