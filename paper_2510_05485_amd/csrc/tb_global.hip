@@ -336,20 +336,18 @@ __global__ __launch_bounds__(1024) void dictionary_narrow_kernel(DictArgs a) {
   {
     const uint64_t* gkeys =
         reinterpret_cast<const uint64_t*>(a.ws.keys[n0 - 1]) + int64_t(g) * pb.group_cap;
+    // unconditional loads (slots past the count re-read the last key, a cache hit): branches
+    // around loads would make the compiler wait for earlier loads before issuing later ones
+    const int last = max(count0 - 1, 0);
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      const int k = tid + i * nt;
-      key0[i] = (k < count0) ? gkeys[k] : 0;
-    }
+    for (int i = 0; i < ITEMS; ++i) key0[i] = gkeys[min(tid + i * nt, last)];
   }
   {
     const uint64_t* gkeys =
         reinterpret_cast<const uint64_t*>(a.ws.keys[max(n1, 1) - 1]) + int64_t(g) * pb.group_cap;
+    const int last = max(count1 - 1, 0);
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      const int k = tid + i * nt;
-      key1[i] = (k < count1) ? gkeys[k] : 0;
-    }
+    for (int i = 0; i < ITEMS; ++i) key1[i] = gkeys[min(tid + i * nt, last)];
   }
   if ((a.slot32_mask >> n0) & 1)
     narrow_dictionary<ITEMS, uint32_t>(a, smem, &next_id, g, n0, key0, count0);
@@ -390,16 +388,9 @@ __global__ __launch_bounds__(1024) void dictionary_wide_kernel(DictArgs a) {
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
 
   Key128 key[ITEMS];
+  const int last = max(count - 1, 0);  // unconditional loads, as in the narrow kernel
 #pragma unroll
-  for (int i = 0; i < ITEMS; ++i) {
-    const int k = tid + i * nt;
-    if (k < count) {
-      key[i] = gkeys[k];
-    } else {
-      key[i].lo = 0;
-      key[i].hi = 0;
-    }
-  }
+  for (int i = 0; i < ITEMS; ++i) key[i] = gkeys[min(tid + i * nt, last)];
   for (int s = tid; s < T; s += nt) table[s] = kEmpty;
   if (tid == 0) next_id = 0;
 #pragma unroll
