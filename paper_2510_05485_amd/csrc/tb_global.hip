@@ -696,6 +696,7 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
     int part = 0;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
+      if (wave_first + i * nt >= ccnt) break;  // only candidate slots can be first occurrences
       if ((first >> i) & 1u) {
         const uint32_t* e = &cnt[__umul24(id[o][i] - gbase, uint32_t(W))];
         const uint32_t w0 = e[0];
