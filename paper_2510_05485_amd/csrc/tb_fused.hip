@@ -169,7 +169,6 @@ template <typename TokT, int SITEMS>
 __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_part[4];              // per order: clipped sum (low 16) | distinct count (high 16)
-  __shared__ int s_len[kMaxFusedSeqs];   // length of each sequence
   __shared__ int s_end[kMaxFusedSeqs];   // end of each sequence in back-to-back token indices
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
@@ -198,7 +197,6 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   }
   const int incl = wave_inclusive_scan(my_len);
   if (wave == 0 && lane <= R) {
-    s_len[lane] = my_len;
     s_end[lane] = incl;
   }
   if (tid < 4) s_part[tid] = 0;
@@ -351,30 +349,31 @@ __global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
   }
   __syncthreads();
 
-  if (tid == 0) {
-    int clipped[4] = {0, 0, 0, 0}, total[4] = {0, 0, 0, 0};
+  // wavefront 0: lane n < N owns order n + 1 (statistics out, one logarithm each)
+  if (wave == 0) {
     const int c = cand_len;
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      if (n < N) {
-        const int sum = s_part[n];
-        clipped[n] = sum & 0xFFFF;
-        total[n] = max(c - n, 0);
-        a.st.clipped[int64_t(g) * N + n] = clipped[n];
-        a.st.total[int64_t(g) * N + n] = total[n];
-        a.st.distinct[int64_t(g) * N + n] = int(uint32_t(sum) >> 16);
-      }
+    const int sum = (lane < N) ? s_part[lane & 3] : 0;
+    const int cn = sum & 0xFFFF;
+    const int tn = max(c - lane, 0);
+    if (lane < N) {
+      a.st.clipped[int64_t(g) * N + lane] = cn;
+      a.st.total[int64_t(g) * N + lane] = tn;
+      a.st.distinct[int64_t(g) * N + lane] = int(uint32_t(sum) >> 16);
     }
-    int best = s_len[1], bd = abs(best - c);
+    // closest reference length, the shorter one on ties (lane j holds the length of sequence j)
+    int best = lane_value(my_len, 1), bd = abs(best - c);
     for (int j = 2; j <= R; ++j) {
-      const int l = s_len[j], d = abs(l - c);
+      const int l = lane_value(my_len, j), d = abs(l - c);
       if (d < bd || (d == bd && l < best)) {
         best = l;
         bd = d;
       }
     }
-    a.st.closest[g] = best;
-    if (a.out) a.out[g] = bleu_from_stats<int>(clipped, total, c, best, a.sp);
+    const float score = bleu_from_stats_wave(cn, tn, c, best, a.sp);
+    if (lane == 0) {
+      a.st.closest[g] = best;
+      if (a.out) a.out[g] = score;
+    }
   }
 }
 
