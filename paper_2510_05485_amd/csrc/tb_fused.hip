@@ -165,8 +165,13 @@ struct ProbeTable {
 // next order runs over full wavefronts; reading and appending stay inside the wavefront and
 // need neither atomics nor extra barriers.
 // SITEMS: token positions per thread (workgroup size * SITEMS >= tokens of a group).
+// The scalar-register cap matters for occupancy: two 1024-thread workgroups per compute unit are
+// eight wavefronts per SIMD, and on this hardware a kernel that allocates more than 80 scalar
+// registers gets only seven (measured: the same kernel at 96 runs one workgroup per compute
+// unit and takes 34 us instead of 25 us at the headline shape).
 template <typename TokT, int SITEMS>
-__global__ __launch_bounds__(1024) void fused_kernel(FusedArgs a) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(80)))
+void fused_kernel(FusedArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_part[4];              // per order: clipped sum (low 16) | distinct count (high 16)
   __shared__ int s_end[kMaxFusedSeqs];   // end of each sequence in back-to-back token indices
