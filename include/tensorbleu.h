@@ -78,6 +78,12 @@ typedef struct tb_config {
   int32_t token_bytes;  /* element size of `cand` / `refs`: 4 (int32; 0 means 4) or 8 (int64).
                            An int64 id outside [0, vocab_size) is reported like any other
                            out-of-range token */
+  const int32_t* ref_count; /* optional DEVICE pointer [B] (NULL: every candidate has R references):
+                           candidate i is scored against its first ref_count[i] references only;
+                           the remaining rows of its R reference rows are ignored entirely (no
+                           n-grams, no part in the closest reference length).  Values outside
+                           [1, R] are clamped and reported through TB_DEV_LENGTH_RANGE.  The
+                           staged GLOBAL entry points must all see the same array. */
 } tb_config_t;
 
 /* Optional integer outputs (each pointer may be NULL).  These are what the parity tests compare

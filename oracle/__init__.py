@@ -45,7 +45,7 @@ def _load():
         lib.oracle_bleu.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p,
                                     ctypes.c_int, ctypes.c_int, ctypes.c_int, f64p, ctypes.c_int,
                                     ctypes.c_double, ctypes.c_int, i32p, i32p, i32p, i32p, i32p,
-                                    f64p, i64p, f64p]
+                                    f64p, i64p, f64p, i32p]
         lib.oracle_bleu_from_stats.restype = ctypes.c_double
         lib.oracle_bleu_from_stats.argtypes = [i64p, i64p, ctypes.c_int64, ctypes.c_int64,
                                                ctypes.c_int, f64p, ctypes.c_int, ctypes.c_double]
@@ -75,8 +75,11 @@ class OracleResult:
 
 def bleu(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.ndarray,
          max_n: int = 4, weights: Optional[Sequence[float]] = None, smoothing: str = "none",
-         smooth_param: float = 0.0, threads: int = 1) -> OracleResult:
-    """Per-sentence and corpus BLEU of a padded batch (see bleu_oracle.cpp for the definition)."""
+         smooth_param: float = 0.0, threads: int = 1,
+         ref_count: Optional[np.ndarray] = None) -> OracleResult:
+    """Per-sentence and corpus BLEU of a padded batch (see bleu_oracle.cpp for the definition).
+
+    ref_count [B] (optional): candidate i has only its first ref_count[i] references."""
     lib = _load()
     cand = np.ascontiguousarray(cand, dtype=np.int32)
     refs = np.ascontiguousarray(refs, dtype=np.int32)
@@ -98,6 +101,10 @@ def bleu(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.n
     out = np.zeros(B, np.float64)
     cstats = np.zeros(2 * N + 2, np.int64)
     cb = np.zeros(1, np.float64)
+    rcnt = None
+    if ref_count is not None:
+        rcnt = np.ascontiguousarray(ref_count, dtype=np.int32)
+        assert rcnt.shape == (B,)
     rc = lib.oracle_bleu(_p(cand, ctypes.c_int32), cand.shape[1], _p(cand_len, ctypes.c_int32),
                          _p(refs, ctypes.c_int32), refs.shape[2], _p(ref_len, ctypes.c_int32),
                          B, R, N, _p(w, ctypes.c_double), SMOOTHING[smoothing],
@@ -105,7 +112,8 @@ def bleu(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.n
                          _p(total, ctypes.c_int32), _p(closest, ctypes.c_int32),
                          _p(gd, ctypes.c_int32), _p(cd, ctypes.c_int32),
                          _p(out, ctypes.c_double), _p(cstats, ctypes.c_int64),
-                         _p(cb, ctypes.c_double))
+                         _p(cb, ctypes.c_double),
+                         _p(rcnt, ctypes.c_int32) if rcnt is not None else None)
     if rc != 0:
         raise ValueError("oracle_bleu: invalid arguments")
     return OracleResult(clipped, total, closest, gd, cd, out, cstats, float(cb[0]))

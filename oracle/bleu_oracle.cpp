@@ -105,16 +105,19 @@ struct Args {
   const int32_t* refs; int64_t ref_stride; const int32_t* ref_len;
   int B, R, N; const double* w; int smoothing; double param;
   int32_t *clipped, *total, *closest, *group_distinct, *cand_distinct; double* bleu;
+  const int32_t* ref_count;  // per candidate: how many of its R reference rows exist (null: R)
 };
 
 void score_sentence(const Args& a, int i) {
   const int32_t* cs = a.cand + int64_t(i) * a.cand_stride;
   int c = a.cand_len[i];
+  // a candidate with fewer references simply has fewer: the definition over its own references
+  const int Ri = a.ref_count ? a.ref_count[i] : a.R;
   int64_t clip64[8], tot64[8];
   for (int n = 1; n <= a.N; ++n) {
     Counter cc = count_ngrams(cs, c, n);
     Counter ref_max, group = cc;
-    for (int j = 0; j < a.R; ++j) {
+    for (int j = 0; j < Ri; ++j) {
       const int32_t* rs = a.refs + (int64_t(i) * a.R + j) * a.ref_stride;
       Counter rc = count_ngrams(rs, a.ref_len[int64_t(i) * a.R + j], n);
       for (const auto& kv : rc) {
@@ -138,7 +141,7 @@ void score_sentence(const Args& a, int i) {
     if (a.group_distinct) a.group_distinct[o] = int32_t(group.size());
     if (a.cand_distinct) a.cand_distinct[o] = int32_t(cc.size());
   }
-  int r = closest_ref_len(c, a.ref_len + int64_t(i) * a.R, a.R);
+  int r = closest_ref_len(c, a.ref_len + int64_t(i) * a.R, Ri);
   a.closest[i] = r;
   a.bleu[i] = bleu_from_stats(clip64, tot64, c, r, a.N, a.w, a.smoothing, a.param);
 }
@@ -154,16 +157,20 @@ extern "C" {
 // Outputs (host, caller-allocated): clipped/total [B, N], closest [B], bleu [B] fp64,
 //   optional group_distinct / cand_distinct [B, N] (distinct n-grams over candidate+references,
 //   and over the candidate alone), corpus_stats [2N+2] = clipped_1..N, total_1..N, sum c, sum r,
-//   corpus_bleu [1].  Returns 0, or 1 on invalid arguments.
+//   corpus_bleu [1].  ref_count [B] (may be null): candidate i has only its first ref_count[i]
+//   reference rows, 1 <= ref_count[i] <= R.  Returns 0, or 1 on invalid arguments.
 int oracle_bleu(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
                 const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int B, int R,
                 int N, const double* weights, int smoothing, double param, int threads,
                 int32_t* clipped, int32_t* total, int32_t* closest, int32_t* group_distinct,
                 int32_t* cand_distinct, double* bleu, int64_t* corpus_stats,
-                double* corpus_bleu) {
+                double* corpus_bleu, const int32_t* ref_count) {
   if (B < 0 || R < 1 || N < 1 || N > 8 || smoothing < 0 || smoothing > 3) return 1;
+  if (ref_count)
+    for (int i = 0; i < B; ++i)
+      if (ref_count[i] < 1 || ref_count[i] > R) return 1;
   Args a{cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, N, weights, smoothing,
-         param, clipped, total, closest, group_distinct, cand_distinct, bleu};
+         param, clipped, total, closest, group_distinct, cand_distinct, bleu, ref_count};
   int T = std::max(1, std::min(threads, std::max(B, 1)));
   if (T == 1) {
     for (int i = 0; i < B; ++i) score_sentence(a, i);

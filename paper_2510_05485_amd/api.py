@@ -49,15 +49,30 @@ class BleuScorer:
             raise _b.TensorBLEUError(f"scorer was built for cand {(B, cs)} / refs {(B, R, rs)}, "
                                      f"got {tuple(cand.shape)} / {tuple(refs.shape)}")
 
-    def __call__(self, cand, cand_len, refs, ref_len) -> torch.Tensor:
+    def _set_ref_count(self, ref_count):
+        """ref_count: int32/int64 device tensor [B] (candidate i uses its first ref_count[i]
+        references) or None (all R)."""
+        if ref_count is None:
+            self.cfg.ref_count = None
+            self._ref_count = None
+            return
+        t = _len32(ref_count).contiguous()
+        if tuple(t.shape) != (self.shape[0],) or not t.is_cuda:
+            raise _b.TensorBLEUError("ref_count must be a device tensor of shape [B]")
+        self._ref_count = t                    # keeps the memory alive for the call
+        self.cfg.ref_count = t.data_ptr()
+
+    def __call__(self, cand, cand_len, refs, ref_len, ref_count=None) -> torch.Tensor:
         refs = _refs3d(refs)
         self._check(cand, refs)
+        self._set_ref_count(ref_count)
         return _b.tensorbleu_sentence(cand, _len32(cand_len), refs, _len32(ref_len), self.cfg,
                                       out=self.out, stats=self.stats, workspace=self.workspace)
 
-    def corpus(self, cand, cand_len, refs, ref_len) -> torch.Tensor:
+    def corpus(self, cand, cand_len, refs, ref_len, ref_count=None) -> torch.Tensor:
         refs = _refs3d(refs)
         self._check(cand, refs)
+        self._set_ref_count(ref_count)
         return _b.tensorbleu_corpus(cand, _len32(cand_len), refs, _len32(ref_len), self.cfg,
                                     out=self.corpus_out, stats=self.stats,
                                     workspace=self.workspace)

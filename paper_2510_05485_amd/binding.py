@@ -33,7 +33,7 @@ class tb_config_t(ctypes.Structure):
     _fields_ = [("max_n", ctypes.c_int32), ("weights", ctypes.c_float * 4),
                 ("smoothing", ctypes.c_int32), ("smooth_param", ctypes.c_float),
                 ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32),
-                ("token_bytes", ctypes.c_int32)]
+                ("token_bytes", ctypes.c_int32), ("ref_count", ctypes.c_void_p)]
 
 
 class tb_stats_t(ctypes.Structure):
@@ -107,7 +107,9 @@ def _check(rc: int, what: str) -> None:
 
 def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
                 smoothing: str = "none", smooth_param: float = 0.0, vocab_size: int = 1 << 16,
-                path: str = "auto") -> tb_config_t:
+                path: str = "auto", ref_count: Optional[torch.Tensor] = None) -> tb_config_t:
+    """ref_count: optional int32 device tensor [B]; candidate i is scored against its first
+    ref_count[i] references only.  The config keeps the tensor alive."""
     cfg = tb_config_t()
     cfg.max_n = int(max_n)
     w = [0.0] * 4
@@ -120,6 +122,12 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
     cfg.vocab_size = int(vocab_size)
     cfg.force_path = PATHS[path] if isinstance(path, str) else int(path)
     cfg.token_bytes = 4
+    cfg.ref_count = None
+    if ref_count is not None:
+        if ref_count.dtype != torch.int32 or not ref_count.is_contiguous() or ref_count.dim() != 1:
+            raise TensorBLEUError("ref_count must be a contiguous int32 tensor of shape [B]")
+        cfg.ref_count = ref_count.data_ptr()
+        cfg._ref_count_tensor = ref_count      # keeps the device memory alive with the config
     return cfg
 
 

@@ -123,6 +123,7 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   pb.cand_len = cand_len;
   pb.refs = refs;
   pb.ref_len = ref_len;
+  pb.ref_count = cfg->ref_count;
   pb.cand_stride = cand_stride;
   pb.ref_stride = ref_stride;
   pb.group_cap = L.group_cap;

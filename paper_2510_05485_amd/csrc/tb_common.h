@@ -119,6 +119,7 @@ struct Problem {
   int32_t bits;       // ceil(log2(vocab)), >= 1
   int32_t vocab;
   int32_t tok64;      // token ids are int64
+  const int32_t* ref_count;  // per-candidate number of references in use, or null (= R)
   int32_t* status;    // may be null
 };
 
@@ -130,6 +131,15 @@ __device__ __forceinline__ int32_t load_token(const void* base, int64_t idx, int
     return (v < 0 || v > 0x7FFFFFFFll) ? -1 : int32_t(v);
   }
   return static_cast<const int32_t*>(base)[idx];
+}
+
+// References candidate g is scored against: all R, or the caller's count clamped into [1, R]
+// (`flag`: report a clamped count; set by one thread per group only).
+__device__ __forceinline__ int refs_used(const Problem& pb, int g, bool flag = false) {
+  if (!pb.ref_count) return pb.R;
+  const int c = pb.ref_count[g];
+  if (flag && (c < 1 || c > pb.R) && pb.status) atomicOr(pb.status, TB_DEV_LENGTH_RANGE);
+  return min(max(c, 1), pb.R);
 }
 
 // Length of a row as the kernels use it: clamped into [0, stride].

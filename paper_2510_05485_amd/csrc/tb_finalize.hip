@@ -18,7 +18,8 @@ __global__ __launch_bounds__(256) void sentence_score_kernel(FinalArgs a) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= pb.B) return;
   const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
-  const int r = closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, pb.R, pb.ref_stride, pb.status);
+  const int r = closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, refs_used(pb, i, true),
+                                pb.ref_stride, pb.status);
   a.st.closest[i] = r;
   int cl[4], to[4];
 #pragma unroll
@@ -50,7 +51,8 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
   for (int i = threadIdx.x; i < pb.B; i += blockDim.x) {
     const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
     const int r =
-        closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, pb.R, pb.ref_stride, pb.status);
+        closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, refs_used(pb, i, true), pb.ref_stride,
+                        pb.status);
     a.st.closest[i] = r;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {

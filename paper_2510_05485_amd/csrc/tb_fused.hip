@@ -193,8 +193,11 @@ void fused_kernel(FusedArgs a) {
   const int bits = pb.bits;
 
   // lane j of every wavefront: length of sequence j and the inclusive prefix of lengths
+  // (a reference beyond the candidate's reference count has length 0 and no say in the closest
+  // reference length)
+  const int used = refs_used(pb, g, tid == 0);
   int my_len = 0;
-  if (lane <= R) {
+  if (lane <= used) {
     my_len = (lane == 0)
         ? clamped_len(pb.cand_len[g], pb.cand_stride, wave == 0 ? pb.status : nullptr)
         : clamped_len(pb.ref_len[int64_t(g) * R + lane - 1], pb.ref_stride,
@@ -367,7 +370,7 @@ void fused_kernel(FusedArgs a) {
     }
     // closest reference length, the shorter one on ties (lane j holds the length of sequence j)
     int best = lane_value(my_len, 1), bd = abs(best - c);
-    for (int j = 2; j <= R; ++j) {
+    for (int j = 2; j <= used; ++j) {
       const int l = lane_value(my_len, j), d = abs(l - c);
       if (d < bd || (d == bd && l < best)) {
         best = l;

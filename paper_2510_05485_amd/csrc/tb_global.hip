@@ -20,9 +20,11 @@
 namespace tb {
 
 // Clamped length of sequence j of group g (j = 0: candidate, j >= 1: reference j-1).
+// A reference beyond the candidate's reference count has no n-grams: length 0.
 __device__ __forceinline__ int seq_len(const Problem& pb, int g, int j) {
-  return j == 0 ? clamped_len(pb.cand_len[g], pb.cand_stride, nullptr)
-                : clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
+  if (j == 0) return clamped_len(pb.cand_len[g], pb.cand_stride, nullptr);
+  if (j > refs_used(pb, g)) return 0;
+  return clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
 }
 
 // Where each sequence of group g starts inside the group's compact slot range for order n.
@@ -35,7 +37,7 @@ class GroupIndex {
   // Issues the loads of the lengths and nothing else: the values are first touched by
   // set_order(), so loads that the caller issues in between are in flight together with them.
   __device__ __forceinline__ GroupIndex(const Problem& pb, int g)
-      : pb_(pb), g_(g), n_(1), fast_(pb.R < kWave), raw_(0), incl_(0) {
+      : pb_(pb), g_(g), n_(1), fast_(pb.R < kWave), raw_(0), used_(pb.R), incl_(0) {
     if (fast_) load_raw();
   }
   __device__ __forceinline__ GroupIndex(const Problem& pb, int g, int n) : GroupIndex(pb, g) {
@@ -44,7 +46,7 @@ class GroupIndex {
   // For kernels that are only launched with fewer than 64 sequences per group: no loop fallback.
   struct WaveOnly {};
   __device__ __forceinline__ GroupIndex(const Problem& pb, int g, WaveOnly)
-      : pb_(pb), g_(g), n_(1), fast_(true), raw_(0), incl_(0) {
+      : pb_(pb), g_(g), n_(1), fast_(true), raw_(0), used_(pb.R), incl_(0) {
     load_raw();
   }
   __device__ __forceinline__ void set_order(int n) {
@@ -55,7 +57,8 @@ class GroupIndex {
       // fields would otherwise be turned into one vector load from a selected address)
       const int cs = __builtin_amdgcn_readfirstlane(int(min(pb_.cand_stride, int64_t(1) << 30)));
       const int rs = __builtin_amdgcn_readfirstlane(int(min(pb_.ref_stride, int64_t(1) << 30)));
-      const int len = clamped_len(raw_, lane == 0 ? cs : rs, nullptr);
+      const int used = min(max(used_, 1), pb_.R);  // references in use
+      const int len = lane <= used ? clamped_len(raw_, lane == 0 ? cs : rs, nullptr) : 0;
       incl_ = wave_inclusive_scan(max(len - n + 1, 0));
     }
   }
@@ -79,11 +82,12 @@ class GroupIndex {
       raw_ = pb_.cand_len[g_];
     else if (lane <= pb_.R)
       raw_ = pb_.ref_len[int64_t(g_) * pb_.R + lane - 1];
+    if (pb_.ref_count) used_ = pb_.ref_count[g_];
   }
   const Problem& pb_;
   int g_, n_;
   bool fast_;
-  int raw_, incl_;
+  int raw_, used_, incl_;
 };
 
 // ---------------------------------------------------------------------------------- pack
@@ -131,6 +135,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     rows = pb.refs;
     row = (int64_t(g) * pb.R + j - 1) * pb.ref_stride;
     len = clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, pb.status);
+    if (j > refs_used(pb, g)) len = 0;  // reference not in use
   }
   const int p0 = chunk * kPackTile;
   if (p0 >= len) return;  // uniform over the workgroup

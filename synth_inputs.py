@@ -279,3 +279,9 @@ def random_small(seed: int, B: int, R: int, vocab: int, max_len: int, min_len: i
                 r[:m] = np.where(keep, c[:m], r[:m])
             refs[i, j, :lr], rl[i, j] = r, lr
     return Workload(f"small_s{seed}_B{B}_R{R}_V{vocab}", vocab, cand, cl, refs, rl)
+
+
+def ref_counts(seed: int, B: int, R: int) -> np.ndarray:
+    """Per-candidate number of references in use, uniform in 1..R (for ragged reference counts)."""
+    u = uniforms(seed, 0, 15, B)
+    return (np.minimum(np.floor(u * R), R - 1) + 1).astype(np.int32)

@@ -110,3 +110,18 @@ def test_hip_graph_capture_and_replay(path):
         eager = tb.sentence_bleu(cand, cl, refs, rl, vocab_size=300, smoothing="floor",
                                  smooth_param=0.1, path=path)
         np.testing.assert_array_equal(out.cpu().numpy(), eager.cpu().numpy())
+
+
+def test_scorer_accepts_reference_counts():
+    w = syn.random_small(61, B=20, R=3, vocab=30, max_len=50)
+    rc = syn.ref_counts(61, w.B, w.R)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp", ref_count=rc)
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    scorer = tb.BleuScorer(w.B, w.R, w.cand.shape[1], w.refs.shape[2], vocab_size=w.vocab,
+                           smoothing="exp")
+    out = scorer(to(w.cand).long(), to(w.cand_len), to(w.refs).long(), to(w.ref_len),
+                 ref_count=to(rc).long()).cpu().numpy()
+    assert np.abs(out.astype(np.float64) - ref.bleu).max() <= 1e-5
+    full = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+    out = scorer(to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len)).cpu().numpy()
+    assert np.abs(out.astype(np.float64) - full.bleu).max() <= 1e-5   # count cleared again

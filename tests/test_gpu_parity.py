@@ -271,3 +271,66 @@ def test_full_size_configs(config, path):
         if run.corpus:
             continue                        # check() always covers the corpus variant too
         check(w, run, path, d=d)
+
+
+# ------------------------------------------------- per-candidate reference counts (ragged R)
+
+def _ragged_case(seed, B, R, V, L):
+    """A batch whose candidates use 1..R references; the unused rows are filled with copies of
+    the candidate (and its length), which would change every statistic if they were read."""
+    w = cached_small(seed, B=B, R=R, vocab=V, max_len=L)
+    rc = syn.ref_counts(seed, B, R)
+    refs, ref_len = w.refs.copy(), w.ref_len.copy()
+    for i in range(B):
+        m = min(w.cand.shape[1], refs.shape[2])
+        refs[i, rc[i]:, :m] = w.cand[i, :m]
+        ref_len[i, rc[i]:] = min(int(w.cand_len[i]), m)
+    return w, rc, refs, ref_len
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("seed,B,R,V,L", [
+    (201, 37, 4, 11, 60),          # LDS kernels, one field per sequence
+    (202, 6, 3, 262144, 700),      # 128-bit keys
+    (203, 5, 40, 300, 120),        # many references (pair-phase count kernel on the global path)
+    (204, 3, 2, 50, 9000),         # group beyond the LDS plans: tables in the workspace
+])
+def test_ragged_reference_counts(path, seed, B, R, V, L):
+    w, rc, refs, ref_len = _ragged_case(seed, B, R, V, L)
+    if not path_supported(w, path):
+        pytest.skip(f"{path} path does not support this shape")
+    cand, cand_len = dev(w.cand), dev(w.cand_len)
+    drefs, dref_len, drc = dev(refs), dev(ref_len), dev(rc)
+    for run in ALL_MODES:
+        ref = oracle.bleu(w.cand, w.cand_len, refs, ref_len, smoothing=run.smoothing,
+                          smooth_param=run.smooth_param, ref_count=rc, threads=8)
+        cfg = tb.make_config(smoothing=run.smoothing, smooth_param=run.smooth_param,
+                             vocab_size=w.vocab, path=path, ref_count=drc)
+        for corpus in (False, True):
+            stats = tb.Stats.allocate(w.B, 4, DEV)
+            fn = tb.tensorbleu_corpus if corpus else tb.tensorbleu_sentence
+            out = fn(cand, cand_len, drefs, dref_len, cfg, stats=stats).cpu().numpy()
+            assert stats.device_status.item() == 0
+            np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
+            np.testing.assert_array_equal(stats.total.cpu().numpy(), ref.total)
+            np.testing.assert_array_equal(stats.closest_ref_len.cpu().numpy(), ref.closest_ref_len)
+            if corpus:
+                np.testing.assert_array_equal(stats.corpus_stats.cpu().numpy(), ref.corpus_stats)
+                assert abs(float(out[0]) - ref.corpus_bleu) <= TOL
+            else:
+                assert np.abs(out.astype(np.float64) - ref.bleu).max() <= TOL
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_reference_count_out_of_range_is_clamped_and_flagged(path):
+    w = cached_small(205, B=8, R=3, vocab=20, max_len=30)
+    rc = np.array([1, 2, 3, 0, 7, -4, 3, 1], np.int32)       # 0 and -4 -> 1, 7 -> 3
+    clamped = np.clip(rc, 1, 3).astype(np.int32)
+    cfg = tb.make_config(vocab_size=w.vocab, path=path, ref_count=dev(rc))
+    stats = tb.Stats.allocate(w.B, 4, DEV)
+    out = tb.tensorbleu_sentence(dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len), cfg,
+                                 stats=stats).cpu().numpy()
+    assert stats.device_status.item() & tb.TB_DEV_LENGTH_RANGE
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, ref_count=clamped)
+    np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
+    assert np.abs(out.astype(np.float64) - ref.bleu).max() <= TOL

@@ -438,3 +438,64 @@ def test_ragged_generators_respect_lengths():
     w = syn.config5(B=64)
     assert (w.cand_len >= 32).all() and (w.cand_len <= 512).all() and w.cand.max() < 64
     assert (w.ref_len <= 640).all() and (w.ref_len >= 0.79 * w.cand_len[:, None] - 1).all()
+
+
+# ---------------------------------------------------- per-candidate reference counts (ragged R)
+
+def _ref_counts(seed, B, R):
+    return syn.ref_counts(seed, B, R)
+
+
+@pytest.mark.parametrize("mode,param", MODES)
+def test_reference_count_equal_to_R_changes_nothing(small, mode, param):
+    full = _run(small, smoothing=mode, smooth_param=param)
+    same = _run(small, smoothing=mode, smooth_param=param,
+                ref_count=np.full(small.B, small.R, np.int32))
+    np.testing.assert_array_equal(same.clipped, full.clipped)
+    np.testing.assert_array_equal(same.closest_ref_len, full.closest_ref_len)
+    np.testing.assert_array_equal(same.bleu, full.bleu)
+    assert same.corpus_bleu == full.corpus_bleu
+
+
+@pytest.mark.parametrize("mode,param", MODES)
+def test_reference_count_equals_scoring_against_the_sliced_references(small, mode, param):
+    """Candidate i with ref_count[i] = k is, by definition, candidate i with references 0..k-1:
+    compared sentence by sentence with a batch of one that holds only those rows; the rows
+    beyond k are overwritten with tokens that would change every count if they were read."""
+    rc = _ref_counts(5, small.B, small.R)
+    assert rc.min() >= 1 and rc.max() <= small.R and len(set(rc.tolist())) > 1
+    poisoned = small.refs.copy()
+    poisoned_len = small.ref_len.copy()
+    for i in range(small.B):
+        poisoned[i, rc[i]:] = small.cand[i, :1].repeat(poisoned.shape[2])[None, :]
+        poisoned_len[i, rc[i]:] = small.cand_len[i]          # would also win the closest length
+    res = oracle.bleu(small.cand, small.cand_len, poisoned, poisoned_len, smoothing=mode,
+                      smooth_param=param, ref_count=rc)
+    for i in range(small.B):
+        k = int(rc[i])
+        one_ = oracle.bleu(small.cand[i:i + 1], small.cand_len[i:i + 1], small.refs[i:i + 1, :k],
+                           small.ref_len[i:i + 1, :k], smoothing=mode, smooth_param=param)
+        np.testing.assert_array_equal(res.clipped[i], one_.clipped[0])
+        assert res.closest_ref_len[i] == one_.closest_ref_len[0]
+        assert res.bleu[i] == one_.bleu[0]
+    # corpus statistics are the sums of the per-sentence ones
+    np.testing.assert_array_equal(res.corpus_stats[:4], res.clipped.sum(0))
+    assert res.corpus_stats[9] == res.closest_ref_len.sum()
+
+
+def test_reference_count_brute_force():
+    w = syn.random_small(31, B=12, R=3, vocab=4, max_len=9, min_len=1)
+    rc = _ref_counts(8, w.B, w.R)
+    res = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, ref_count=rc)
+    for i in range(w.B):
+        refs = [w.refs[i, j, :w.ref_len[i, j]].tolist() for j in range(rc[i])]
+        clipped, total = brute_force_stats(w.cand[i, :w.cand_len[i]].tolist(), refs, 4)
+        assert res.clipped[i].tolist() == clipped and res.total[i].tolist() == total
+
+
+def test_reference_count_out_of_range_is_rejected():
+    w = syn.random_small(32, B=4, R=2, vocab=5, max_len=8)
+    for bad in (0, 3):
+        with pytest.raises(ValueError):
+            oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len,
+                        ref_count=np.array([1, 2, bad, 1], np.int32))
