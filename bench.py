@@ -74,10 +74,10 @@ def cpu_baseline(w, run, budget_s=12.0):
 # runs summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters'
 # reading for a plain copy of known size).  Keyed by (workload name, kernel); None = not measured.
 MEASURED_TRAFFIC = {
-    ("cfg3_B512_L1024_R4", "fused"): 10.93e6,
+    ("cfg3_B512_L1024_R4", "fused"): 10.89e6,
     ("cfg3_B512_L1024_R4", "pack"): 94.89e6,
-    ("cfg3_B512_L1024_R4", "dictionary"): 125.83e6,
-    ("cfg3_B512_L1024_R4", "count_clip"): 50.89e6,
+    ("cfg3_B512_L1024_R4", "dictionary"): 125.85e6,
+    ("cfg3_B512_L1024_R4", "count_clip"): 50.83e6,
 }
 
 
