@@ -21,9 +21,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(w, lay, N):
+def algorithmic_bytes(w, lay, N, token_bytes=4):
     """Bytes each pass must move by the method itself (tokens, keys, ids, statistics)."""
-    T = w.tokens
+    T = w.tokens * token_bytes // 4      # tokens counted in 4-byte units
     G = [w.ngrams(n) for n in range(1, N + 1)]
     kb = [lay.key_bytes[n] for n in range(N)]
     stats = 8 * w.B * N
@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "global"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--int64", action="store_true",
+                    help="feed int64 token ids (the usual tokenizer dtype) instead of int32")
     ap.add_argument("--no-global-passes", action="store_true",
                     help="skip the per-pass timing of the GLOBAL path")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -126,6 +128,8 @@ def main():
     N = w.max_n
     to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
     cand, cl, refs, rl = to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len)
+    if a.int64:
+        cand, refs = cand.long(), refs.long()
     cs, rs = int(w.cand.shape[1]), int(w.refs.shape[2])
 
     def config(path):
@@ -168,7 +172,7 @@ def main():
     # per-kernel durations, each kernel on its own between HIP events
     glay = tb.tensorbleu_workspace_layout(w.B, w.R, cs, rs, config("global")) \
         if lay.global_ok else None
-    alg = algorithmic_bytes(w, glay or lay, N)
+    alg = algorithmic_bytes(w, glay or lay, N, 8 if a.int64 else 4)
     global_section = None
     if glay is not None and not (a.no_global_passes and path != "global"):
         gcfg = config("global")
@@ -205,8 +209,8 @@ def main():
         "value": round(w.B / (ms * 1e-3), 1), "unit": "sentences/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 keys / u16 counts / f32 scores" if path == "fused"
-                 else "u64 keys / u16 counts / f32 scores",
+        "dtype": ("u32 keys / u16 counts / f32 scores" if path == "fused"
+                  else "u64 keys / u16 counts / f32 scores") + (" (int64 ids)" if a.int64 else ""),
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "R": w.R, "cand_stride": cs, "ref_stride": rs,
                    "vocab": w.vocab, "max_n": N, "smoothing": run.smoothing, "path": path,

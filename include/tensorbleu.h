@@ -63,7 +63,8 @@ typedef enum { TB_PATH_AUTO = 0, TB_PATH_FUSED = 1, TB_PATH_GLOBAL = 2 } tb_path
 
 /* Bits of *stats->device_status. */
 enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0, vocab_size) */
-       TB_DEV_LENGTH_RANGE = 2  /* a length was outside [0, stride] and was clamped */ };
+       TB_DEV_LENGTH_RANGE = 2  /* a length outside [0, stride], or a reference count outside
+                                   [1, R], was clamped */ };
 
 typedef struct tb_config {
   int32_t max_n;        /* N: highest n-gram order, 1..4 (Section 2.1: "typically n=1 to 4") */
