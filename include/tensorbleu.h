@@ -41,7 +41,7 @@ extern "C" {
 
 typedef enum {
   TB_OK = 0,
-  TB_ERR_INVALID_ARG = 1, /* NULL required pointer, B < 0, R < 1, max_n outside 1..4, bad stride */
+  TB_ERR_INVALID_ARG = 1, /* NULL required pointer, B < 0, R < 1, max_n outside 1..8, bad stride */
   TB_ERR_WORKSPACE = 2,   /* workspace NULL, misaligned (256 B) or smaller than workspace_bytes */
   TB_ERR_UNSUPPORTED = 3, /* shape outside what the kernels handle (see tensorbleu_workspace_layout) */
   TB_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed */
@@ -67,8 +67,9 @@ enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0,
                                    [1, R], was clamped */ };
 
 typedef struct tb_config {
-  int32_t max_n;        /* N: highest n-gram order, 1..4 (Section 2.1: "typically n=1 to 4") */
-  float   weights[4];   /* w_1..w_N of the BLEU equation, used as given (not renormalised);
+  int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1: "typically n=1 to 4");
+                           the GLOBAL path handles N <= 4, larger N needs the FUSED path */
+  float   weights[8];   /* w_1..w_N of the BLEU equation, used as given (not renormalised);
                            w_n == 0 drops order n; all zero means uniform 1/N */
   int32_t smoothing;    /* tb_smooth_t */
   float   smooth_param; /* eps for FLOOR, k for ADD_K; ignored otherwise */

@@ -30,7 +30,7 @@ EXPORTS = [
 
 
 class tb_config_t(ctypes.Structure):
-    _fields_ = [("max_n", ctypes.c_int32), ("weights", ctypes.c_float * 4),
+    _fields_ = [("max_n", ctypes.c_int32), ("weights", ctypes.c_float * 8),
                 ("smoothing", ctypes.c_int32), ("smooth_param", ctypes.c_float),
                 ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32),
                 ("token_bytes", ctypes.c_int32), ("ref_count", ctypes.c_void_p)]
@@ -112,11 +112,11 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
     ref_count[i] references only.  The config keeps the tensor alive."""
     cfg = tb_config_t()
     cfg.max_n = int(max_n)
-    w = [0.0] * 4
+    w = [0.0] * 8
     if weights is not None:
-        for n, x in enumerate(list(weights)[:4]):
+        for n, x in enumerate(list(weights)[:8]):
             w[n] = float(x)
-    cfg.weights = (ctypes.c_float * 4)(*w)
+    cfg.weights = (ctypes.c_float * 8)(*w)
     cfg.smoothing = SMOOTHING[smoothing] if isinstance(smoothing, str) else int(smoothing)
     cfg.smooth_param = float(smooth_param)
     cfg.vocab_size = int(vocab_size)

@@ -19,7 +19,7 @@ int ceil_log2(int32_t v) {
 
 bool config_ok(const tb_config_t* cfg) {
   if (!cfg) return false;
-  if (cfg->max_n < 1 || cfg->max_n > 4) return false;
+  if (cfg->max_n < 1 || cfg->max_n > 8) return false;
   if (cfg->vocab_size < 1) return false;
   if (cfg->smoothing < TB_SMOOTH_NONE || cfg->smoothing > TB_SMOOTH_EXP) return false;
   if (cfg->force_path < TB_PATH_AUTO || cfg->force_path > TB_PATH_GLOBAL) return false;
@@ -50,9 +50,11 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     return TB_ERR_UNSUPPORTED;
   L.group_cap = cand_stride + int64_t(R) * ref_stride;
   const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
-  const bool lds_ok = plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
+  const bool global_n = N <= 4;  // the GLOBAL path materialises at most four orders
+  const bool lds_ok = global_n &&
+                      plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
                       plan_count(L.group_cap, cand_stride, ref_stride, R, &p->count);
-  p->use_big = !lds_ok && plan_big(L.group_cap, N, &p->big);
+  p->use_big = global_n && !lds_ok && plan_big(L.group_cap, N, &p->big);
   L.global_ok = ids_fit && (lds_ok || p->use_big);
   L.global_tables_in_hbm = p->use_big ? 1 : 0;
   L.fused_ok = plan_fused(cand_stride, ref_stride, R, N, L.bits, &p->fused);
@@ -68,7 +70,7 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   L.total_off = off;    off = align_up(off + bn * 4);
   L.closest_off = off;  off = align_up(off + size_t(B) * 4);
   L.distinct_off = off; off = align_up(off + bn * 4);
-  L.corpus_off = off;   off = align_up(off + 10 * 8);
+  L.corpus_off = off;   off = align_up(off + 18 * 8);
   if (path == TB_PATH_GLOBAL) {
     const size_t slots = size_t(B) * size_t(L.group_cap);
     for (int n = 0; n < N; ++n) {
@@ -158,7 +160,7 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   sp.param = cfg->smooth_param;
   bool all_zero = true;
   for (int n = 0; n < sp.N; ++n) all_zero = all_zero && cfg->weights[n] == 0.0f;
-  for (int n = 0; n < 4; ++n)
+  for (int n = 0; n < 8; ++n)
     sp.w[n] = (n < sp.N) ? (all_zero ? 1.0f / float(sp.N) : cfg->weights[n]) : 0.0f;
   c->stream = static_cast<hipStream_t>(hip_stream);
   return TB_OK;

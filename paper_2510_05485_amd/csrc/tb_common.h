@@ -152,7 +152,7 @@ __device__ __forceinline__ int clamped_len(int len, int64_t stride, int32_t* sta
 }
 
 struct ScoreParams {
-  float w[4];
+  float w[8];
   int32_t N;
   int32_t smoothing;
   float param;

@@ -21,9 +21,9 @@ __global__ __launch_bounds__(256) void sentence_score_kernel(FinalArgs a) {
   const int r = closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, refs_used(pb, i, true),
                                 pb.ref_stride, pb.status);
   a.st.closest[i] = r;
-  int cl[4], to[4];
+  int cl[8], to[8];
 #pragma unroll
-  for (int n = 0; n < 4; ++n) {
+  for (int n = 0; n < 8; ++n) {
     cl[n] = (n < pb.N) ? a.st.clipped[int64_t(i) * pb.N + n] : 0;
     to[n] = (n < pb.N) ? a.st.total[int64_t(i) * pb.N + n] : 0;
   }
@@ -43,11 +43,11 @@ __device__ __forceinline__ long long wave_sum64(long long v) {
 // A single workgroup strides over the batch, reduces the 2N+2 integer sums with wavefront
 // shuffles and LDS, and lane 0 forms the corpus score.
 __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_score) {
-  __shared__ long long part[16][10];
+  __shared__ long long part[16][18];
   const Problem& pb = a.pb;
-  long long acc[10];
+  long long acc[18];  // clipped_1..8, total_1..8, candidate lengths, closest reference lengths
 #pragma unroll
-  for (int k = 0; k < 10; ++k) acc[k] = 0;
+  for (int k = 0; k < 18; ++k) acc[k] = 0;
   for (int i = threadIdx.x; i < pb.B; i += blockDim.x) {
     const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
     const int r =
@@ -55,36 +55,36 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
                         pb.status);
     a.st.closest[i] = r;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
+    for (int n = 0; n < 8; ++n) {
       if (n < pb.N) {
         acc[n] += a.st.clipped[int64_t(i) * pb.N + n];
-        acc[4 + n] += a.st.total[int64_t(i) * pb.N + n];
+        acc[8 + n] += a.st.total[int64_t(i) * pb.N + n];
       }
     }
-    acc[8] += c;
-    acc[9] += r;
+    acc[16] += c;
+    acc[17] += r;
   }
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 #pragma unroll
-  for (int k = 0; k < 10; ++k) {
+  for (int k = 0; k < 18; ++k) {
     const long long s = wave_sum64(acc[k]);
     if (lane == 0) part[wave][k] = s;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     const int nwaves = blockDim.x / kWave;
-    long long tot[10];
-    for (int k = 0; k < 10; ++k) {
+    long long tot[18];
+    for (int k = 0; k < 18; ++k) {
       tot[k] = 0;
       for (int w = 0; w < nwaves; ++w) tot[k] += part[w][k];
     }
     for (int n = 0; n < pb.N; ++n) {
       a.st.corpus[n] = tot[n];
-      a.st.corpus[pb.N + n] = tot[4 + n];
+      a.st.corpus[pb.N + n] = tot[8 + n];
     }
-    a.st.corpus[2 * pb.N] = tot[8];
-    a.st.corpus[2 * pb.N + 1] = tot[9];
-    if (write_score) a.out[0] = bleu_from_stats<long long>(tot, tot + 4, tot[8], tot[9], a.sp);
+    a.st.corpus[2 * pb.N] = tot[16];
+    a.st.corpus[2 * pb.N + 1] = tot[17];
+    if (write_score) a.out[0] = bleu_from_stats<long long>(tot, tot + 8, tot[16], tot[17], a.sp);
   }
 }
 

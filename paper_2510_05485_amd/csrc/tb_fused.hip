@@ -173,7 +173,7 @@ template <typename TokT, int SITEMS>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(80)))
 void fused_kernel(FusedArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int s_part[4];              // per order: clipped sum (low 16) | distinct count (high 16)
+  __shared__ int s_part[8];              // per order: clipped sum (low 16) | distinct count (high 16)
   __shared__ int s_end[kMaxFusedSeqs];   // end of each sequence in back-to-back token indices
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
@@ -207,7 +207,7 @@ void fused_kernel(FusedArgs a) {
   if (wave == 0 && lane <= R) {
     s_end[lane] = incl;
   }
-  if (tid < 4) s_part[tid] = 0;
+  if (tid < 8) s_part[tid] = 0;
   const int total_tokens = min(lane_value(incl, R), SITEMS * nt);
   const int cand_len = lane_value(my_len, 0);
 
@@ -360,7 +360,7 @@ void fused_kernel(FusedArgs a) {
   // wavefront 0: lane n < N owns order n + 1 (statistics out, one logarithm each)
   if (wave == 0) {
     const int c = cand_len;
-    const int sum = (lane < N) ? s_part[lane & 3] : 0;
+    const int sum = (lane < N) ? s_part[lane & 7] : 0;
     const int cn = sum & 0xFFFF;
     const int tn = max(c - lane, 0);
     if (lane < N) {

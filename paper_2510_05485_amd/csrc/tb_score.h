@@ -59,7 +59,7 @@ __device__ __forceinline__ float bleu_from_stats(const IntT* clipped, const IntT
   int zeros_seen = 0;
   bool dead = false;
 #pragma unroll
-  for (int n = 1; n <= 4; ++n) {
+  for (int n = 1; n <= 8; ++n) {
     if (n > sp.N) break;
     zeros_seen += (clipped[n - 1] == 0) ? 1 : 0;
     logsum = __fadd_rn(logsum, order_log_term<IntT>(n, clipped[n - 1], total[n - 1], zeros_seen,
@@ -79,7 +79,9 @@ __device__ __forceinline__ float bleu_from_stats_wave(int cn, int tn, int c, int
   const bool order_lane = lane < sp.N;
   const unsigned long long zero_mask = __builtin_amdgcn_ballot_w64(order_lane && cn == 0);
   const int zeros_seen = __popcll(zero_mask & ((2ull << lane) - 1ull));  // orders 1..lane+1
-  const float w = lane == 0 ? sp.w[0] : lane == 1 ? sp.w[1] : lane == 2 ? sp.w[2] : sp.w[3];
+  float w = sp.w[0];
+#pragma unroll
+  for (int n = 1; n < 8; ++n) w = (lane == n) ? sp.w[n] : w;
   bool dead = false;
   float t = 0.0f;
   if (order_lane) t = order_log_term<int>(lane + 1, cn, tn, zeros_seen, sp, w, &dead);
@@ -87,7 +89,7 @@ __device__ __forceinline__ float bleu_from_stats_wave(int cn, int tn, int c, int
   const int first_clipped = lane_value(cn, 0);
   float logsum = 0.0f;
 #pragma unroll
-  for (int n = 0; n < 4; ++n)
+  for (int n = 0; n < 8; ++n)
     logsum = __fadd_rn(logsum, __int_as_float(lane_value(__float_as_int(t), n)));
   const float x = lane == 0 ? logsum : 1.0f - float(r) / float(c);
   const float y = expf(x);

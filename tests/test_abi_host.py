@@ -70,13 +70,19 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert tb.tensorbleu_workspace_bytes(-1, 1, 16, 16, good) == 0
     assert tb.tensorbleu_workspace_bytes(4, 0, 16, 16, good) == 0
     assert tb.tensorbleu_workspace_bytes(4, 1, 0, 16, good) == 0
-    for bad in (tb.make_config(max_n=0, vocab_size=100), tb.make_config(max_n=5, vocab_size=100),
+    for bad in (tb.make_config(max_n=0, vocab_size=100), tb.make_config(max_n=9, vocab_size=100),
                 tb.make_config(vocab_size=0), tb.make_config(vocab_size=100, smoothing=7),
                 tb.make_config(vocab_size=100, path=3)):
         assert tb.tensorbleu_workspace_bytes(4, 1, 16, 16, bad) == 0
     lay = binding.tb_layout_t()
     rc = lib.tensorbleu_workspace_layout(4, 1, 16, 16, None, ctypes.byref(lay))
     assert rc == 1
+    # more than four orders: the FUSED path only
+    five = tb.make_config(max_n=5, vocab_size=100, path="global")
+    assert lib.tensorbleu_workspace_layout(4, 1, 16, 16, ctypes.byref(five), ctypes.byref(lay)) == 3
+    five = tb.make_config(max_n=5, vocab_size=100, path="auto")
+    assert lib.tensorbleu_workspace_layout(4, 1, 16, 16, ctypes.byref(five), ctypes.byref(lay)) == 0
+    assert lay.path == 1 and lay.global_ok == 0 and lay.fused_ok == 1
     # NULL data pointers / workspace are caught before any launch
     args = [None, 16, None, None, 16, None, 4, 1, ctypes.byref(good), None, None, None, 0, None]
     assert lib.tensorbleu_sentence(*args) == 1

@@ -42,7 +42,7 @@ def cached_small(*args, **kw):
 
 
 def path_supported(w, path, max_n=4):
-    cfg = tb.make_config(max_n=max_n, vocab_size=w.vocab, path="global")
+    cfg = tb.make_config(max_n=max_n, vocab_size=w.vocab, path="auto")
     lay = tb.binding.tb_layout_t()
     import ctypes
     tb.load_library().tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2],
@@ -334,3 +334,22 @@ def test_reference_count_out_of_range_is_clamped_and_flagged(path):
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, ref_count=clamped)
     np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
     assert np.abs(out.astype(np.float64) - ref.bleu).max() <= TOL
+
+
+# ------------------------------------------------------------------- more than four orders
+
+@pytest.mark.parametrize("N", [5, 6, 8])
+@pytest.mark.parametrize("seed,B,R,V,L", [
+    (301, 24, 2, 5, 40),           # tiny vocabulary: long n-grams still repeat
+    (302, 6, 3, 50257, 600),
+    (303, 4, 1, 262144, 1200),     # packed 8-grams would need 144 bits; hierarchical keys do not
+])
+def test_more_than_four_orders_on_the_fused_path(N, seed, B, R, V, L):
+    w = cached_small(seed, B=B, R=R, vocab=V, max_len=L)
+    d = Device(w)
+    weights = [1.0 / N] * N
+    for run in ALL_MODES:
+        check(w, run, "auto", max_n=N, weights=weights, d=d)
+    cfg = tb.make_config(max_n=N, vocab_size=w.vocab, path="global")
+    with pytest.raises(tb.TensorBLEUError):
+        tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg)

@@ -499,3 +499,32 @@ def test_reference_count_out_of_range_is_rejected():
         with pytest.raises(ValueError):
             oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len,
                         ref_count=np.array([1, 2, bad, 1], np.int32))
+
+
+# ------------------------------------------------------------------- more than four orders
+
+@pytest.mark.parametrize("N", [5, 6, 8])
+def test_more_than_four_orders_closed_forms_and_brute_force(N):
+    """Nothing in the definition is special about N = 4: identity, the prefix brevity penalty,
+    the single-substitution window count and the brute-force enumerator at N up to 8."""
+    L = 30
+    ref = list(range(100, 100 + L))
+    assert one(ref, [ref], max_n=N).bleu[0] == pytest.approx(1.0, abs=1e-15)
+    assert one(ref[:20], [ref], max_n=N).bleu[0] == pytest.approx(np.exp(1 - L / 20), rel=1e-13)
+    k = 11
+    cand = list(ref)
+    cand[k] = 7
+    res = one(cand, [ref], max_n=N)
+    expect = 1.0
+    for n in range(1, N + 1):
+        total = L - n + 1
+        covering = min(k, L - n) - max(0, k - n + 1) + 1
+        assert res.clipped[0, n - 1] == total - covering
+        expect *= ((total - covering) / total) ** (1.0 / N)
+    assert res.bleu[0] == pytest.approx(expect, rel=1e-12)
+    w = syn.random_small(91, B=10, R=2, vocab=3, max_len=14, min_len=1)
+    res = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, max_n=N)
+    for i in range(w.B):
+        refs = [w.refs[i, j, :w.ref_len[i, j]].tolist() for j in range(w.R)]
+        clipped, total = brute_force_stats(w.cand[i, :w.cand_len[i]].tolist(), refs, N)
+        assert res.clipped[i].tolist() == clipped and res.total[i].tolist() == total
