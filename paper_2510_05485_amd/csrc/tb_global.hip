@@ -625,33 +625,42 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
   GroupIndex gi(pb, g, GroupIndex::WaveOnly{});  // the loads of the lengths go out first
   int U4[4], total4[4] = {0, 0, 0, 0};
   uint32_t id[4][ITEMS];
-  // The id loads go out before the group's n-gram counts are known (those need the lengths):
-  // every slot of the group's range exists, slots past the count hold stale bytes that are never
-  // used.  They are unconditional (clamped slot, clamped order) so that the hardware's in-order
+  // The id loads are unconditional (clamped slot, clamped order) so that the hardware's in-order
   // load counter lets an order start as soon as its own ids have arrived; the ids of order o + 1
-  // are requested when order o starts, which spreads the memory traffic over the kernel.
-  auto request_ids = [&](int o) {
+  // are requested when order o starts, which spreads the memory traffic over the kernel.  The
+  // first order's request goes out before the lengths have arrived and therefore covers the
+  // group's whole slot range (slots past the count hold stale bytes that are never used); later
+  // requests stop at the order's real n-gram count (slots beyond re-read its last id, a cache
+  // hit).
+  auto request_ids = [&](int o, int last_slot) {
     const int n = min(first_order + o * a.split, pb.N);
     const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) id[o][i] = ginv[min(tid + i * nt, cap - 1)];
+    for (int i = 0; i < ITEMS; ++i) id[o][i] = ginv[min(tid + i * nt, last_slot)];
   };
-  request_ids(0);
+  request_ids(0, cap - 1);
 #pragma unroll
   for (int o = 0; o < 4; ++o)
     U4[o] = a.st.distinct[int64_t(g) * pb.N + min(first_order + o * a.split, pb.N) - 1];
   if (tid < 4) clipped_sum[tid] = 0;
   const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
+  gi.set_order(first_order);
 
 #pragma unroll
   for (int o = 0; o < 4; ++o) {
     const int n = first_order + o * a.split;
     if (n > pb.N) break;
-    if (o < 3) request_ids(o + 1);
     const int U = min(max(U4[o], 0), cap);
-    gi.set_order(n);
+    // this order's slot ranges (the index already holds order n) ...
     const int count = min(gi.start(pb.R + 1), ITEMS * nt);
     const int ccnt = gi.start(1);
+    const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
+    // ... then the next order's, for its request
+    if (o < 3) {
+      const int next = min(n + a.split, pb.N);
+      gi.set_order(next);
+      request_ids(o + 1, max(min(gi.start(pb.R + 1), cap) - 1, 0));
+    }
     if (o > 0) __syncthreads();  // the previous order's entries have been clipped
     {
       uint4* c4 = reinterpret_cast<uint4*>(cnt);
@@ -660,10 +669,9 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
     }
     __syncthreads();
 
-    // Sequence of a slot = number of sequences that end at or before it.  A wavefront's slots
-    // of one item are 64 consecutive ones, so that number is usually the same for all lanes and
-    // is found with one ballot over the lanes holding the sequence ends.
-    const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
+    // Sequence of a slot = number of sequences that end at or before it (seq_end: lane j holds
+    // the end of sequence j).  A wavefront's slots of one item are 64 consecutive ones, so that
+    // number is usually the same for all lanes and is found with one ballot.
     uint32_t first = 0;  // bit i: item i is the first occurrence of its candidate n-gram
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
