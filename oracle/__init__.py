@@ -53,6 +53,10 @@ def _load():
         lib.oracle_group_counts.argtypes = [i32p, ctypes.c_int, i32p, ctypes.c_int64, i32p,
                                             ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p, i32p,
                                             i32p]
+        lib.oracle_rouge_n.restype = ctypes.c_int
+        lib.oracle_rouge_n.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                       i32p, i32p, f64p, i32p]
         _lib = lib
     return _lib
 
@@ -148,3 +152,40 @@ def group_counts(cand_row: np.ndarray, cand_len: int, ref_rows: np.ndarray, ref_
                                 _p(grams, ctypes.c_int32), _p(cc, ctypes.c_int32),
                                 _p(rm, ctypes.c_int32))
     return grams[:k], cc[:k], rm[:k]
+
+
+@dataclass
+class RougeResult:
+    overlap: np.ndarray      # [B, R] int32: sum over n-grams of min(candidate count, reference count)
+    prf: np.ndarray          # [B, 3] float64: precision, recall, F of the best reference
+    best: np.ndarray         # [B] int32: index of that reference (highest F, lowest index on ties)
+
+
+def rouge_n(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.ndarray,
+            n: int = 2, beta: float = 1.0, ref_count: Optional[np.ndarray] = None) -> RougeResult:
+    """ROUGE-N of every candidate against its references (see oracle_rouge_n)."""
+    lib = _load()
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    refs = np.ascontiguousarray(refs, dtype=np.int32)
+    cand_len = np.ascontiguousarray(cand_len, dtype=np.int32)
+    ref_len = np.ascontiguousarray(ref_len, dtype=np.int32)
+    B, R = cand.shape[0], refs.shape[1]
+    assert refs.ndim == 3 and refs.shape[0] == B and ref_len.shape == (B, R)
+    assert (cand_len <= cand.shape[1]).all() and (ref_len <= refs.shape[2]).all()
+    assert (cand_len >= 0).all() and (ref_len >= 0).all()
+    rcnt = None
+    if ref_count is not None:
+        rcnt = np.ascontiguousarray(ref_count, dtype=np.int32)
+        assert rcnt.shape == (B,)
+    overlap = np.zeros((B, R), np.int32)
+    prf = np.zeros((B, 3), np.float64)
+    best = np.zeros(B, np.int32)
+    rc = lib.oracle_rouge_n(_p(cand, ctypes.c_int32), cand.shape[1], _p(cand_len, ctypes.c_int32),
+                            _p(refs, ctypes.c_int32), refs.shape[2], _p(ref_len, ctypes.c_int32),
+                            B, R, int(n), float(beta),
+                            _p(rcnt, ctypes.c_int32) if rcnt is not None else None,
+                            _p(overlap, ctypes.c_int32), _p(prf, ctypes.c_double),
+                            _p(best, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("oracle_rouge_n: invalid arguments")
+    return RougeResult(overlap, prf, best)
