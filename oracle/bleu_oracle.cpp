@@ -241,7 +241,11 @@ int oracle_group_counts(const int32_t* cand, int cand_len, const int32_t* refs,
 //   recall = overlap / (reference n-grams), precision = overlap / (candidate n-grams), each 0 when
 //   its denominator is 0, F = (1 + beta^2) P R / (R + beta^2 P), 0 when P + R = 0.
 // With several references the candidate is credited with the reference of the highest F (ties:
-// the lowest index).  prf[i] = precision, recall, F of that reference; best[i] = its index.
+// the lowest index).  F is proportional to overlap / (candidate n-grams + beta^2 * reference
+// n-grams); the choice between references is taken on that quotient in single precision
+// (float(overlap) / fmaf(beta^2, float(ref n-grams), float(cand n-grams))), the precision the GPU
+// path scores in, so that both sides break near-ties the same way.
+// prf[i] = precision, recall, F (fp64) of the chosen reference; best[i] = its index.
 // ref_count as in oracle_bleu.  Returns 0, or 1 on invalid arguments.
 int oracle_rouge_n(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
                    const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int B, int R,
@@ -254,7 +258,7 @@ int oracle_rouge_n(const int32_t* cand, int64_t cand_stride, const int32_t* cand
     const int c = cand_len[i];
     Counter cc = count_ngrams(cand + int64_t(i) * cand_stride, c, n);
     const double cand_total = double(std::max(c - n + 1, 0));
-    double best_f = -1.0;
+    float best_key = -1.0f;
     for (int j = 0; j < R; ++j) overlap[int64_t(i) * R + j] = 0;
     for (int j = 0; j < Ri; ++j) {
       const int r = ref_len[int64_t(i) * R + j];
@@ -270,8 +274,10 @@ int oracle_rouge_n(const int32_t* cand, int64_t cand_stride, const int32_t* cand
       const double Rc = ref_total > 0 ? double(ov) / ref_total : 0.0;
       const double b2 = beta * beta;
       const double F = (P + Rc > 0) ? (1.0 + b2) * P * Rc / (Rc + b2 * P) : 0.0;
-      if (F > best_f) {
-        best_f = F;
+      const float key = ov > 0 ? float(ov) / std::fmaf(float(b2), float(ref_total), float(cand_total))
+                               : 0.0f;
+      if (key > best_key) {
+        best_key = key;
         best[i] = j;
         prf[int64_t(i) * 3 + 0] = P;
         prf[int64_t(i) * 3 + 1] = Rc;
