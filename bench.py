@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "global"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rouge", type=int, default=0, metavar="N",
+                    help="also time ROUGE-N (tensorrouge_n, order N) on the same batch")
     ap.add_argument("--int64", action="store_true",
                     help="feed int64 token ids (the usual tokenizer dtype) instead of int32")
     ap.add_argument("--no-global-passes", action="store_true",
@@ -220,6 +222,18 @@ def main():
     }
     if global_section is not None and path != "global":
         result["global_path"] = global_section
+    if a.rouge:
+        # the ROUGE-N extension on the same batch (same kernel family, order a.rouge)
+        rws = tb.allocate_workspace(w.B, w.R, cs, rs, tb.make_config(
+            max_n=a.rouge, vocab_size=w.vocab, path="fused"), dev)
+        rfn = lambda: tb.tensorrouge_n(cand, cl, refs, rl, n=a.rouge, vocab_size=w.vocab,
+                                       workspace=rws)
+        for _ in range(a.warmup):
+            rfn()
+        r_ms = time_region(rfn, a.steps, torch)
+        result["rouge"] = {"n": a.rouge, "us": round(r_ms * 1e3, 2),
+                           "sentences_per_s": round(w.B / (r_ms * 1e-3), 1),
+                           "frac_hbm": round(alg["fused"] / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, run)
     print(json.dumps(result), flush=True)

@@ -154,6 +154,27 @@ int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand
                       const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                       void* hip_stream);
 
+/* ROUGE-N on the same n-gram counting core (the paper's Section 6 names ROUGE as the first
+ * metric the method extends to; the metric is Lin 2004).  For the single order n = cfg->max_n
+ * (1..8) and every candidate i and reference j:
+ *   overlap[i][j] = sum over distinct n-grams of min(count in candidate i, count in reference j),
+ *   precision = overlap / candidate n-grams, recall = overlap / reference n-grams (0 when the
+ *   denominator is 0), F = (1 + beta^2) P R / (R + beta^2 P) (0 when P + R = 0),
+ *   beta = cfg->smooth_param (<= 0 means 1).
+ * out_prf[B, 3] float32 (device) receives precision, recall and F of the candidate's best
+ * reference: the first one with the largest overlap / (candidate n-grams + beta^2 * reference
+ * n-grams), to which F is proportional.  overlap[B, R] int32 and best_ref[B] int32 (index of that
+ * reference) are optional device outputs (NULL to skip); entries of references beyond
+ * cfg->ref_count[i] are 0.  cfg->weights and cfg->smoothing are ignored; vocab_size, token_bytes
+ * and ref_count mean what they mean for BLEU.  Runs on the FUSED path only: shapes it does not
+ * support return TB_ERR_UNSUPPORTED.  Workspace: tensorbleu_workspace_bytes with force_path =
+ * TB_PATH_FUSED (or AUTO when AUTO resolves to FUSED).  stats: only device_status is used. */
+int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                  const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+                  int32_t R, const tb_config_t* cfg, float* out_prf, int32_t* overlap,
+                  int32_t* best_ref, const tb_stats_t* stats, void* workspace,
+                  size_t workspace_bytes, void* hip_stream);
+
 /* ---- The GLOBAL path one pass at a time (same arguments and workspace as above; the workspace
  * must have been sized with force_path = TB_PATH_GLOBAL).  tensorbleu_sentence on the GLOBAL
  * path is exactly pack, dictionary, count_clip, finalize in this order.  Exposed so that each

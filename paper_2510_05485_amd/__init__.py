@@ -7,6 +7,6 @@ from .binding import (  # noqa: F401
     LIB_PATH, TB_DEV_LENGTH_RANGE, TB_DEV_TOKEN_RANGE, Stats, TensorBLEUError, allocate_workspace, load_library, make_config,
     tensorbleu_corpus, tensorbleu_count_clip, tensorbleu_dictionary, tensorbleu_finalize,
     tensorbleu_pack, tensorbleu_sentence, tensorbleu_status_string, tensorbleu_workspace_bytes,
-    tensorbleu_workspace_layout,
+    tensorbleu_workspace_layout, tensorrouge_n,
 )
-from .api import BleuScorer, corpus_bleu, sentence_bleu  # noqa: F401
+from .api import BleuScorer, corpus_bleu, rouge_n, sentence_bleu  # noqa: F401

@@ -92,3 +92,13 @@ def corpus_bleu(cand, cand_len, refs, ref_len, *, vocab_size: int, **kw) -> torc
     s = BleuScorer(cand.shape[0], refs.shape[1], cand.shape[1], refs.shape[2],
                    vocab_size=vocab_size, device=cand.device, **kw)
     return s.corpus(cand, cand_len, refs, ref_len).clone()
+
+
+def rouge_n(cand, cand_len, refs, ref_len, *, n: int = 2, beta: float = 1.0, vocab_size: int,
+            ref_count=None) -> torch.Tensor:
+    """ROUGE-N precision, recall and F (float32 [B, 3]) of every candidate against the best of
+    its references; runs `tensorrouge_n` on the current stream."""
+    refs = _refs3d(refs)
+    rc = None if ref_count is None else _len32(ref_count).contiguous()
+    return _b.tensorrouge_n(cand, _len32(cand_len), refs, _len32(ref_len), n=n, beta=beta,
+                            vocab_size=vocab_size, ref_count=rc)

@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.tensorbleu_sentence.argtypes = full
     lib.tensorbleu_corpus.restype = ctypes.c_int
     lib.tensorbleu_corpus.argtypes = full
+    lib.tensorrouge_n.restype = ctypes.c_int
+    lib.tensorrouge_n.argtypes = [vp, i64, vp, vp, i64, vp, i32, i32, cfgp, vp, vp, vp, stp, vp, sz, vp]
     lib.tensorbleu_pack.restype = ctypes.c_int
     lib.tensorbleu_pack.argtypes = [vp, i64, vp, vp, i64, vp, i32, i32, cfgp, stp, vp, sz, vp]
     stage = [vp, vp, i64, i64, i32, i32, cfgp, stp, vp, sz, vp]
@@ -253,6 +255,37 @@ def tensorbleu_corpus(cand, cand_len, refs, ref_len, cfg: tb_config_t,
         out = torch.zeros(1, dtype=torch.float32, device=cand.device)
     return _full("tensorbleu_corpus", cand, cand_len, refs, ref_len, cfg, out, stats, workspace,
                  stream)
+
+
+def tensorrouge_n(cand, cand_len, refs, ref_len, n: int = 2, beta: float = 1.0, *,
+                  vocab_size: int, ref_count: Optional[torch.Tensor] = None,
+                  want_overlap: bool = False, want_best: bool = False,
+                  workspace: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
+                  stream=None):
+    """ROUGE-N of every candidate against its references: float32 [B, 3] (precision, recall, F of
+    the best reference), plus overlap int32 [B, R] and best-reference index int32 [B] on request
+    (returned as a tuple then)."""
+    cfg = make_config(max_n=n, smooth_param=beta, vocab_size=vocab_size, path="fused",
+                      ref_count=ref_count)
+    b = _batch(cand, cand_len, refs, ref_len, cfg)
+    if workspace is None:
+        workspace = allocate_workspace(b.B, b.R, b.cand_stride, b.ref_stride, cfg, b.cand.device)
+    dev = b.cand.device
+    out = torch.zeros(b.B, 3, dtype=torch.float32, device=dev)
+    overlap = torch.zeros(b.B, b.R, dtype=torch.int32, device=dev) if want_overlap else None
+    best = torch.zeros(b.B, dtype=torch.int32, device=dev) if want_best else None
+    st = stats.as_struct() if stats is not None else None
+    rc = load_library().tensorrouge_n(
+        b.cand.data_ptr(), b.cand_stride, b.cand_len.data_ptr(), b.refs.data_ptr(), b.ref_stride,
+        b.ref_len.data_ptr(), b.B, b.R, ctypes.byref(cfg), out.data_ptr(),
+        overlap.data_ptr() if overlap is not None else None,
+        best.data_ptr() if best is not None else None,
+        ctypes.byref(st) if st is not None else None, workspace.data_ptr(), workspace.numel(),
+        _stream_ptr(stream))
+    _check(rc, "tensorrouge_n")
+    if want_overlap or want_best:
+        return out, overlap, best
+    return out
 
 
 def tensorbleu_pack(cand, cand_len, refs, ref_len, cfg, workspace, stats=None, stream=None):

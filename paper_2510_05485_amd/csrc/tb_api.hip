@@ -242,6 +242,33 @@ int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand
                  stats, workspace, workspace_bytes, hip_stream, true);
 }
 
+int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                  const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
+                  int32_t R, const tb_config_t* cfg, float* out_prf, int32_t* overlap,
+                  int32_t* best_ref, const tb_stats_t* stats, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  Call c;
+  int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
+                   workspace, workspace_bytes, hip_stream, true, TB_PATH_FUSED, &c);
+  if (rc != TB_OK || B == 0) return rc;
+  if (!out_prf) return TB_ERR_INVALID_ARG;
+  const float beta = cfg->smooth_param > 0.0f ? cfg->smooth_param : 1.0f;
+  RougeOut ro;
+  ro.prf = out_prf;
+  ro.overlap = overlap;
+  ro.best = best_ref;
+  ro.beta2 = float(double(beta) * double(beta));
+  // the integer BLEU statistics of the run are scratch here: never the caller's arrays
+  unsigned char* w = static_cast<unsigned char*>(workspace);
+  const tb_layout_t& L = c.plans.layout;
+  StatPtrs st = c.st;
+  st.clipped = reinterpret_cast<int32_t*>(w + L.clipped_off);
+  st.total = reinterpret_cast<int32_t*>(w + L.total_off);
+  st.closest = reinterpret_cast<int32_t*>(w + L.closest_off);
+  st.distinct = reinterpret_cast<int32_t*>(w + L.distinct_off);
+  return hip_rc(launch_fused(c.pb, c.plans.fused, st, c.sp, nullptr, c.stream, &ro));
+}
+
 int tensorbleu_pack(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                     const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
                     int32_t R, const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,

@@ -27,6 +27,11 @@ struct FusedArgs {
   StatPtrs st;
   ScoreParams sp;
   float* out;           // per-sentence scores, or null
+  // ROUGE-N mode (fused_kernel<.., true>): order N = pb.N only
+  float* rouge_prf;     // [B, 3] precision, recall, F of the best reference
+  int32_t* rouge_overlap;  // [B, R] or null
+  int32_t* rouge_best;  // [B] or null
+  float beta2;          // beta squared
   int table_slots;      // power of two
   int table_shift;      // 32 - log2(table_slots)
   int words;            // 32-bit counter words per id: ceil((R + 1) / 2)
@@ -169,12 +174,16 @@ struct ProbeTable {
 // eight wavefronts per SIMD, and on this hardware a kernel that allocates more than 80 scalar
 // registers gets only seven (measured: the same kernel at 96 runs one workgroup per compute
 // unit and takes 34 us instead of 25 us at the headline shape).
-template <typename TokT, int SITEMS>
+// ROUGE: the same pipeline scores ROUGE-N for n = N instead of BLEU: at the last order the
+// creator of an entry adds min(candidate count, reference j's count) to an overlap sum per
+// reference, and the tail turns the sums into precision, recall and F.
+template <typename TokT, int SITEMS, bool ROUGE>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(80)))
 void fused_kernel(FusedArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_part[8];              // per order: clipped sum (low 16) | distinct count (high 16)
   __shared__ int s_end[kMaxFusedSeqs];   // end of each sequence in back-to-back token indices
+  __shared__ int s_overlap[ROUGE ? kMaxFusedSeqs : 1];  // ROUGE: overlap with each reference
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
   const int lane = tid & (kWave - 1), nwaves = nt / kWave;
@@ -208,6 +217,7 @@ void fused_kernel(FusedArgs a) {
     s_end[lane] = incl;
   }
   if (tid < 8) s_part[tid] = 0;
+  if (ROUGE && tid < kMaxFusedSeqs) s_overlap[tid] = 0;
   const int total_tokens = min(lane_value(incl, R), SITEMS * nt);
   const int cand_len = lane_value(my_len, 0);
 
@@ -341,14 +351,21 @@ void fused_kernel(FusedArgs a) {
       if (st >> 31) {
         const uint32_t base = __umul24(uint32_t(k), W);
         const uint32_t w0 = cnt[base];
+        const uint32_t cc = w0 & 0xFFFFu;  // candidate count; reference j is field j + 1
         uint32_t mx = w0 >> 16;
         cnt[base] = 0;
+        if (ROUGE && n == N && min(cc, mx)) atomicAdd(&s_overlap[0], int(min(cc, mx)));
         for (uint32_t w = 1; w < W; ++w) {
           const uint32_t x = cnt[base + w];
           mx = max(mx, max(x & 0xFFFFu, x >> 16));
           cnt[base + w] = 0;
+          if (ROUGE && n == N) {  // per reference: min(candidate count, its own count)
+            const uint32_t m_lo = min(cc, x & 0xFFFFu), m_hi = min(cc, x >> 16);
+            if (m_lo) atomicAdd(&s_overlap[2 * w - 1], int(m_lo));
+            if (m_hi) atomicAdd(&s_overlap[2 * w], int(m_hi));
+          }
         }
-        part += int(min(w0 & 0xFFFFu, mx)) + 0x10000;
+        part += int(min(cc, mx)) + 0x10000;
         table[st & 0xFFFFu] = kEmptySlot;
       }
     }
@@ -377,24 +394,59 @@ void fused_kernel(FusedArgs a) {
         bd = d;
       }
     }
-    const float score = bleu_from_stats_wave(cn, tn, c, best, a.sp);
-    if (lane == 0) {
-      a.st.closest[g] = best;
-      if (a.out) a.out[g] = score;
+    if (!ROUGE) {
+      const float score = bleu_from_stats_wave(cn, tn, c, best, a.sp);
+      if (lane == 0) {
+        a.st.closest[g] = best;
+        if (a.out) a.out[g] = score;
+      }
+    } else {
+      // lane j = 1..used: reference j - 1.  F is proportional to overlap / (cand + beta^2 ref)
+      // n-grams; the best reference is the first one with the largest such quotient.
+      const bool ref_lane = lane >= 1 && lane <= used;
+      const int ov = ref_lane ? s_overlap[(lane - 1) & (kMaxFusedSeqs - 1)] : 0;
+      const float ct = float(max(c - N + 1, 0)), rt = float(max(my_len - N + 1, 0));
+      const float key = (ref_lane && ov > 0) ? float(ov) / __fmaf_rn(a.beta2, rt, ct) : 0.0f;
+      if (a.rouge_overlap && lane >= 1 && lane <= R)
+        a.rouge_overlap[int64_t(g) * R + lane - 1] = ov;
+      int best_j = 1;
+      float best_key = __int_as_float(lane_value(__float_as_int(key), 1));
+      for (int j = 2; j <= used; ++j) {
+        const float kj = __int_as_float(lane_value(__float_as_int(key), j));
+        if (kj > best_key) {
+          best_key = kj;
+          best_j = j;
+        }
+      }
+      const float p = ct > 0.0f ? float(ov) / ct : 0.0f;
+      const float r = rt > 0.0f ? float(ov) / rt : 0.0f;
+      const float f = (p + r > 0.0f) ? (1.0f + a.beta2) * p * r / (r + a.beta2 * p) : 0.0f;
+      if (lane == best_j) {
+        a.rouge_prf[int64_t(g) * 3 + 0] = p;
+        a.rouge_prf[int64_t(g) * 3 + 1] = r;
+        a.rouge_prf[int64_t(g) * 3 + 2] = f;
+        if (a.rouge_best) a.rouge_best[g] = best_j - 1;
+      }
     }
   }
 }
 
+template <typename TokT, int SITEMS, bool ROUGE>
+hipError_t launch_fused_mode(const FusedArgs& a, const FusedPlan& plan, int blocks,
+                             hipStream_t s) {
+  hipError_t e =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<TokT, SITEMS, ROUGE>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.lds_bytes));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((fused_kernel<TokT, SITEMS, ROUGE>), dim3(blocks), dim3(plan.threads),
+                     plan.lds_bytes, s, a);
+  return hipGetLastError();
+}
 template <typename TokT, int SITEMS>
 hipError_t launch_fused_items(const FusedArgs& a, const FusedPlan& plan, int blocks,
                               hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<TokT, SITEMS>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     int(plan.lds_bytes));
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((fused_kernel<TokT, SITEMS>), dim3(blocks), dim3(plan.threads),
-                     plan.lds_bytes, s, a);
-  return hipGetLastError();
+  return a.rouge_prf ? launch_fused_mode<TokT, SITEMS, true>(a, plan, blocks, s)
+                     : launch_fused_mode<TokT, SITEMS, false>(a, plan, blocks, s);
 }
 
 template <typename TokT>
@@ -411,12 +463,17 @@ hipError_t launch_fused_tok(const FusedArgs& a, const FusedPlan& plan, int block
 }
 
 hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs& st,
-                        const ScoreParams& sp, float* out_bleu_or_null, hipStream_t s) {
+                        const ScoreParams& sp, float* out_bleu_or_null, hipStream_t s,
+                        const RougeOut* rouge) {
   FusedArgs a;
   a.pb = pb;
   a.st = st;
   a.sp = sp;
   a.out = out_bleu_or_null;
+  a.rouge_prf = rouge ? rouge->prf : nullptr;
+  a.rouge_overlap = rouge ? rouge->overlap : nullptr;
+  a.rouge_best = rouge ? rouge->best : nullptr;
+  a.beta2 = rouge ? rouge->beta2 : 1.0f;
   a.table_slots = plan.table_slots;
   int lg = 0;
   while ((1 << lg) < plan.table_slots) ++lg;
