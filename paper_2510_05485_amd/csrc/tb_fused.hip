@@ -11,8 +11,9 @@
 //      the offset of Section 3.3 step 1 achieves,
 //   3. lets the thread that created an entry take the maximum over the reference fields and the
 //      minimum with the candidate field (Section 3.3 step 3) and sum it,
-// and finally lane 0 forms the brevity penalty, smoothing and geometric mean (Section 3.4).
-// HBM traffic is the tokens in and one score (plus optional integer statistics) out.
+// and finally wavefront 0 forms the brevity penalty, smoothing and geometric mean (Section 3.4),
+// one order per lane.  HBM traffic is the tokens in and one score (plus optional integer
+// statistics) out.  The same kernel, instantiated with ROUGE = true, scores ROUGE-N instead.
 #include "tb_kernels.h"
 #include "tb_score.h"
 
@@ -102,7 +103,9 @@ bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
 // hashing.  One 32-bit multiply hashes the key: the top bits of the product pick the slot, lower
 // bits the (odd) probe step, so a probe sequence reaches every slot of the power-of-two table.
 // A probe loop ends at the key or at an empty slot; the table is at most 3/4 full and the probe
-// count is capped at the table size.  (Measured on this hardware: plain divergent loops beat
+// count is capped at the table size.  The loops have a single exit (one condition, no break):
+// that halves the instructions the compiler emits per probe round.  (Measured on this hardware:
+// plain divergent loops beat
 // variants that keep all lanes in lock step until the slowest is done, and probing slot pairs
 // or 4-slot buckets with wider LDS reads did not pay either.)
 struct ProbeTable {
