@@ -1,0 +1,79 @@
+"""Randomised differential sweep: a few hundred small batches with random shapes, vocabularies,
+orders (1..8), weights, smoothing modes, paths, reference counts and id dtypes, each compared
+with the CPU oracle (integers bit-exactly, scores within 1e-5), BLEU and ROUGE-N alike."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_05485_amd as tb
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+MODES = [("none", 0.0), ("floor", 0.1), ("add-k", 1.0), ("exp", 0.0)]
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+@pytest.mark.parametrize("sweep_seed", [11, 12, 13])
+def test_random_sweep(sweep_seed):
+    rng = np.random.default_rng(sweep_seed)
+    worst = 0.0
+    for case in range(120):
+        B = int(rng.integers(1, 40))
+        R = int(rng.choice([1, 1, 2, 3, 4, 7, 20]))
+        V = int(rng.choice([2, 3, 5, 17, 64, 1000, 50257, 65536, 262144, 2 ** 31 - 1]))
+        L = int(rng.choice([1, 2, 3, 5, 9, 30, 64, 65, 127, 300, 700, 1500]))
+        L = min(L, 12000 // (1 + R))
+        seed = int(rng.integers(1, 1 << 30))
+        w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=int(rng.integers(0, 2)))
+        N = int(rng.choice([1, 2, 3, 4, 4, 4, 5, 8]))
+        path = str(rng.choice(["global", "fused", "auto"])) if N <= 4 else "auto"
+        mode, param = MODES[int(rng.integers(0, 4))]
+        rc = syn.ref_counts(seed, B, R) if rng.random() < 0.4 else None
+        i64 = rng.random() < 0.3
+        weights = [1.0 / N] * N if rng.random() < 0.7 else list(rng.random(N).round(3) + 0.01)
+        tag = (f"sweep={sweep_seed} case={case} seed={seed} B={B} R={R} V={V} L={L} N={N} "
+               f"path={path} mode={mode} ref_count={rc is not None} int64={i64}")
+        ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, max_n=N, weights=weights,
+                          smoothing=mode, smooth_param=param, ref_count=rc, threads=4)
+        drc = dev(rc) if rc is not None else None
+        cfg = tb.make_config(max_n=N, weights=weights, smoothing=mode, smooth_param=param,
+                             vocab_size=V, path=path, ref_count=drc)
+        cand, refs = dev(w.cand), dev(w.refs)
+        if i64:
+            cand, refs = cand.long(), refs.long()
+        cl, rl = dev(w.cand_len), dev(w.ref_len)
+        try:
+            lay = tb.tensorbleu_workspace_layout(B, R, cand.shape[1], refs.shape[2], cfg)
+        except tb.TensorBLEUError:
+            continue                                        # shape outside the forced path
+        for corpus in (False, True):
+            st = tb.Stats.allocate(B, N, DEV)
+            fn = tb.tensorbleu_corpus if corpus else tb.tensorbleu_sentence
+            out = fn(cand, cl, refs, rl, cfg, stats=st).cpu().numpy()
+            assert st.device_status.item() == 0, tag
+            assert (st.clipped.cpu().numpy() == ref.clipped).all(), tag
+            assert (st.total.cpu().numpy() == ref.total).all(), tag
+            assert (st.closest_ref_len.cpu().numpy() == ref.closest_ref_len).all(), tag
+            if corpus:
+                assert (st.corpus_stats.cpu().numpy() == ref.corpus_stats).all(), tag
+                err = abs(float(out[0]) - ref.corpus_bleu)
+            else:
+                err = float(np.abs(out.astype(np.float64) - ref.bleu).max())
+            assert err <= 1e-5, (tag, err)
+            worst = max(worst, err)
+        if lay.fused_ok:
+            n = int(rng.integers(1, 7))
+            beta = float(rng.choice([0.5, 1.0, 2.0]))
+            rr = oracle.rouge_n(w.cand, w.cand_len, w.refs, w.ref_len, n=n, beta=beta,
+                                ref_count=rc)
+            o, ov, best = tb.tensorrouge_n(cand, cl, refs, rl, n=n, beta=beta, vocab_size=V,
+                                           ref_count=drc, want_overlap=True, want_best=True)
+            assert (ov.cpu().numpy() == rr.overlap).all(), ("rouge overlap", tag, n)
+            assert (best.cpu().numpy() == rr.best).all(), ("rouge best", tag, n, beta)
+            assert np.abs(o.cpu().numpy().astype(np.float64) - rr.prf).max() <= 1e-5, tag
+    assert worst <= 1e-5
