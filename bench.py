@@ -49,6 +49,28 @@ def time_region(fn, iters, torch):
     return start.elapsed_time(stop) / iters
 
 
+def achievable_hbm(torch, dev):
+    """What plain device kernels reach on this machine, in the same run: a fill (write only), a sum
+    (read only) and a copy, at a size like the GLOBAL path's arrays (128 MiB: partly served by
+    the 256 MB last-level cache) and at 1 GiB (beyond it).  GB/s of bytes read + written."""
+    out = {}
+    for mib in (128, 1024):
+        n = mib * 1024 * 1024 // 8
+        x = torch.empty(n, dtype=torch.int64, device=dev)
+        y = torch.empty_like(x)
+        x.fill_(1)
+        y.fill_(1)
+        b = mib * 1024 * 1024
+        for name, fn, nbytes in (("fill", lambda: y.fill_(7), b), ("read", lambda: x.sum(), b),
+                                 ("copy", lambda: y.copy_(x), 2 * b)):
+            for _ in range(3):
+                fn()
+            ms = time_region(fn, 20, torch)
+            out[f"{name}_{mib}MiB"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+        del x, y
+    return out
+
+
 def cpu_baseline(w, run, budget_s=12.0):
     """The oracle, as it stands, on the host cores: sentences/s on a bounded sample."""
     import oracle
@@ -89,6 +111,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "global"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hbm-ceiling", action="store_true",
+                    help="skip the fill / read / copy bandwidth check of plain device kernels")
     ap.add_argument("--rouge", type=int, default=0, metavar="N",
                     help="also time ROUGE-N (tensorrouge_n, order N) on the same batch")
     ap.add_argument("--int64", action="store_true",
@@ -234,6 +258,8 @@ def main():
         result["rouge"] = {"n": a.rouge, "us": round(r_ms * 1e3, 2),
                            "sentences_per_s": round(w.B / (r_ms * 1e-3), 1),
                            "frac_hbm": round(alg["fused"] / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    if not a.no_hbm_ceiling:
+        result["achievable_hbm_GBps"] = achievable_hbm(torch, dev)
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, run)
     print(json.dumps(result), flush=True)
