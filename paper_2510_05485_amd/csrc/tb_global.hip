@@ -611,6 +611,7 @@ bool plan_count(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int 
 // minimum with the candidate field), so no sweep over the table is needed.
 template <int ITEMS>
 __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
+  static_assert(ITEMS % 2 == 0, "items are processed in pairs");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int clipped_sum[4];
   const Problem& pb = a.pb;
@@ -621,6 +622,12 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
   const int W = a.words;
   uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
   const uint32_t gbase = uint32_t(int64_t(g) * pb.group_cap);
+
+  // Slot layout: a wavefront owns blocks of 128 consecutive slots (block p of wavefront w starts
+  // at 128 * w + p * 2 * nt); lane l holds the slots l and 64 + l of each block as items 2p and
+  // 2p + 1.  The scalar work that finds a block's sequence is then shared by 128 n-grams.
+  const int wave_block = __builtin_amdgcn_readfirstlane(2 * (tid - lane));
+  auto block_start = [&](int p) { return wave_block + p * 2 * nt; };
 
   GroupIndex gi(pb, g, GroupIndex::WaveOnly{});  // the loads of the lengths go out first
   int U4[4], total4[4] = {0, 0, 0, 0};
@@ -636,14 +643,14 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
     const int n = min(first_order + o * a.split, pb.N);
     const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) id[o][i] = ginv[min(tid + i * nt, last_slot)];
+    for (int i = 0; i < ITEMS; ++i)
+      id[o][i] = ginv[min(block_start(i >> 1) + (i & 1) * kWave + lane, last_slot)];
   };
   request_ids(0, cap - 1);
 #pragma unroll
   for (int o = 0; o < 4; ++o)
     U4[o] = a.st.distinct[int64_t(g) * pb.N + min(first_order + o * a.split, pb.N) - 1];
   if (tid < 4) clipped_sum[tid] = 0;
-  const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
   gi.set_order(first_order);
 
 #pragma unroll
@@ -670,38 +677,40 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
     __syncthreads();
 
     // Sequence of a slot = number of sequences that end at or before it (seq_end: lane j holds
-    // the end of sequence j).  A wavefront's slots of one item are 64 consecutive ones, so that
-    // number is usually the same for all lanes and is found with one ballot.
+    // the end of sequence j).  A block's 128 slots usually lie inside one sequence, which one
+    // ballot finds; then sequence, counter word and addend are scalars for both items.
     uint32_t first = 0;  // bit i: item i is the first occurrence of its candidate n-gram
+    // one n-gram whose sequence is known per lane
+    auto count_one = [&](int i, uint32_t u, int f) {
+      if (f <= pb.R && u < uint32_t(U)) {
+        uint32_t* word = &cnt[__umul24(u, uint32_t(W)) + uint32_t(f >> 1)];
+        if (f == 0) {
+          if ((atomicAdd(word, 1u) & 0xFFFFu) == 0u) first |= 1u << i;
+        } else {
+          atomicAdd(word, (f & 1) ? 0x10000u : 1u);
+        }
+      }
+    };
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      const int k0 = wave_first + i * nt;
+    for (int p = 0; p < ITEMS / 2; ++p) {
+      const int k0 = block_start(p);
       if (k0 >= count) break;
       const int f = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0));  // <= R: k0 < count
       const int f_end = __builtin_amdgcn_readlane(seq_end, f);
-      const uint32_t u = id[o][i] - gbase;
-      if (k0 + kWave <= f_end) {  // the whole wavefront is inside sequence f
-        if (u < uint32_t(U)) {
-          uint32_t* word = &cnt[__umul24(u, uint32_t(W)) + uint32_t(f >> 1)];
-          if (f == 0) {
-            if ((atomicAdd(word, 1u) & 0xFFFFu) == 0u) first |= 1u << i;
-          } else {
-            atomicAdd(word, (f & 1) ? 0x10000u : 1u);
-          }
+      const uint32_t u0 = id[o][2 * p] - gbase, u1 = id[o][2 * p + 1] - gbase;
+      if (k0 + 2 * kWave <= f_end) {  // the whole block is inside sequence f
+        count_one(2 * p, u0, f);
+        count_one(2 * p + 1, u1, f);
+      } else {  // the block straddles sequences (or the end): sequence per lane and half
+        const int f_hi = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0 + 2 * kWave - 1));
+        int fl0 = f, fl1 = f;
+        for (int j = f; j < f_hi; ++j) {
+          const int e = __builtin_amdgcn_readlane(seq_end, j);
+          fl0 += (k0 + lane >= e);
+          fl1 += (k0 + kWave + lane >= e);
         }
-      } else {  // the wavefront straddles sequences: sequence per lane
-        const int k = k0 + lane;
-        const int f_hi = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0 + kWave - 1));
-        int fl = f;
-        for (int j = f; j < f_hi; ++j) fl += (k >= __builtin_amdgcn_readlane(seq_end, j));
-        if (fl <= pb.R && u < uint32_t(U)) {
-          uint32_t* word = &cnt[__umul24(u, uint32_t(W)) + uint32_t(fl >> 1)];
-          if (fl == 0) {
-            if ((atomicAdd(word, 1u) & 0xFFFFu) == 0u) first |= 1u << i;
-          } else {
-            atomicAdd(word, (fl & 1) ? 0x10000u : 1u);
-          }
-        }
+        count_one(2 * p, u0, fl0);
+        count_one(2 * p + 1, u1, fl1);
       }
     }
     __syncthreads();
@@ -709,7 +718,8 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
     int part = 0;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-      if (wave_first + i * nt >= ccnt) break;  // only candidate slots can be first occurrences
+      // only candidate slots can be first occurrences
+      if (block_start(i >> 1) + (i & 1) * kWave >= ccnt) break;
       if ((first >> i) & 1u) {
         const uint32_t* e = &cnt[__umul24(id[o][i] - gbase, uint32_t(W))];
         const uint32_t w0 = e[0];
