@@ -68,7 +68,8 @@ enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0,
 
 typedef struct tb_config {
   int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1: "typically n=1 to 4");
-                           the GLOBAL path handles N <= 4, larger N needs the FUSED path */
+                           the GLOBAL path packs whole n-grams into keys and so needs
+                           N * bits <= 128, the FUSED path has no such limit */
   float   weights[8];   /* w_1..w_N of the BLEU equation, used as given (not renormalised);
                            w_n == 0 drops order n; all zero means uniform 1/N */
   int32_t smoothing;    /* tb_smooth_t */
@@ -112,10 +113,10 @@ typedef struct tb_stats {
 typedef struct tb_layout {
   int32_t path;            /* path AUTO resolves to for this shape (TB_PATH_FUSED / TB_PATH_GLOBAL) */
   int32_t bits;            /* ceil(log2(vocab_size)), at least 1 */
-  int32_t key_bytes[4];    /* 8 or 16 per order */
+  int32_t key_bytes[8];    /* 8 or 16 per order */
   int64_t group_cap;       /* cand_stride + R*ref_stride */
-  size_t  keys_off[4];     /* packed keys of order n: B*group_cap entries of key_bytes[n-1] */
-  size_t  inv_off[4];      /* uint32 offset ids (g*group_cap + dense id in the group's dictionary) */
+  size_t  keys_off[8];     /* packed keys of order n: B*group_cap entries of key_bytes[n-1] */
+  size_t  inv_off[8];      /* uint32 offset ids (g*group_cap + dense id in the group's dictionary) */
   size_t  clipped_off, total_off, closest_off, distinct_off; /* int32 [B,N],[B,N],[B],[B,N] */
   size_t  corpus_off;      /* int64 [2N+2] */
   size_t  bytes;           /* total workspace size for this path */

@@ -44,8 +44,8 @@ class tb_stats_t(ctypes.Structure):
 
 class tb_layout_t(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("bits", ctypes.c_int32),
-                ("key_bytes", ctypes.c_int32 * 4), ("group_cap", ctypes.c_int64),
-                ("keys_off", ctypes.c_size_t * 4), ("inv_off", ctypes.c_size_t * 4),
+                ("key_bytes", ctypes.c_int32 * 8), ("group_cap", ctypes.c_int64),
+                ("keys_off", ctypes.c_size_t * 8), ("inv_off", ctypes.c_size_t * 8),
                 ("clipped_off", ctypes.c_size_t), ("total_off", ctypes.c_size_t),
                 ("closest_off", ctypes.c_size_t), ("distinct_off", ctypes.c_size_t),
                 ("corpus_off", ctypes.c_size_t), ("bytes", ctypes.c_size_t),

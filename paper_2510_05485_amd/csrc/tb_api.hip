@@ -45,12 +45,12 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   std::memset(&L, 0, sizeof(L));
   const int N = cfg->max_n;
   L.bits = ceil_log2(cfg->vocab_size);
-  for (int n = 1; n <= 4; ++n) L.key_bytes[n - 1] = (n * L.bits > 64) ? 16 : 8;
+  for (int n = 1; n <= 8; ++n) L.key_bytes[n - 1] = (n * L.bits > 64) ? 16 : 8;
   if (cand_stride > (int64_t(1) << 30) || ref_stride > (int64_t(1) << 30) || R > (1 << 20))
     return TB_ERR_UNSUPPORTED;
   L.group_cap = cand_stride + int64_t(R) * ref_stride;
   const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
-  const bool global_n = N <= 4;  // the GLOBAL path materialises at most four orders
+  const bool global_n = N * L.bits <= 128;  // the GLOBAL path packs whole n-grams into keys
   const bool lds_ok = global_n &&
                       plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
                       plan_count(L.group_cap, cand_stride, ref_stride, R, &p->count);
@@ -136,7 +136,7 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   pb.vocab = cfg->vocab_size;
   pb.tok64 = cfg->token_bytes == 8;
   pb.status = stats ? stats->device_status : nullptr;
-  for (int n = 0; n < 4; ++n) {
+  for (int n = 0; n < 8; ++n) {
     c->ws.keys[n] = (L.path == TB_PATH_GLOBAL && n < pb.N) ? w + L.keys_off[n] : nullptr;
     c->ws.inv[n] = (L.path == TB_PATH_GLOBAL && n < pb.N)
                        ? reinterpret_cast<uint32_t*>(w + L.inv_off[n]) : nullptr;

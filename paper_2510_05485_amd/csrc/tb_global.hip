@@ -114,7 +114,7 @@ __device__ __forceinline__ void store_key(void* base, int wide, int64_t slot, ui
 }
 
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
-  __shared__ int32_t tok[kPackTile + 4];
+  __shared__ int32_t tok[kPackTile + 8];
   const Problem& pb = a.pb;
   const int per_group = a.cand_chunks + pb.R * a.ref_chunks;
   const int g = blockIdx.x / per_group;
@@ -140,10 +140,19 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
   const int p0 = chunk * kPackTile;
   if (p0 >= len) return;  // uniform over the workgroup
   // where this sequence's n-grams start inside the group's compact range, per order
-  int base[4];
+  int base[8];
+  {
+    GroupIndex gi(pb, g);
 #pragma unroll
-  for (int n = 1; n <= 4; ++n) base[n - 1] = GroupIndex(pb, g, n).start(j);
-  const int ntok = min(kPackTile + 3, len - p0);
+    for (int n = 1; n <= 8; ++n) {
+      base[n - 1] = 0;
+      if (n <= pb.N) {
+        gi.set_order(n);
+        base[n - 1] = gi.start(j);
+      }
+    }
+  }
+  const int ntok = min(kPackTile + pb.N - 1, len - p0);
   bool bad = false;
   for (int i = threadIdx.x; i < ntok; i += kPackThreads) {
     const int32_t t = load_token(rows, row + p0 + i, pb.tok64);
@@ -162,7 +171,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     uint64_t lo = uint32_t(tok[q]), hi = 0;
     store_key(a.ws.keys[0], a.ws.wide[0], gslot + base[0] + q, lo, hi);
 #pragma unroll
-    for (int n = 2; n <= 4; ++n) {
+    for (int n = 2; n <= 8; ++n) {
       if (n > pb.N || n > avail) break;
       hi = (hi << bits) | (lo >> (64 - bits));
       lo = (lo << bits) | uint32_t(tok[q + n - 1]);
@@ -193,7 +202,7 @@ struct DictArgs {
   int table_shift;  // 32 - log2(table_slots)
   uint32_t lds_table_off;
   int slot32_mask;  // bit n: the keys of order n fit 32 bits
-  int orders[8];   // wide kernel: its orders; narrow kernel: pairs (orders[2p], orders[2p + 1])
+  int orders[16];  // wide kernel: its orders; narrow kernel: pairs (orders[2p], orders[2p + 1])
   int num_orders;  // wide kernel
   int num_pairs;   // narrow kernel: workgroups per group
 };
@@ -521,8 +530,8 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
     a.table_shift = shift_of(plan.narrow_slots);
     a.lds_table_off = 0;
     a.slot32_mask = plan.slot32_mask;
-    // Pairs of about equal cost (cost grows with the order): four orders -> (1st, 4th) and
-    // (2nd, 3rd).  An odd number of orders would leave workgroups of unequal length, which
+    // Pairs of about equal cost (cost grows with the order): the cheapest with the most
+    // expensive, e.g. four orders -> (1st, 4th) and (2nd, 3rd).  An odd number of orders would leave workgroups of unequal length, which
     // measured slower than one order per workgroup; a small batch keeps one order per workgroup
     // so that the GPU still fills.
     const int m = plan.n_narrow;
@@ -535,11 +544,8 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
     };
     if (!pairs) {
       for (int k = 0; k < m; ++k) add(k, -1);
-    } else if (m == 4) {
-      add(0, 3);
-      add(1, 2);
     } else {
-      add(0, 1);
+      for (int k = 0; k < m / 2; ++k) add(k, m - 1 - k);
     }
     a.num_pairs = np;
     hipError_t e = dispatch_items<NarrowLauncher>(plan.items, a, int64_t(pb.B) * a.num_pairs,
@@ -551,7 +557,7 @@ hipError_t launch_dictionary(const Problem& pb, const GlobalWs& ws, const DictPl
     a.table_shift = shift_of(plan.wide_slots);
     a.lds_table_off = uint32_t(plan.wide_table_off);
     a.num_orders = plan.n_wide;
-    for (int k = 0; k < 4; ++k) a.orders[k] = plan.wide_orders[k];
+    for (int k = 0; k < 8; ++k) a.orders[k] = plan.wide_orders[k];
     const int64_t blocks = int64_t(pb.B) * plan.n_wide;
     hipError_t e = plan.wide_compact
                        ? dispatch_items<CompactWideLauncher>(plan.items, a, blocks, plan.threads,
@@ -578,7 +584,7 @@ struct CountArgs {
 // the GPU, more when the batch is small.
 static int order_split(int B, int N) {
   int split = 1;
-  while (split < N && int64_t(B) * split < 384) split *= 2;
+  while (split < N && (int64_t(B) * split < 384 || 4 * split < N)) split *= 2;  // <= 4 orders each
   return split < N ? split : N;
 }
 

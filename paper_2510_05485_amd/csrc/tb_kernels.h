@@ -7,9 +7,9 @@ namespace tb {
 
 // Resolved pointers into the caller's workspace for the GLOBAL path.
 struct GlobalWs {
-  void* keys[4];      // packed keys per order, B * group_cap entries of 8 or 16 bytes
-  uint32_t* inv[4];   // offset dictionary ids per order, B * group_cap entries
-  int32_t wide[4];    // 1 when the order uses 16-byte keys
+  void* keys[8];      // packed keys per order, B * group_cap entries of 8 or 16 bytes
+  uint32_t* inv[8];   // offset dictionary ids per order, B * group_cap entries
+  int32_t wide[8];    // 1 when the order uses 16-byte keys
   void* tables;       // hash tables / counters in HBM (groups too large for LDS), else null
 };
 
@@ -27,12 +27,12 @@ struct StatPtrs {
 struct DictPlan {
   int threads;          // workgroup size (256, 512 or 1024)
   int items;            // register-resident n-grams per thread: 2, 4, 6, 8 or 12
-  int narrow_orders[4]; // orders with 8-byte keys, and how many
+  int narrow_orders[8]; // orders with 8-byte keys, and how many
   int n_narrow;
   int slot32_mask;      // bit n: order n's keys fit 32 bits (4-byte table entries, 2x the slots)
   int narrow_slots;     // hash-table slots (power of two, >= 4/3 group_cap), 8-byte entries
   size_t narrow_lds;
-  int wide_orders[4];   // orders with 16-byte keys
+  int wide_orders[8];   // orders with 16-byte keys
   int n_wide;
   int wide_slots;       // 4-byte tag:position entries
   int wide_compact;     // 1: keys within 64 + 18 bits, only their low halves are staged in LDS

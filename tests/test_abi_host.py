@@ -46,11 +46,11 @@ def test_status_strings(lib):
 def test_layout_key_widths_follow_vocab(lib):
     cfg = tb.make_config(vocab_size=50257, path="global")
     lay = tb.tensorbleu_workspace_layout(512, 4, 1024, 1280, cfg)
-    assert lay.bits == 16 and list(lay.key_bytes) == [8, 8, 8, 8]
+    assert lay.bits == 16 and list(lay.key_bytes) == [8, 8, 8, 8, 16, 16, 16, 16]
     assert lay.group_cap == 1024 + 4 * 1280 and lay.path == 2 and lay.global_ok == 1
     cfg = tb.make_config(vocab_size=262144, path="global")
     lay = tb.tensorbleu_workspace_layout(1024, 1, 2048, 2048, cfg)
-    assert lay.bits == 18 and list(lay.key_bytes) == [8, 8, 8, 16]
+    assert lay.bits == 18 and list(lay.key_bytes)[:4] == [8, 8, 8, 16]
     slots = 1024 * 4096
     assert lay.keys_off[3] - lay.keys_off[2] >= slots * 8
     assert lay.inv_off[0] - lay.keys_off[3] >= slots * 16
@@ -77,10 +77,13 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     lay = binding.tb_layout_t()
     rc = lib.tensorbleu_workspace_layout(4, 1, 16, 16, None, ctypes.byref(lay))
     assert rc == 1
-    # more than four orders: the FUSED path only
-    five = tb.make_config(max_n=5, vocab_size=100, path="global")
+    # more than four orders: the GLOBAL path needs the packed n-gram to fit 128 bits
+    eight = tb.make_config(max_n=8, vocab_size=65536, path="global")       # 8 * 16 bits
+    assert lib.tensorbleu_workspace_layout(4, 1, 16, 16, ctypes.byref(eight), ctypes.byref(lay)) == 0
+    assert lay.global_ok == 1 and lay.keys_off[7] > lay.keys_off[6] > 0
+    five = tb.make_config(max_n=5, vocab_size=2 ** 26, path="global")      # 5 * 26 bits
     assert lib.tensorbleu_workspace_layout(4, 1, 16, 16, ctypes.byref(five), ctypes.byref(lay)) == 3
-    five = tb.make_config(max_n=5, vocab_size=100, path="auto")
+    five = tb.make_config(max_n=5, vocab_size=2 ** 26, path="auto")
     assert lib.tensorbleu_workspace_layout(4, 1, 16, 16, ctypes.byref(five), ctypes.byref(lay)) == 0
     assert lay.path == 1 and lay.global_ok == 0 and lay.fused_ok == 1
     # NULL data pointers / workspace are caught before any launch

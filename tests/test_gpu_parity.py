@@ -344,12 +344,27 @@ def test_reference_count_out_of_range_is_clamped_and_flagged(path):
     (302, 6, 3, 50257, 600),
     (303, 4, 1, 262144, 1200),     # packed 8-grams would need 144 bits; hierarchical keys do not
 ])
-def test_more_than_four_orders_on_the_fused_path(N, seed, B, R, V, L):
+def test_more_than_four_orders(N, seed, B, R, V, L):
     w = cached_small(seed, B=B, R=R, vocab=V, max_len=L)
     d = Device(w)
     weights = [1.0 / N] * N
     for run in ALL_MODES:
         check(w, run, "auto", max_n=N, weights=weights, d=d)
-    cfg = tb.make_config(max_n=N, vocab_size=w.vocab, path="global")
-    with pytest.raises(tb.TensorBLEUError):
-        tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg)
+    bits = max(1, (V - 1).bit_length())
+    if N * bits <= 128:                # the GLOBAL path packs the whole n-gram into a key
+        for run in ALL_MODES:
+            check(w, run, "global", max_n=N, weights=weights, d=d)
+    else:
+        cfg = tb.make_config(max_n=N, vocab_size=w.vocab, path="global")
+        with pytest.raises(tb.TensorBLEUError):
+            tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg)
+
+
+@pytest.mark.parametrize("N", [5, 7, 8])
+def test_more_than_four_orders_on_the_global_path_large_and_tiny_groups(N):
+    w = cached_small(304, B=3, R=2, vocab=65536, max_len=1500)        # 16-byte keys from n = 5
+    check(w, syn.Run("exp"), "global", max_n=N, weights=[1.0 / N] * N)
+    w = cached_small(305, B=2, R=1, vocab=4, max_len=9000)            # tables in the workspace
+    check(w, syn.Run("floor", 0.1), "global", max_n=N, weights=[1.0 / N] * N)
+    w = cached_small(306, B=600, R=1, vocab=200, max_len=40)          # many groups: paired orders
+    check(w, syn.Run("none"), "global", max_n=N, weights=[1.0 / N] * N)

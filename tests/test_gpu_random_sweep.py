@@ -31,7 +31,7 @@ def test_random_sweep(sweep_seed):
         seed = int(rng.integers(1, 1 << 30))
         w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=int(rng.integers(0, 2)))
         N = int(rng.choice([1, 2, 3, 4, 4, 4, 5, 8]))
-        path = str(rng.choice(["global", "fused", "auto"])) if N <= 4 else "auto"
+        path = str(rng.choice(["global", "fused", "auto"]))
         mode, param = MODES[int(rng.integers(0, 4))]
         rc = syn.ref_counts(seed, B, R) if rng.random() < 0.4 else None
         i64 = rng.random() < 0.3
