@@ -9,4 +9,6 @@ from .binding import (  # noqa: F401
     tensorbleu_pack, tensorbleu_sentence, tensorbleu_status_string, tensorbleu_workspace_bytes,
     tensorbleu_workspace_layout, tensorrouge_n,
 )
-from .api import BleuScorer, corpus_bleu, rouge_n, sentence_bleu  # noqa: F401
+from .api import (  # noqa: F401
+    BleuScorer, corpus_bleu, pad_references, rouge_n, sentence_bleu,
+)

@@ -102,3 +102,28 @@ def rouge_n(cand, cand_len, refs, ref_len, *, n: int = 2, beta: float = 1.0, voc
     rc = None if ref_count is None else _len32(ref_count).contiguous()
     return _b.tensorrouge_n(cand, _len32(cand_len), refs, _len32(ref_len), n=n, beta=beta,
                             vocab_size=vocab_size, ref_count=rc)
+
+
+def pad_references(references, device="cuda:0", dtype=torch.int32):
+    """Lay out a ragged list of references for the fixed-R interface.
+
+    `references[i]` is the list of reference token sequences (lists or 1-D tensors) of candidate
+    i; candidates may have different numbers of references (at least one each).  Returns
+    (refs [B, R, L], ref_len [B, R] int32, ref_count [B] int32) on `device`, with R the largest
+    number of references and L the longest one; pass ref_count on to the scorer.  Host-side
+    convenience: builds the arrays on the CPU and copies them once."""
+    B = len(references)
+    if B == 0 or any(len(r) == 0 for r in references):
+        raise _b.TensorBLEUError("every candidate needs at least one reference")
+    R = max(len(r) for r in references)
+    L = max(1, max(len(s) for r in references for s in r))
+    refs = torch.zeros(B, R, L, dtype=dtype)
+    ref_len = torch.zeros(B, R, dtype=torch.int32)
+    ref_count = torch.empty(B, dtype=torch.int32)
+    for i, group in enumerate(references):
+        ref_count[i] = len(group)
+        for j, seq in enumerate(group):
+            t = torch.as_tensor(seq, dtype=dtype)
+            refs[i, j, :t.numel()] = t
+            ref_len[i, j] = t.numel()
+    return refs.to(device), ref_len.to(device), ref_count.to(device)

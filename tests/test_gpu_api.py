@@ -125,3 +125,31 @@ def test_scorer_accepts_reference_counts():
     full = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
     out = scorer(to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len)).cpu().numpy()
     assert np.abs(out.astype(np.float64) - full.bleu).max() <= 1e-5   # count cleared again
+
+
+def test_pad_references_with_ragged_reference_lists():
+    rng = np.random.default_rng(5)
+    B, V = 12, 40
+    cands = [rng.integers(0, V, rng.integers(5, 30)).tolist() for _ in range(B)]
+    refs = [[rng.integers(0, V, rng.integers(3, 35)).tolist() for _ in range(rng.integers(1, 5))]
+            for _ in range(B)]
+    drefs, dref_len, dcount = tb.pad_references(refs)
+    L = max(len(c) for c in cands)
+    cand = np.zeros((B, L), np.int32)
+    for i, c in enumerate(cands):
+        cand[i, :len(c)] = c
+    cand_len = np.array([len(c) for c in cands], np.int32)
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    scorer = tb.BleuScorer(B, drefs.shape[1], L, drefs.shape[2], vocab_size=V, smoothing="floor",
+                           smooth_param=0.1)
+    out = scorer(to(cand), to(cand_len), drefs, dref_len, ref_count=dcount).cpu().numpy()
+    for i in range(B):       # each candidate against exactly its own references, one at a time
+        k = len(refs[i])
+        Lr = max(len(r) for r in refs[i])
+        r = np.zeros((1, k, Lr), np.int32)
+        for j, seq in enumerate(refs[i]):
+            r[0, j, :len(seq)] = seq
+        rl = np.array([[len(seq) for seq in refs[i]]], np.int32)
+        ref = oracle.bleu(cand[i:i + 1], cand_len[i:i + 1], r, rl, smoothing="floor",
+                          smooth_param=0.1)
+        assert abs(float(out[i]) - ref.bleu[0]) <= 1e-5
