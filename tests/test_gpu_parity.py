@@ -368,3 +368,22 @@ def test_more_than_four_orders_on_the_global_path_large_and_tiny_groups(N):
     check(w, syn.Run("floor", 0.1), "global", max_n=N, weights=[1.0 / N] * N)
     w = cached_small(306, B=600, R=1, vocab=200, max_len=40)          # many groups: paired orders
     check(w, syn.Run("none"), "global", max_n=N, weights=[1.0 / N] * N)
+
+
+def test_more_than_63_references_use_the_loop_fallback_of_the_group_index():
+    """With 64 or more sequences per group the wave-wide length scan no longer applies: the
+    GLOBAL kernels fall back to loops over the lengths (FUSED does not take such shapes)."""
+    w = cached_small(401, B=3, R=70, vocab=30, max_len=25)
+    assert not path_supported(w, "fused")
+    d = Device(w)
+    for run in ALL_MODES:
+        check(w, run, "global", d=d)
+    check(w, syn.Run("exp"), "auto", d=d)
+    rc = syn.ref_counts(401, w.B, w.R)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp", ref_count=rc)
+    cfg = tb.make_config(smoothing="exp", vocab_size=w.vocab, path="global", ref_count=dev(rc))
+    stats = tb.Stats.allocate(w.B, 4, DEV)
+    out = tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg, stats=stats)
+    np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
+    np.testing.assert_array_equal(stats.closest_ref_len.cpu().numpy(), ref.closest_ref_len)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ref.bleu).max() <= TOL
