@@ -48,7 +48,25 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(PKG, "example", "c_caller.c")
+EXAMPLE_BIN = os.path.join(PKG, "c_caller")
+
+
+def build_example(verbose: bool = True) -> str:
+    """The plain-C caller of the ABI (gcc, HIP runtime only), linked against the library."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c99", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__",
+           "-I", INCLUDE, "-I", os.path.join(rocm, "include"), EXAMPLE_SRC, "-L", PKG,
+           "-ltensorbleu", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     build()
+    build_example()
     print("built", LIB)
     sys.exit(0)

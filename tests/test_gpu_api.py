@@ -153,3 +153,19 @@ def test_pad_references_with_ragged_reference_lists():
         ref = oracle.bleu(cand[i:i + 1], cand_len[i:i + 1], r, rl, smoothing="floor",
                           smooth_param=0.1)
         assert abs(float(out[i]) - ref.bleu[0]) <= 1e-5
+
+
+def test_plain_c_caller_of_the_abi():
+    """The C ABI is usable without PyTorch: a C99 program (built beforehand by build.py) links the
+    library, runs both paths on three closed-form cases and compares them itself."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(tb.LIB_PATH), "c_caller")
+    assert os.path.exists(exe), "run python -m paper_2510_05485_amd.build first"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 0, res.stdout + res.stderr
+    rows = [tuple(map(float, line.split())) for line in res.stdout.split("\n") if line.strip()]
+    assert len(rows) == 6
+    for got, want in rows:
+        assert abs(got - want) <= 1e-5
+    assert rows[1][1] == pytest.approx(np.exp(-0.5), abs=1e-6)
