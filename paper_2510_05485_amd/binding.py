@@ -25,7 +25,7 @@ TB_DEV_TOKEN_RANGE, TB_DEV_LENGTH_RANGE = 1, 2
 EXPORTS = [
     "tensorbleu_workspace_bytes", "tensorbleu_workspace_layout", "tensorbleu_sentence",
     "tensorbleu_corpus", "tensorbleu_pack", "tensorbleu_dictionary", "tensorbleu_count_clip",
-    "tensorbleu_finalize", "tensorbleu_status_string",
+    "tensorbleu_finalize", "tensorbleu_status_string", "tensorrouge_n",
 ]
 
 

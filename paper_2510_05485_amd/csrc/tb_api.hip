@@ -49,7 +49,9 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   if (cand_stride > (int64_t(1) << 30) || ref_stride > (int64_t(1) << 30) || R > (1 << 20))
     return TB_ERR_UNSUPPORTED;
   L.group_cap = cand_stride + int64_t(R) * ref_stride;
-  const bool ids_fit = int64_t(B) * L.group_cap < (int64_t(1) << 32);
+  // group_cap can reach 2^50 here: bound it first so that the product below cannot overflow
+  const bool ids_fit = L.group_cap < (int64_t(1) << 32) &&
+                       int64_t(B) * L.group_cap < (int64_t(1) << 32);
   const bool global_n = N * L.bits <= 128;  // the GLOBAL path packs whole n-grams into keys
   const bool lds_ok = global_n &&
                       plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&

@@ -25,12 +25,12 @@ def lib():
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tensorbleu_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(tensor(?:bleu|rouge)_\w+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) >= 9
+    assert len(names) >= 10 and "tensorrouge_n" in names
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(binding.EXPORTS) == names
@@ -86,6 +86,12 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     five = tb.make_config(max_n=5, vocab_size=2 ** 26, path="auto")
     assert lib.tensorbleu_workspace_layout(4, 1, 16, 16, ctypes.byref(five), ctypes.byref(lay)) == 0
     assert lay.path == 1 and lay.global_ok == 0 and lay.fused_ok == 1
+    # shapes whose slot count would not fit the 32-bit ids (or int64 at all) are refused, not wrapped
+    huge = tb.make_config(vocab_size=100, path="global")
+    assert lib.tensorbleu_workspace_layout(2 ** 31 - 1, 2 ** 20, 2 ** 30, 2 ** 30, ctypes.byref(huge),
+                                           ctypes.byref(lay)) == 3
+    assert tb.tensorbleu_workspace_bytes(2 ** 31 - 1, 2 ** 20, 2 ** 30, 2 ** 30, huge) == 0
+    assert tb.tensorbleu_workspace_bytes(1 << 20, 1, 4096, 4096, huge) == 0     # 2^33 slots
     # NULL data pointers / workspace are caught before any launch
     args = [None, 16, None, None, 16, None, 4, 1, ctypes.byref(good), None, None, None, 0, None]
     assert lib.tensorbleu_sentence(*args) == 1
