@@ -266,8 +266,11 @@ void fused_kernel(FusedArgs a) {
     for (int i = 0; i < SITEMS; ++i) {
       const int k = tid + i * nt;
       if (k < total_tokens) {
-        tok[k] = TokT(t[i]);
-        bad |= (uint32_t(t[i]) >= uint32_t(pb.vocab));
+        // a token outside the vocabulary is reported and staged as 0, so that every key formed
+        // from the staged tokens stays below the empty-slot marker
+        const bool outside = uint32_t(t[i]) >= uint32_t(pb.vocab);
+        tok[k] = TokT(outside ? 0 : t[i]);
+        bad |= outside;
       }
     }
     if (bad && pb.status) atomicOr(pb.status, TB_DEV_TOKEN_RANGE);
