@@ -102,6 +102,16 @@ MEASURED_TRAFFIC = {
     ("cfg3_B512_L1024_R4", "count_clip"): 44.52e6,
 }
 
+# Wave-level instructions per launch (SQ_INSTS_VALU, SQ_INSTS_SALU) from the same --pmc runs.  A
+# compute unit issues about one of them per cycle, so their sum over 256 CUs at 2.4 GHz is the
+# time the instruction stream alone needs: the figure that actually bounds these kernels.
+MEASURED_INSTRUCTIONS = {
+    ("cfg3_B512_L1024_R4", "fused"): (9.58e6, 7.76e6),
+    ("cfg3_B512_L1024_R4", "dictionary"): (10.00e6, 10.08e6),
+    ("cfg3_B512_L1024_R4", "count_clip"): (4.72e6, 5.28e6),
+}
+NUM_CUS, CLOCK_GHZ = 256, 2.4
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -229,6 +239,13 @@ def main():
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["GBps"],
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_hbm"],
                 "traffic": traffic}
+    instr = MEASURED_INSTRUCTIONS.get((w.name, dom["kernel"]))
+    if instr is not None:
+        issue_us = sum(instr) / NUM_CUS / (CLOCK_GHZ * 1e3)
+        roofline["instruction_issue"] = {
+            "valu_wave_instr": instr[0], "salu_wave_instr": instr[1],
+            "issue_us_at_1_per_cu_cycle": round(issue_us, 2),
+            "frac_of_kernel_time": round(issue_us / dom["us"], 3)}
 
     result = {
         "metric": "per-sentence BLEU sentences/sec at B=512, L=1024; % HBM roofline",
