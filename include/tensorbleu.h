@@ -81,6 +81,9 @@ typedef struct tb_config {
   int32_t token_bytes;  /* element size of `cand` / `refs`: 4 (int32; 0 means 4) or 8 (int64).
                            An int64 id outside [0, vocab_size) is reported like any other
                            out-of-range token */
+  int32_t score_bytes;  /* element size of the score outputs: 4 (float32; 0 means 4) or 2
+                           (bfloat16: the float32 score rounded to nearest even, the direction
+                           Section 6 names; the arithmetic itself stays float32) */
   const int32_t* ref_count; /* optional DEVICE pointer [B] (NULL: every candidate has R references):
                            candidate i is scored against its first ref_count[i] references only;
                            the remaining rows of its R reference rows are ignored entirely (no
@@ -138,20 +141,21 @@ size_t tensorbleu_workspace_bytes(int32_t B, int32_t R, int64_t cand_stride, int
 int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
                                 const tb_config_t* cfg, tb_layout_t* layout);
 
-/* One BLEU score per candidate: out_bleu[B] float32 (device).  Implements Sections 3.1-3.4 with
+/* One BLEU score per candidate: out_bleu[B] float32, or bfloat16 when cfg->score_bytes == 2
+ * (device).  Implements Sections 3.1-3.4 with
  * the brevity penalty BP = 1 if c > r else exp(1 - r/c) and BLEU = BP * exp(sum_n w_n log p_n). */
 int tensorbleu_sentence(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                         const void* refs, int64_t ref_stride, const int32_t* ref_len,
-                        int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
+                        int32_t B, int32_t R, const tb_config_t* cfg, void* out_bleu,
                         const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                         void* hip_stream);
 
 /* One score for the whole batch: numerators, denominators, candidate lengths and closest
  * reference lengths are summed over the batch before the precisions are formed (Section 3.4,
- * second paragraph).  out_bleu[1] float32 (device). */
+ * second paragraph).  out_bleu[1] float32 or bfloat16 (device). */
 int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                       const void* refs, int64_t ref_stride, const int32_t* ref_len,
-                      int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
+                      int32_t B, int32_t R, const tb_config_t* cfg, void* out_bleu,
                       const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                       void* hip_stream);
 
@@ -162,7 +166,7 @@ int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand
  *   precision = overlap / candidate n-grams, recall = overlap / reference n-grams (0 when the
  *   denominator is 0), F = (1 + beta^2) P R / (R + beta^2 P) (0 when P + R = 0),
  *   beta = cfg->smooth_param (<= 0 means 1).
- * out_prf[B, 3] float32 (device) receives precision, recall and F of the candidate's best
+ * out_prf[B, 3] float32 or bfloat16 (cfg->score_bytes; device) receives precision, recall and F of the candidate's best
  * reference: the first one with the largest overlap / (candidate n-grams + beta^2 * reference
  * n-grams), to which F is proportional.  overlap[B, R] int32 and best_ref[B] int32 (index of that
  * reference) are optional device outputs (NULL to skip); entries of references beyond
@@ -172,7 +176,7 @@ int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand
  * TB_PATH_FUSED (or AUTO when AUTO resolves to FUSED).  stats: only device_status is used. */
 int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                   const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
-                  int32_t R, const tb_config_t* cfg, float* out_prf, int32_t* overlap,
+                  int32_t R, const tb_config_t* cfg, void* out_prf, int32_t* overlap,
                   int32_t* best_ref, const tb_stats_t* stats, void* workspace,
                   size_t workspace_bytes, void* hip_stream);
 
@@ -208,7 +212,7 @@ int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64
  * integer statistics in the workspace.  corpus != 0 writes out_bleu[1], else out_bleu[B]. */
 int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t B, int32_t R,
                         int64_t cand_stride, int64_t ref_stride, const tb_config_t* cfg,
-                        int32_t corpus, float* out_bleu, const tb_stats_t* stats, void* workspace,
+                        int32_t corpus, void* out_bleu, const tb_stats_t* stats, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
 
 /* Text for a tb_status_t value (static storage, host). */

@@ -189,3 +189,22 @@ def rouge_n(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: n
     if rc != 0:
         raise ValueError("oracle_rouge_n: invalid arguments")
     return RougeResult(overlap, prf, best)
+
+
+def to_bfloat16(x) -> np.ndarray:
+    """The stored value of a bfloat16 score (Section 6: lower-precision scores), as float64.
+
+    The paper fixes no rounding; the reading taken: the fp32 score (the precision the scores are
+    formed in) rounded to the nearest number with an 8-bit significand, ties to the even one.
+    Written from that definition: a finite x with 2^e <= |x| < 2^(e+1) lies on a grid of spacing
+    2^(e-7) (2^-133 below the smallest normal, 2^-126), and is moved to the nearest grid point.
+    """
+    x32 = np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)
+    out = np.array(x32, copy=True)
+    finite = np.isfinite(x32) & (x32 != 0.0)
+    if finite.any():
+        v = x32[finite]
+        e = np.maximum(np.floor(np.log2(np.abs(v))), -126.0)
+        spacing = np.exp2(e - 7.0)
+        out[finite] = np.rint(v / spacing) * spacing          # rint: ties to even
+    return out

@@ -29,18 +29,23 @@ class BleuScorer:
 
     scorer = BleuScorer(B, R, cand_stride, ref_stride, vocab_size=50257, smoothing="exp")
     reward = scorer(cand, cand_len, refs, ref_len)          # float32 [B], on the GPU
+
+    score_dtype=torch.bfloat16 stores the scores as bfloat16 (the fp32 score rounded to nearest
+    even) for consumers that keep rewards in that type.
     """
 
     def __init__(self, B: int, R: int, cand_stride: int, ref_stride: int, *, vocab_size: int,
                  max_n: int = 4, weights: Optional[Sequence[float]] = None,
                  smoothing: str = "none", smooth_param: float = 0.0, path: str = "auto",
-                 device="cuda:0", want_stats: bool = False):
+                 device="cuda:0", want_stats: bool = False,
+                 score_dtype: torch.dtype = torch.float32):
         self.shape = (int(B), int(R), int(cand_stride), int(ref_stride))
         self.cfg = _b.make_config(max_n=max_n, weights=weights, smoothing=smoothing,
-                                  smooth_param=smooth_param, vocab_size=vocab_size, path=path)
+                                  smooth_param=smooth_param, vocab_size=vocab_size, path=path,
+                                  score_dtype=score_dtype)
         self.workspace = _b.allocate_workspace(B, R, cand_stride, ref_stride, self.cfg, device)
-        self.out = torch.empty(B, dtype=torch.float32, device=device)
-        self.corpus_out = torch.zeros(1, dtype=torch.float32, device=device)
+        self.out = torch.empty(B, dtype=score_dtype, device=device)
+        self.corpus_out = torch.zeros(1, dtype=score_dtype, device=device)
         self.stats = _b.Stats.allocate(B, max_n, device) if want_stats else None
 
     def _check(self, cand, refs):
@@ -95,13 +100,13 @@ def corpus_bleu(cand, cand_len, refs, ref_len, *, vocab_size: int, **kw) -> torc
 
 
 def rouge_n(cand, cand_len, refs, ref_len, *, n: int = 2, beta: float = 1.0, vocab_size: int,
-            ref_count=None) -> torch.Tensor:
-    """ROUGE-N precision, recall and F (float32 [B, 3]) of every candidate against the best of
+            ref_count=None, score_dtype: torch.dtype = torch.float32) -> torch.Tensor:
+    """ROUGE-N precision, recall and F (float32 or bfloat16 [B, 3]) of every candidate against the best of
     its references; runs `tensorrouge_n` on the current stream."""
     refs = _refs3d(refs)
     rc = None if ref_count is None else _len32(ref_count).contiguous()
     return _b.tensorrouge_n(cand, _len32(cand_len), refs, _len32(ref_len), n=n, beta=beta,
-                            vocab_size=vocab_size, ref_count=rc)
+                            vocab_size=vocab_size, ref_count=rc, score_dtype=score_dtype)
 
 
 def pad_references(references, device="cuda:0", dtype=torch.int32):

@@ -33,7 +33,8 @@ class tb_config_t(ctypes.Structure):
     _fields_ = [("max_n", ctypes.c_int32), ("weights", ctypes.c_float * 8),
                 ("smoothing", ctypes.c_int32), ("smooth_param", ctypes.c_float),
                 ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32),
-                ("token_bytes", ctypes.c_int32), ("ref_count", ctypes.c_void_p)]
+                ("token_bytes", ctypes.c_int32), ("score_bytes", ctypes.c_int32),
+                ("ref_count", ctypes.c_void_p)]
 
 
 class tb_stats_t(ctypes.Structure):
@@ -109,9 +110,13 @@ def _check(rc: int, what: str) -> None:
 
 def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
                 smoothing: str = "none", smooth_param: float = 0.0, vocab_size: int = 1 << 16,
-                path: str = "auto", ref_count: Optional[torch.Tensor] = None) -> tb_config_t:
+                path: str = "auto", ref_count: Optional[torch.Tensor] = None,
+                score_dtype: torch.dtype = torch.float32) -> tb_config_t:
     """ref_count: optional int32 device tensor [B]; candidate i is scored against its first
-    ref_count[i] references only.  The config keeps the tensor alive."""
+    ref_count[i] references only.  The config keeps the tensor alive.
+    score_dtype: torch.float32, or torch.bfloat16 for scores stored as bfloat16."""
+    if score_dtype not in (torch.float32, torch.bfloat16):
+        raise TensorBLEUError(f"score_dtype must be float32 or bfloat16 (got {score_dtype})")
     cfg = tb_config_t()
     cfg.max_n = int(max_n)
     w = [0.0] * 8
@@ -124,6 +129,7 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
     cfg.vocab_size = int(vocab_size)
     cfg.force_path = PATHS[path] if isinstance(path, str) else int(path)
     cfg.token_bytes = 4
+    cfg.score_bytes = 2 if score_dtype == torch.bfloat16 else 4
     cfg.ref_count = None
     if ref_count is not None:
         if ref_count.dtype != torch.int32 or not ref_count.is_contiguous() or ref_count.dim() != 1:
@@ -223,6 +229,16 @@ def allocate_workspace(B: int, R: int, cand_stride: int, ref_stride: int, cfg: t
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def _score_out(out: Optional[torch.Tensor], cfg: tb_config_t, shape, device) -> torch.Tensor:
+    """The score tensor of the dtype the config asks for (checked when the caller brings one)."""
+    dtype = torch.bfloat16 if cfg.score_bytes == 2 else torch.float32
+    if out is None:
+        return torch.zeros(shape, dtype=dtype, device=device)
+    if out.dtype != dtype or tuple(out.shape) != tuple(shape) or not out.is_contiguous():
+        raise TensorBLEUError(f"out must be a contiguous {dtype} tensor of shape {tuple(shape)}")
+    return out
+
+
 def _full(entry: str, cand, cand_len, refs, ref_len, cfg, out, stats, workspace, stream):
     b = _batch(cand, cand_len, refs, ref_len, cfg)
     if workspace is None:
@@ -240,9 +256,8 @@ def _full(entry: str, cand, cand_len, refs, ref_len, cfg, out, stats, workspace,
 def tensorbleu_sentence(cand, cand_len, refs, ref_len, cfg: tb_config_t,
                         out: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """float32 [B]: one BLEU score per candidate."""
-    if out is None:
-        out = torch.empty(cand.shape[0], dtype=torch.float32, device=cand.device)
+    """float32 (or bfloat16, see make_config) [B]: one BLEU score per candidate."""
+    out = _score_out(out, cfg, (cand.shape[0],), cand.device)
     return _full("tensorbleu_sentence", cand, cand_len, refs, ref_len, cfg, out, stats,
                  workspace, stream)
 
@@ -250,9 +265,8 @@ def tensorbleu_sentence(cand, cand_len, refs, ref_len, cfg: tb_config_t,
 def tensorbleu_corpus(cand, cand_len, refs, ref_len, cfg: tb_config_t,
                       out: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
                       workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """float32 [1]: one BLEU score for the batch."""
-    if out is None:
-        out = torch.zeros(1, dtype=torch.float32, device=cand.device)
+    """float32 (or bfloat16) [1]: one BLEU score for the batch."""
+    out = _score_out(out, cfg, (1,), cand.device)
     return _full("tensorbleu_corpus", cand, cand_len, refs, ref_len, cfg, out, stats, workspace,
                  stream)
 
@@ -261,17 +275,17 @@ def tensorrouge_n(cand, cand_len, refs, ref_len, n: int = 2, beta: float = 1.0, 
                   vocab_size: int, ref_count: Optional[torch.Tensor] = None,
                   want_overlap: bool = False, want_best: bool = False,
                   workspace: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
-                  stream=None):
-    """ROUGE-N of every candidate against its references: float32 [B, 3] (precision, recall, F of
-    the best reference), plus overlap int32 [B, R] and best-reference index int32 [B] on request
-    (returned as a tuple then)."""
+                  stream=None, score_dtype: torch.dtype = torch.float32):
+    """ROUGE-N of every candidate against its references: float32 (or bfloat16) [B, 3] (precision,
+    recall, F of the best reference), plus overlap int32 [B, R] and best-reference index int32 [B]
+    on request (returned as a tuple then)."""
     cfg = make_config(max_n=n, smooth_param=beta, vocab_size=vocab_size, path="fused",
-                      ref_count=ref_count)
+                      ref_count=ref_count, score_dtype=score_dtype)
     b = _batch(cand, cand_len, refs, ref_len, cfg)
     if workspace is None:
         workspace = allocate_workspace(b.B, b.R, b.cand_stride, b.ref_stride, cfg, b.cand.device)
     dev = b.cand.device
-    out = torch.zeros(b.B, 3, dtype=torch.float32, device=dev)
+    out = _score_out(None, cfg, (b.B, 3), dev)
     overlap = torch.zeros(b.B, b.R, dtype=torch.int32, device=dev) if want_overlap else None
     best = torch.zeros(b.B, dtype=torch.int32, device=dev) if want_best else None
     st = stats.as_struct() if stats is not None else None

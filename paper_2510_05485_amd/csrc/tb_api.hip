@@ -24,6 +24,7 @@ bool config_ok(const tb_config_t* cfg) {
   if (cfg->smoothing < TB_SMOOTH_NONE || cfg->smoothing > TB_SMOOTH_EXP) return false;
   if (cfg->force_path < TB_PATH_AUTO || cfg->force_path > TB_PATH_GLOBAL) return false;
   if (cfg->token_bytes != 0 && cfg->token_bytes != 4 && cfg->token_bytes != 8) return false;
+  if (cfg->score_bytes != 0 && cfg->score_bytes != 4 && cfg->score_bytes != 2) return false;
   return true;
 }
 
@@ -160,6 +161,7 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   sp.N = cfg->max_n;
   sp.smoothing = cfg->smoothing;
   sp.param = cfg->smooth_param;
+  sp.out_bf16 = cfg->score_bytes == 2;
   bool all_zero = true;
   for (int n = 0; n < sp.N; ++n) all_zero = all_zero && cfg->weights[n] == 0.0f;
   for (int n = 0; n < 8; ++n)
@@ -181,7 +183,7 @@ hipError_t run_count_clip(const Call& c) {
 
 int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
             const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
-            const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats, void* workspace,
+            const tb_config_t* cfg, void* out_bleu, const tb_stats_t* stats, void* workspace,
             size_t workspace_bytes, void* hip_stream, bool corpus) {
   Call c;
   int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
@@ -229,7 +231,7 @@ int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64
 
 int tensorbleu_sentence(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                         const void* refs, int64_t ref_stride, const int32_t* ref_len,
-                        int32_t B, int32_t R, const tb_config_t* cfg, float* out_bleu,
+                        int32_t B, int32_t R, const tb_config_t* cfg, void* out_bleu,
                         const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                         void* hip_stream) {
   return run_all(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, out_bleu,
@@ -238,7 +240,7 @@ int tensorbleu_sentence(const void* cand, int64_t cand_stride, const int32_t* ca
 
 int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                       const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
-                      int32_t R, const tb_config_t* cfg, float* out_bleu, const tb_stats_t* stats,
+                      int32_t R, const tb_config_t* cfg, void* out_bleu, const tb_stats_t* stats,
                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   return run_all(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, out_bleu,
                  stats, workspace, workspace_bytes, hip_stream, true);
@@ -246,7 +248,7 @@ int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand
 
 int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                   const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
-                  int32_t R, const tb_config_t* cfg, float* out_prf, int32_t* overlap,
+                  int32_t R, const tb_config_t* cfg, void* out_prf, int32_t* overlap,
                   int32_t* best_ref, const tb_stats_t* stats, void* workspace,
                   size_t workspace_bytes, void* hip_stream) {
   Call c;
@@ -306,7 +308,7 @@ int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64
 
 int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t B, int32_t R,
                         int64_t cand_stride, int64_t ref_stride, const tb_config_t* cfg,
-                        int32_t corpus, float* out_bleu, const tb_stats_t* stats, void* workspace,
+                        int32_t corpus, void* out_bleu, const tb_stats_t* stats, void* workspace,
                         size_t workspace_bytes, void* hip_stream) {
   Call c;
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,

@@ -156,6 +156,7 @@ struct ScoreParams {
   int32_t N;
   int32_t smoothing;
   float param;
+  int32_t out_bf16;  // scores are stored as bfloat16 (fp32 rounded to nearest even) instead of fp32
 };
 
 }  // namespace tb

@@ -9,7 +9,7 @@ struct FinalArgs {
   Problem pb;
   StatPtrs st;
   ScoreParams sp;
-  float* out;
+  void* out;  // fp32 or bfloat16 scores (sp.out_bf16)
 };
 
 // One lane per sentence.
@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void sentence_score_kernel(FinalArgs a) {
     cl[n] = (n < pb.N) ? a.st.clipped[int64_t(i) * pb.N + n] : 0;
     to[n] = (n < pb.N) ? a.st.total[int64_t(i) * pb.N + n] : 0;
   }
-  a.out[i] = bleu_from_stats<int>(cl, to, c, r, a.sp);
+  store_score(a.out, i, bleu_from_stats<int>(cl, to, c, r, a.sp), a.sp.out_bf16);
 }
 
 __device__ __forceinline__ long long wave_sum64(long long v) {
@@ -84,13 +84,15 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
     }
     a.st.corpus[2 * pb.N] = tot[16];
     a.st.corpus[2 * pb.N + 1] = tot[17];
-    if (write_score) a.out[0] = bleu_from_stats<long long>(tot, tot + 8, tot[16], tot[17], a.sp);
+    if (write_score)
+      store_score(a.out, 0, bleu_from_stats<long long>(tot, tot + 8, tot[16], tot[17], a.sp),
+                  a.sp.out_bf16);
   }
 }
 
 hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
                            bool sentence_scores, bool corpus_sums, bool corpus_score,
-                           float* out_bleu, hipStream_t s) {
+                           void* out_bleu, hipStream_t s) {
   FinalArgs a;
   a.pb = pb;
   a.st = st;

@@ -27,9 +27,9 @@ struct FusedArgs {
   Problem pb;
   StatPtrs st;
   ScoreParams sp;
-  float* out;           // per-sentence scores, or null
+  void* out;            // per-sentence scores (fp32 or bfloat16: sp.out_bf16), or null
   // ROUGE-N mode (fused_kernel<.., true>): order N = pb.N only
-  float* rouge_prf;     // [B, 3] precision, recall, F of the best reference
+  void* rouge_prf;      // [B, 3] precision, recall, F of the best reference (same type)
   int32_t* rouge_overlap;  // [B, R] or null
   int32_t* rouge_best;  // [B] or null
   float beta2;          // beta squared
@@ -404,7 +404,7 @@ void fused_kernel(FusedArgs a) {
       const float score = bleu_from_stats_wave(cn, tn, c, best, a.sp);
       if (lane == 0) {
         a.st.closest[g] = best;
-        if (a.out) a.out[g] = score;
+        if (a.out) store_score(a.out, g, score, a.sp.out_bf16);
       }
     } else {
       // lane j = 1..used: reference j - 1.  F is proportional to overlap / (cand + beta^2 ref)
@@ -428,9 +428,9 @@ void fused_kernel(FusedArgs a) {
       const float r = rt > 0.0f ? float(ov) / rt : 0.0f;
       const float f = (p + r > 0.0f) ? (1.0f + a.beta2) * p * r / (r + a.beta2 * p) : 0.0f;
       if (lane == best_j) {
-        a.rouge_prf[int64_t(g) * 3 + 0] = p;
-        a.rouge_prf[int64_t(g) * 3 + 1] = r;
-        a.rouge_prf[int64_t(g) * 3 + 2] = f;
+        store_score(a.rouge_prf, int64_t(g) * 3 + 0, p, a.sp.out_bf16);
+        store_score(a.rouge_prf, int64_t(g) * 3 + 1, r, a.sp.out_bf16);
+        store_score(a.rouge_prf, int64_t(g) * 3 + 2, f, a.sp.out_bf16);
         if (a.rouge_best) a.rouge_best[g] = best_j - 1;
       }
     }
@@ -469,7 +469,7 @@ hipError_t launch_fused_tok(const FusedArgs& a, const FusedPlan& plan, int block
 }
 
 hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs& st,
-                        const ScoreParams& sp, float* out_bleu_or_null, hipStream_t s,
+                        const ScoreParams& sp, void* out_bleu_or_null, hipStream_t s,
                         const RougeOut* rouge) {
   FusedArgs a;
   a.pb = pb;

@@ -81,17 +81,17 @@ hipError_t launch_count_clip(const Problem& pb, const GlobalWs& ws, const CountP
 // corpus_score: additionally write the corpus score to out_bleu[0] (not with sentence_scores).
 hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
                            bool sentence_scores, bool corpus_sums, bool corpus_score,
-                           float* out_bleu, hipStream_t s);
+                           void* out_bleu, hipStream_t s);
 // ROUGE-N outputs of the fused kernel (order n = pb.N): see tensorrouge_n.
 struct RougeOut {
-  float* prf;        // [B, 3]
+  void* prf;         // [B, 3] fp32 or bfloat16 (ScoreParams::out_bf16)
   int32_t* overlap;  // [B, R] or null
   int32_t* best;     // [B] or null
   float beta2;
 };
 // rouge == null: BLEU (statistics and, if out_bleu_or_null, per-sentence scores).
 hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs& st,
-                        const ScoreParams& sp, float* out_bleu_or_null, hipStream_t s,
+                        const ScoreParams& sp, void* out_bleu_or_null, hipStream_t s,
                         const RougeOut* rouge = nullptr);
 
 }  // namespace tb

@@ -99,4 +99,18 @@ __device__ __forceinline__ float bleu_from_stats_wave(int cn, int tn, int c, int
   return ((c > r) ? 1.0f : e1) * e0;
 }
 
+// Store score v as element i of `out`: fp32, or bfloat16 = the upper half of the fp32 pattern
+// after rounding to nearest, ties to even (Section 6 names lower-precision scores as a direction;
+// all arithmetic stays fp32, only the stored value is narrowed).  A NaN stays a quiet NaN.
+__device__ __forceinline__ void store_score(void* out, int64_t i, float v, int out_bf16) {
+  if (out_bf16) {
+    const uint32_t u = __float_as_uint(v);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const bool is_nan = (u & 0x7FFFFFFFu) > 0x7F800000u;
+    static_cast<uint16_t*>(out)[i] = uint16_t(is_nan ? ((u >> 16) | 0x40u) : rounded);
+  } else {
+    static_cast<float*>(out)[i] = v;
+  }
+}
+
 }  // namespace tb
