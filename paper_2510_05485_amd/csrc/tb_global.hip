@@ -685,10 +685,14 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
     // Sequence of a slot = number of sequences that end at or before it (seq_end: lane j holds
     // the end of sequence j).  A block's 128 slots usually lie inside one sequence, which one
     // ballot finds; then sequence, counter word and addend are scalars for both items.
+    // Ids are clamped to the dictionary size instead of tested against it: every id the
+    // dictionary pass wrote is below U, so the clamp only matters for a workspace that pass never
+    // filled, where it keeps the LDS accesses inside the table.
+    const uint32_t u_max = uint32_t(max(U, 1) - 1);
     uint32_t first = 0;  // bit i: item i is the first occurrence of its candidate n-gram
     // one n-gram whose sequence is known per lane
     auto count_one = [&](int i, uint32_t u, int f) {
-      if (f <= pb.R && u < uint32_t(U)) {
+      if (f <= pb.R) {
         uint32_t* word = &cnt[__umul24(u, uint32_t(W)) + uint32_t(f >> 1)];
         if (f == 0) {
           if ((atomicAdd(word, 1u) & 0xFFFFu) == 0u) first |= 1u << i;
@@ -703,10 +707,20 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
       if (k0 >= count) break;
       const int f = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0));  // <= R: k0 < count
       const int f_end = __builtin_amdgcn_readlane(seq_end, f);
-      const uint32_t u0 = id[o][2 * p] - gbase, u1 = id[o][2 * p + 1] - gbase;
+      const uint32_t u0 = min(id[o][2 * p] - gbase, u_max);
+      const uint32_t u1 = min(id[o][2 * p + 1] - gbase, u_max);
       if (k0 + 2 * kWave <= f_end) {  // the whole block is inside sequence f
-        count_one(2 * p, u0, f);
-        count_one(2 * p + 1, u1, f);
+        uint32_t* w0 = &cnt[__umul24(u0, uint32_t(W)) + uint32_t(f >> 1)];
+        uint32_t* w1 = &cnt[__umul24(u1, uint32_t(W)) + uint32_t(f >> 1)];
+        if (f == 0) {  // candidate slots: remember the first occurrence of each n-gram
+          const uint32_t before0 = atomicAdd(w0, 1u), before1 = atomicAdd(w1, 1u);
+          first |= ((before0 & 0xFFFFu) == 0u ? 1u : 0u) << (2 * p);
+          first |= ((before1 & 0xFFFFu) == 0u ? 1u : 0u) << (2 * p + 1);
+        } else {
+          const uint32_t addend = (f & 1) ? 0x10000u : 1u;
+          atomicAdd(w0, addend);
+          atomicAdd(w1, addend);
+        }
       } else {  // the block straddles sequences (or the end): sequence per lane and half
         const int f_hi = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0 + 2 * kWave - 1));
         int fl0 = f, fl1 = f;
@@ -727,10 +741,18 @@ __global__ __launch_bounds__(1024) void count_fields_kernel(CountArgs a) {
       // only candidate slots can be first occurrences
       if (block_start(i >> 1) + (i & 1) * kWave >= ccnt) break;
       if ((first >> i) & 1u) {
-        const uint32_t* e = &cnt[__umul24(id[o][i] - gbase, uint32_t(W))];
+        const uint32_t* e = &cnt[__umul24(min(id[o][i] - gbase, u_max), uint32_t(W))];
         const uint32_t w0 = e[0];
         uint32_t m = w0 >> 16;
-        for (int q = 1; q < W; ++q) {
+        // (the first words unrolled under a scalar test: the usual few references need no loop)
+#pragma unroll
+        for (int q = 1; q < 4; ++q) {
+          if (q < W) {
+            const uint32_t w = e[q];
+            m = max(m, max(w & 0xFFFFu, w >> 16));
+          }
+        }
+        for (int q = 4; q < W; ++q) {
           const uint32_t w = e[q];
           m = max(m, max(w & 0xFFFFu, w >> 16));
         }
