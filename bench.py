@@ -108,7 +108,7 @@ MEASURED_TRAFFIC = {
 MEASURED_INSTRUCTIONS = {
     ("cfg3_B512_L1024_R4", "fused"): (9.58e6, 7.76e6),
     ("cfg3_B512_L1024_R4", "dictionary"): (10.00e6, 10.08e6),
-    ("cfg3_B512_L1024_R4", "count_clip"): (4.72e6, 5.28e6),
+    ("cfg3_B512_L1024_R4", "count_clip"): (4.47e6, 3.87e6),
 }
 NUM_CUS, CLOCK_GHZ = 256, 2.4
 
