@@ -239,6 +239,16 @@ def test_group_too_large_for_lds_is_scored_with_tables_in_hbm(vocab):
         check(w, run, "auto", d=d)
 
 
+def test_long_form_sequences_of_300k_tokens():
+    # two groups of ~600 000 tokens each (a candidate and one reference of up to 300 000): far
+    # beyond LDS, and with a 3-token vocabulary single n-gram counts far beyond 16 bits
+    w = cached_small(145, B=2, R=1, vocab=3, max_len=300000, min_len=250000)
+    assert np.bincount(w.cand[0, :w.cand_len[0]]).max() > 65535
+    check(w, syn.Run("exp"), "auto")
+    w = cached_small(146, B=2, R=1, vocab=50257, max_len=300000, min_len=250000)
+    check(w, syn.Run("add-k", 1.0), "global")
+
+
 def test_determinism_of_integer_statistics():
     w = syn.make(1)
     d = Device(w)
