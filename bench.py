@@ -4,7 +4,12 @@
 A "step" is one pass of the whole hot path (n-gram extraction .. geometric mean) over one
 synthetic batch already resident in HBM.  The default workload is the headline configuration
 (B=512 candidates of 1024 tokens, 4 references each, vocabulary 50257).  One JSON line is
-printed; the design doc (measurement contract) gives the meaning of every field.
+printed: `value` = sentences/s of the whole call, `roofline` = the dominant kernel's algorithmic
+bytes per launch over its HIP-event duration against the 8 TB/s HBM peak (plus its measured HBM
+traffic and instruction-issue time from the committed profiler summaries), `passes` = every
+kernel of the path that ran, `global_path` = the staged pipeline's passes timed one by one,
+`achievable_hbm_GBps` = plain fill / read / copy kernels in the same run, `cpu_baseline` = the CPU
+oracle on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
