@@ -76,25 +76,49 @@ def achievable_hbm(torch, dev):
     return out
 
 
-def cpu_baseline(w, run, budget_s=12.0):
-    """The oracle, as it stands, on the host cores: sentences/s on a bounded sample."""
+def cpu_baseline(w, run, gpu=None, budget_s=10.0):
+    """The oracle, as it stands, on the host cores: sentences/s on a bounded sample, with all
+    threads and with one; `gpu` (scores, clipped, total, closest length of the timed call, as
+    numpy arrays) is compared with the oracle's results on the same sample."""
+    import numpy as np
     import oracle
     cores = len(os.sched_getaffinity(0))
     threads = min(cores, 16)
-    sample = w.subset(min(w.B, 256))
     args = dict(max_n=w.max_n, weights=w.weights, smoothing=run.smoothing,
                 smooth_param=run.smooth_param)
-    best, reps, t_end = None, 0, time.time() + budget_s
-    while reps < 3 and (reps == 0 or time.time() < t_end):
+
+    def timed(sample, nthreads):
         t0 = time.time()
-        oracle.bleu(sample.cand, sample.cand_len, sample.refs, sample.ref_len, threads=threads,
-                    **args)
-        dt = time.time() - t0
+        res = oracle.bleu(sample.cand, sample.cand_len, sample.refs, sample.ref_len,
+                          threads=nthreads, **args)
+        return time.time() - t0, res
+
+    # a small probe fixes the sample: as much of the workload as about budget_s of CPU work
+    # (three repetitions with all threads) allows
+    probe = w.subset(min(w.B, 4 * threads))
+    dt, _ = timed(probe, threads)
+    rate = probe.B / max(dt, 1e-6)
+    sample = w.subset(int(min(w.B, max(probe.B, rate * budget_s / 3))))
+    best, res = None, None
+    for _ in range(3):
+        dt, res = timed(sample, threads)
         best = dt if best is None else min(best, dt)
-        reps += 1
-    return {"value": sample.B / best, "unit": "sentences/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {sample.B} sentence groups of the workload, best of {reps}, "
-                      f"{threads} std::threads over sentences"}
+    single = w.subset(min(sample.B, max(8, int(rate / threads))))      # about a second
+    dt1, _ = timed(single, 1)
+    what = "the whole workload" if sample.B == w.B else f"first {sample.B} sentence groups"
+    out = {"value": sample.B / best, "unit": "sentences/s", "cores": threads, "kind": "oracle",
+           "sample": f"{what}, best of 3, {threads} std::threads over sentences",
+           "value_1_thread": single.B / dt1,
+           "sample_1_thread": f"first {single.B} sentence groups, one run"}
+    if gpu is not None:
+        k = sample.B
+        out["parity_on_sample"] = {
+            "max_abs_dbleu": float(np.abs(gpu["bleu"][:k].astype(np.float64) - res.bleu).max()),
+            "clipped_exact": bool(np.array_equal(gpu["clipped"][:k], res.clipped)),
+            "total_exact": bool(np.array_equal(gpu["total"][:k], res.total)),
+            "closest_ref_len_exact": bool(np.array_equal(gpu["closest"][:k],
+                                                         res.closest_ref_len))}
+    return out
 
 
 # HBM traffic per launch (fetch + write bytes) of the dominant kernel, from the rocprofv3 --pmc
@@ -283,7 +307,11 @@ def main():
     if not a.no_hbm_ceiling:
         result["achievable_hbm_GBps"] = achievable_hbm(torch, dev)
     if not a.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, run)
+        step()
+        torch.cuda.synchronize()
+        gpu = {"bleu": out.cpu().numpy(), "clipped": stats.clipped.cpu().numpy(),
+               "total": stats.total.cpu().numpy(), "closest": stats.closest_ref_len.cpu().numpy()}
+        result["cpu_baseline"] = cpu_baseline(w, run, gpu)
     print(json.dumps(result), flush=True)
 
 
