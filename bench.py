@@ -121,6 +121,58 @@ def cpu_baseline(w, run, gpu=None, budget_s=10.0):
     return out
 
 
+def other_configs(skip, steps, torch, tb, syn, np, dev):
+    """The remaining BASELINE configurations in short form: sentences/s of the default path and
+    the three main GLOBAL passes as fractions of the HBM peak.  A failure is recorded, not
+    raised: it must not take the headline line with it."""
+    rows = []
+    for k in (1, 2, 3, 4, 5):
+        if k == skip:
+            continue
+        try:
+            w = syn.make(k)
+            run = [r for r in w.runs if not r.corpus][-1]
+            to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+            cand, cl, refs, rl = to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len)
+            cs, rs = int(w.cand.shape[1]), int(w.refs.shape[2])
+            mk = lambda path: tb.make_config(max_n=w.max_n, weights=w.weights,
+                                             smoothing=run.smoothing,
+                                             smooth_param=run.smooth_param, vocab_size=w.vocab,
+                                             path=path)
+            cfg = mk("auto")
+            lay = tb.tensorbleu_workspace_layout(w.B, w.R, cs, rs, cfg)
+            ws = tb.allocate_workspace(w.B, w.R, cs, rs, cfg, dev)
+            out = torch.empty(w.B, dtype=torch.float32, device=dev)
+            fn = lambda: tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out, workspace=ws)
+            for _ in range(5):
+                fn()
+            ms = time_region(fn, steps, torch)
+            row = {"workload": w.name, "path": {1: "fused", 2: "global"}[lay.path],
+                   "us": round(ms * 1e3, 2), "sentences_per_s": round(w.B / (ms * 1e-3), 1)}
+            if lay.global_ok:
+                gcfg = mk("global")
+                glay = tb.tensorbleu_workspace_layout(w.B, w.R, cs, rs, gcfg)
+                gws = tb.allocate_workspace(w.B, w.R, cs, rs, gcfg, dev)
+                alg = algorithmic_bytes(w, glay, w.max_n)
+                tb.tensorbleu_sentence(cand, cl, refs, rl, gcfg, out=out, workspace=gws)
+                stages = {
+                    "pack": lambda: tb.tensorbleu_pack(cand, cl, refs, rl, gcfg, gws),
+                    "dictionary": lambda: tb.tensorbleu_dictionary(cl, rl, cs, rs, gcfg, gws),
+                    "count_clip": lambda: tb.tensorbleu_count_clip(cl, rl, cs, rs, gcfg, gws)}
+                for name, st in stages.items():
+                    for _ in range(3):
+                        st()
+                    t_ms = time_region(st, steps, torch)
+                    row[name + "_us"] = round(t_ms * 1e3, 2)
+                    row[name + "_frac_hbm"] = round(alg[name] / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                                    4)
+            rows.append(row)
+            del cand, refs, ws
+        except Exception as err:       # noqa: BLE001 - reported in the output line
+            rows.append({"config": k, "error": repr(err)})
+    return rows
+
+
 # HBM traffic per launch (fetch + write bytes) of the dominant kernel, from the rocprofv3 --pmc
 # runs summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters'
 # reading for a plain copy of known size).  Keyed by (workload name, kernel); None = not measured.
@@ -156,6 +208,8 @@ def main():
                     help="also time ROUGE-N (tensorrouge_n, order N) on the same batch")
     ap.add_argument("--int64", action="store_true",
                     help="feed int64 token ids (the usual tokenizer dtype) instead of int32")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short measurements of the other BASELINE configurations")
     ap.add_argument("--no-global-passes", action="store_true",
                     help="skip the per-pass timing of the GLOBAL path")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -304,6 +358,8 @@ def main():
         result["rouge"] = {"n": a.rouge, "us": round(r_ms * 1e3, 2),
                            "sentences_per_s": round(w.B / (r_ms * 1e-3), 1),
                            "frac_hbm": round(alg["fused"] / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    if not a.no_other_configs:
+        result["other_configs"] = other_configs(a.config, min(a.steps, 100), torch, tb, syn, np, dev)
     if not a.no_hbm_ceiling:
         result["achievable_hbm_GBps"] = achievable_hbm(torch, dev)
     if not a.no_cpu_baseline:
