@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     tensorbleu_workspace_layout, tensorrouge_n,
 )
 from .api import (  # noqa: F401
-    BleuScorer, corpus_bleu, pad_references, rouge_n, sentence_bleu,
+    BleuScorer, corpus_bleu, lengths_from_padding, pad_references, rouge_n, sentence_bleu,
 )

@@ -109,6 +109,16 @@ def rouge_n(cand, cand_len, refs, ref_len, *, n: int = 2, beta: float = 1.0, voc
                             vocab_size=vocab_size, ref_count=rc, score_dtype=score_dtype)
 
 
+def lengths_from_padding(tokens: torch.Tensor, pad_id: int) -> torch.Tensor:
+    """int32 lengths of right-padded rows: the number of cells before the trailing run of
+    `pad_id` (a pad-valued token inside the sentence is kept).  Plain torch on the tensor's device;
+    for callers that hold (batch, seq_len) tensors without a length array."""
+    keep = tokens != pad_id
+    L = tokens.shape[-1]
+    pos = torch.arange(1, L + 1, device=tokens.device, dtype=torch.int32)
+    return (keep.to(torch.int32) * pos).amax(dim=-1).to(torch.int32)
+
+
 def pad_references(references, device="cuda:0", dtype=torch.int32):
     """Lay out a ragged list of references for the fixed-R interface.
 

@@ -112,3 +112,13 @@ def test_group_too_large_for_lds_falls_back_to_tables_in_the_workspace(lib):
     assert lib.tensorbleu_workspace_layout(2, 8, 8192, 8192, ctypes.byref(fused),
                                            ctypes.byref(lay)) == 3
     assert tb.tensorbleu_workspace_bytes(2, 8, 8192, 8192, fused) == 0
+
+
+def test_lengths_from_padding():
+    import torch
+    x = torch.tensor([[5, 0, 7, 0, 0], [0, 0, 0, 0, 0], [1, 2, 3, 4, 5], [0, 0, 3, 0, 0]])
+    assert tb.lengths_from_padding(x, 0).tolist() == [3, 0, 5, 3]      # inner pad ids are kept
+    assert tb.lengths_from_padding(x, 7).tolist() == [5, 5, 5, 5]
+    refs = x.view(2, 2, 5).to(torch.int64)
+    got = tb.lengths_from_padding(refs, 0)
+    assert got.dtype == torch.int32 and got.tolist() == [[3, 0], [5, 3]]
