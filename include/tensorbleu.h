@@ -63,8 +63,11 @@ typedef enum { TB_PATH_AUTO = 0, TB_PATH_FUSED = 1, TB_PATH_GLOBAL = 2 } tb_path
 
 /* Bits of *stats->device_status. */
 enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0, vocab_size) */
-       TB_DEV_LENGTH_RANGE = 2  /* a length outside [0, stride], or a reference count outside
-                                   [1, R], was clamped */ };
+       TB_DEV_LENGTH_RANGE = 2, /* a length outside [0, stride], or a reference count outside
+                                   [1, R], was clamped */
+       TB_DEV_TABLE_OVERFLOW = 4 /* GLOBAL path with partitioned tables (global_partitions > 0):
+                                   more distinct n-grams hashed into one partition than it can
+                                   hold; cannot happen unless keys are built to collide */ };
 
 typedef struct tb_config {
   int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1: "typically n=1 to 4");
@@ -119,7 +122,9 @@ typedef struct tb_layout {
   int32_t key_bytes[8];    /* 8 or 16 per order */
   int64_t group_cap;       /* cand_stride + R*ref_stride */
   size_t  keys_off[8];     /* packed keys of order n: B*group_cap entries of key_bytes[n-1] */
-  size_t  inv_off[8];      /* uint32 offset ids (g*group_cap + dense id in the group's dictionary) */
+  size_t  inv_off[8];      /* uint32 offset ids: g*id_stride + the n-gram's id in the group's
+                              dictionary (ids are below id_stride; dense 0..distinct-1 unless
+                              global_partitions > 0) */
   size_t  clipped_off, total_off, closest_off, distinct_off; /* int32 [B,N],[B,N],[B],[B,N] */
   size_t  corpus_off;      /* int64 [2N+2] */
   size_t  bytes;           /* total workspace size for this path */
@@ -128,6 +133,12 @@ typedef struct tb_layout {
   int32_t global_tables_in_hbm; /* 1 if the group is too large for the LDS kernels: the GLOBAL
                               path then keeps its hash tables and counters at tables_off */
   size_t  tables_off;
+  int64_t id_stride;       /* id range per group on the GLOBAL path: group_cap, or more when
+                              global_partitions > 0 */
+  int32_t global_partitions; /* P > 0: groups beyond the single-table LDS kernels (12 288 slots)
+                              but within 65 536 are handled by P workgroups per (group, order),
+                              each keeping one hash partition of the dictionary in LDS; ids are
+                              then p*6144 + a number dense within partition p */
 } tb_layout_t;
 
 /* Workspace size in bytes for a problem shape (pure host function of the shapes; 0 on invalid

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libtensorbleu.so")
 TB_OK = 0
 SMOOTHING = {"none": 0, "floor": 1, "add-k": 2, "exp": 3}
 PATHS = {"auto": 0, "fused": 1, "global": 2}
-TB_DEV_TOKEN_RANGE, TB_DEV_LENGTH_RANGE = 1, 2
+TB_DEV_TOKEN_RANGE, TB_DEV_LENGTH_RANGE, TB_DEV_TABLE_OVERFLOW = 1, 2, 4
 
 EXPORTS = [
     "tensorbleu_workspace_bytes", "tensorbleu_workspace_layout", "tensorbleu_sentence",
@@ -51,7 +51,8 @@ class tb_layout_t(ctypes.Structure):
                 ("closest_off", ctypes.c_size_t), ("distinct_off", ctypes.c_size_t),
                 ("corpus_off", ctypes.c_size_t), ("bytes", ctypes.c_size_t),
                 ("fused_ok", ctypes.c_int32), ("global_ok", ctypes.c_int32),
-                ("global_tables_in_hbm", ctypes.c_int32), ("tables_off", ctypes.c_size_t)]
+                ("global_tables_in_hbm", ctypes.c_int32), ("tables_off", ctypes.c_size_t),
+                ("id_stride", ctypes.c_int64), ("global_partitions", ctypes.c_int32)]
 
 
 class TensorBLEUError(RuntimeError):

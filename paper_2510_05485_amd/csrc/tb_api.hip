@@ -34,7 +34,9 @@ struct Plans {
   CountPlan count;
   FusedPlan fused;
   BigPlan big;
-  bool use_big;  // GLOBAL path with tables in the workspace (group too large for LDS)
+  PartPlan part;
+  bool use_part;  // GLOBAL path with P workgroups per (group, order), tables split over their LDS
+  bool use_big;   // GLOBAL path with tables in the workspace (group too large for that, too)
 };
 
 // Everything that depends on shapes only.  Returns TB_OK or an error.
@@ -51,15 +53,19 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     return TB_ERR_UNSUPPORTED;
   L.group_cap = cand_stride + int64_t(R) * ref_stride;
   // group_cap can reach 2^50 here: bound it first so that the product below cannot overflow
-  const bool ids_fit = L.group_cap < (int64_t(1) << 32) &&
-                       int64_t(B) * L.group_cap < (int64_t(1) << 32);
   const bool global_n = N * L.bits <= 128;  // the GLOBAL path packs whole n-grams into keys
   const bool lds_ok = global_n &&
                       plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
                       plan_count(L.group_cap, cand_stride, ref_stride, R, &p->count);
-  p->use_big = global_n && !lds_ok && plan_big(L.group_cap, N, &p->big);
-  L.global_ok = ids_fit && (lds_ok || p->use_big);
+  p->use_part = global_n && !lds_ok &&
+                plan_part(L.group_cap, cand_stride, ref_stride, R, N, L.key_bytes, &p->part);
+  p->use_big = global_n && !lds_ok && !p->use_part && plan_big(L.group_cap, N, &p->big);
+  L.id_stride = p->use_part ? p->part.id_stride : L.group_cap;
+  const bool ids_fit = L.id_stride < (int64_t(1) << 32) &&
+                       int64_t(B) * L.id_stride < (int64_t(1) << 32);
+  L.global_ok = ids_fit && (lds_ok || p->use_part || p->use_big);
   L.global_tables_in_hbm = p->use_big ? 1 : 0;
+  L.global_partitions = p->use_part ? (1 << p->part.log2_parts) : 0;
   L.fused_ok = plan_fused(cand_stride, ref_stride, R, N, L.bits, &p->fused);
   int path = cfg->force_path;
   if (path == TB_PATH_AUTO) path = L.fused_ok ? TB_PATH_FUSED : TB_PATH_GLOBAL;
@@ -87,6 +93,10 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     if (p->use_big) {
       L.tables_off = off;
       off = align_up(off + size_t(B) * N * size_t(p->big.table_entries) * 8);
+    }
+    if (p->use_part) {  // int32 [B, N, P]: dictionary size of every partition
+      L.tables_off = off;
+      off = align_up(off + ((size_t(B) * N) << p->part.log2_parts) * 4);
     }
   }
   L.bytes = off < kAlign ? kAlign : off;
@@ -145,7 +155,8 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                        ? reinterpret_cast<uint32_t*>(w + L.inv_off[n]) : nullptr;
     c->ws.wide[n] = L.key_bytes[n] == 16;
   }
-  c->ws.tables = (L.path == TB_PATH_GLOBAL && c->plans.use_big) ? w + L.tables_off : nullptr;
+  c->ws.tables = (L.path == TB_PATH_GLOBAL && (c->plans.use_big || c->plans.use_part))
+                     ? w + L.tables_off : nullptr;
   StatPtrs& st = c->st;
   st.clipped = (stats && stats->clipped) ? stats->clipped
                                          : reinterpret_cast<int32_t*>(w + L.clipped_off);
@@ -173,10 +184,12 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 
 hipError_t run_dictionary(const Call& c) {
+  if (c.plans.use_part) return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st, c.stream);
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }
 hipError_t run_count_clip(const Call& c) {
+  if (c.plans.use_part) return launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream);
   return c.plans.use_big ? launch_big_count_clip(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream);
 }

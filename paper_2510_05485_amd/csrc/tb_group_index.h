@@ -1,0 +1,80 @@
+// Where the sequences of a sentence group start inside the group's compact slot range.
+// Shared by the GLOBAL path's kernels (pack, dictionary, count/clip, LDS and partitioned).
+#pragma once
+
+#include "tb_common.h"
+
+namespace tb {
+
+// Clamped length of sequence j of group g (j = 0: candidate, j >= 1: reference j-1).
+// A reference beyond the candidate's reference count has no n-grams: length 0.
+__device__ __forceinline__ int seq_len(const Problem& pb, int g, int j) {
+  if (j == 0) return clamped_len(pb.cand_len[g], pb.cand_stride, nullptr);
+  if (j > refs_used(pb, g)) return 0;
+  return clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
+}
+
+// Where each sequence of group g starts inside the group's compact slot range for order n.
+// With at most 64 sequences per group every wavefront loads all lengths with one vector load
+// (lane j takes sequence j) and prefix-sums the n-gram counts with cross-lane shuffles, so no
+// chain of dependent scalar loads sits in front of the kernel's real work.  Larger groups fall
+// back to a loop.  Must be constructed and queried in wave-uniform control flow.
+class GroupIndex {
+ public:
+  // Issues the loads of the lengths and nothing else: the values are first touched by
+  // set_order(), so loads that the caller issues in between are in flight together with them.
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g)
+      : pb_(pb), g_(g), n_(1), fast_(pb.R < kWave), raw_(0), used_(pb.R), incl_(0) {
+    if (fast_) load_raw();
+  }
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g, int n) : GroupIndex(pb, g) {
+    set_order(n);
+  }
+  // For kernels that are only launched with fewer than 64 sequences per group: no loop fallback.
+  struct WaveOnly {};
+  __device__ __forceinline__ GroupIndex(const Problem& pb, int g, WaveOnly)
+      : pb_(pb), g_(g), n_(1), fast_(true), raw_(0), used_(pb.R), incl_(0) {
+    load_raw();
+  }
+  __device__ __forceinline__ void set_order(int n) {
+    n_ = n;
+    if (fast_) {
+      const int lane = threadIdx.x & (kWave - 1);
+      // (readfirstlane keeps the two strides in scalar registers: a select between the two
+      // fields would otherwise be turned into one vector load from a selected address)
+      const int cs = __builtin_amdgcn_readfirstlane(int(min(pb_.cand_stride, int64_t(1) << 30)));
+      const int rs = __builtin_amdgcn_readfirstlane(int(min(pb_.ref_stride, int64_t(1) << 30)));
+      const int used = min(max(used_, 1), pb_.R);  // references in use
+      const int len = lane <= used ? clamped_len(raw_, lane == 0 ? cs : rs, nullptr) : 0;
+      incl_ = wave_inclusive_scan(max(len - n + 1, 0));
+    }
+  }
+  // First slot of sequence j (0 = candidate); j = R + 1 gives the group's n-gram count.
+  __device__ __forceinline__ int start(int j) const {
+    if (j == 0) return 0;
+    if (fast_) return lane_value(incl_, j - 1);
+    int s = 0;
+    for (int jj = 0; jj < j; ++jj) s += max(seq_len(pb_, g_, jj) - n_ + 1, 0);
+    return s;
+  }
+  // Lane j <= R: one past the last slot of sequence j.  Only when the group has < 64 sequences.
+  __device__ __forceinline__ int end_in_lane() const { return incl_; }
+
+ private:
+  // lane j <= R: the stored length of sequence j; other lanes: 0
+  __device__ __forceinline__ void load_raw() {
+    const int lane = threadIdx.x & (kWave - 1);
+    raw_ = 0;
+    if (lane == 0)
+      raw_ = pb_.cand_len[g_];
+    else if (lane <= pb_.R)
+      raw_ = pb_.ref_len[int64_t(g_) * pb_.R + lane - 1];
+    if (pb_.ref_count) used_ = pb_.ref_count[g_];
+  }
+  const Problem& pb_;
+  int g_, n_;
+  bool fast_;
+  int raw_, used_, incl_;
+};
+
+}  // namespace tb

@@ -10,7 +10,8 @@ struct GlobalWs {
   void* keys[8];      // packed keys per order, B * group_cap entries of 8 or 16 bytes
   uint32_t* inv[8];   // offset dictionary ids per order, B * group_cap entries
   int32_t wide[8];    // 1 when the order uses 16-byte keys
-  void* tables;       // hash tables / counters in HBM (groups too large for LDS), else null
+  void* tables;       // hash tables / counters in HBM (groups too large for LDS), or the
+                      // per-partition dictionary sizes of the partitioned kernels, else null
 };
 
 // Integer statistics (either the caller's arrays or workspace scratch; never null).
@@ -59,6 +60,22 @@ struct BigPlan {
   int64_t slots;          // hash-table slots per (group, order): power of two >= 2 * group_cap
   int64_t table_entries;  // slots + padding, 8 bytes each
 };
+// Groups of up to 65 536 n-gram slots beyond the LDS plans: P workgroups per (group, order), each
+// with the dictionary entries / counters of one hash partition in LDS.
+struct PartPlan {
+  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 16
+  int id_cap;         // ids a partition may hand out
+  int words;          // count/clip: 32-bit counter words per id
+  int64_t id_stride;  // id range per group: max(group_cap, P * id_cap)
+  size_t dict_lds, count_lds;
+};
+bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
+               const int32_t* key_bytes, PartPlan* plan);
+hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
+                                  const StatPtrs& st, hipStream_t s);
+hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
+                                  const StatPtrs& st, hipStream_t s);
+
 bool plan_big(int64_t group_cap, int N, BigPlan* plan);
 hipError_t launch_big_dictionary(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
                                  const StatPtrs& st, hipStream_t s);

@@ -1,0 +1,353 @@
+// GLOBAL path for sentence groups of 12 289 .. 65 536 n-gram slots: too many for one LDS hash
+// table, few enough that the table can be split.  The dictionary and count/clip passes
+// (paper Sections 3.2-3.3) run with P workgroups per (group, order); workgroup p owns the
+// n-grams whose key hashes into partition p.  Every workgroup streams all of the group's keys
+// (or ids), which costs P sequential reads of data that sits in cache, and keeps its share of the
+// dictionary (or of the counters) in LDS, where random access is cheap -- the same kernels with
+// the table in HBM are about ten times slower per n-gram.
+//
+// Ids: partition p numbers its distinct n-grams 0, 1, ... and publishes them as p * id_cap + local,
+// so ids stay unique inside the group without any exchange between workgroups; they are no
+// longer dense, and the group's id range grows to id_stride = max(group_cap, P * id_cap).
+// Keys are spread over the partitions by a multiplicative hash; a partition that receives more
+// than id_cap distinct keys (possible only for keys built to collide) is reported through
+// TB_DEV_TABLE_OVERFLOW instead of being scored wrongly in silence.
+#include "tb_group_index.h"
+#include "tb_kernels.h"
+
+namespace tb {
+
+namespace {
+
+constexpr int kPartThreads = 1024;
+constexpr int kPartSlots = 8192;     // 8-byte table entries: 64 KB of LDS
+constexpr int kPartIdCap = 6144;     // distinct n-grams a partition may hold (3/4 of its slots)
+constexpr int kPartTarget = 4096;    // expected distinct n-grams per partition at most
+constexpr int kPartUnroll = 8;       // loads in flight per thread while streaming
+constexpr int kPartChunk = 4096;     // keys gathered per round of the dictionary's first pass
+constexpr unsigned long long kFreeEntry = ~0ull;
+
+struct PartArgs {
+  Problem pb;
+  GlobalWs ws;
+  StatPtrs st;
+  int32_t* part_distinct;  // [B, N, P] distinct n-grams per partition (dictionary -> count/clip)
+  int log2_parts;          // P = 1 << log2_parts, P >= 2
+  int words;               // count/clip: 32-bit counter words per id (two 16-bit fields each)
+  int64_t id_stride;       // ids of group g lie in [g * id_stride, (g + 1) * id_stride)
+};
+
+__device__ __forceinline__ uint32_t part_hash(uint64_t key) {
+  const uint32_t lo = uint32_t(key), hi = uint32_t(key >> 32);
+  return (lo ^ ((hi << 15) | (hi >> 17))) * 0x9E3779B1u;
+}
+// Partition of a key: the top bits of a second product, independent of the bits that pick the
+// slot (top bits of h) and the probe step.
+__device__ __forceinline__ int part_of(uint32_t h, int log2_parts) {
+  return int((h * 0x85EBCA6Bu + 0x27D4EB2Fu) >> (32 - log2_parts));
+}
+
+// Workgroup -> (group, order, partition).  Workgroups are handed to the eight XCDs in turn
+// (workgroup i runs on XCD i mod 8) and each XCD has its own L2, so the P workgroups that stream
+// the same keys are given indices that are equal mod 8: the keys then come from HBM once and
+// from that XCD's L2 the other P - 1 times.  g < 0: no work (the grid is rounded up).
+constexpr int kXcds = 8;
+struct Role {
+  int g, n, p;
+};
+__device__ __forceinline__ Role role_of_block(const PartArgs& a) {
+  const int parts = 1 << a.log2_parts;
+  const int xcd = int(blockIdx.x) % kXcds, j = int(blockIdx.x) / kXcds;
+  Role r;
+  r.p = j & (parts - 1);
+  const int64_t gn = int64_t(j >> a.log2_parts) * kXcds + xcd;
+  r.g = gn < int64_t(a.pb.B) * a.pb.N ? int(gn / a.pb.N) : -1;
+  r.n = int(gn % a.pb.N) + 1;
+  return r;
+}
+__host__ inline int64_t part_grid(const Problem& pb, const PartPlan& plan) {
+  const int64_t gn = int64_t(pb.B) * pb.N;
+  return (((gn + kXcds - 1) / kXcds * kXcds)) << plan.log2_parts;
+}
+
+__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int64_t count) {
+  const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < count) p[i] = 0;
+}
+
+// Dictionary of one partition of one (group, order).  Pass 1 inserts the partition's keys into
+// the LDS table and parks each occurrence's slot in the id array; the occupied entries are then
+// numbered; pass 2 replaces the parked slots by ids.
+__global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int scan_scratch[17];
+  __shared__ int list_count;
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const Role me = role_of_block(a);
+  if (me.g < 0) return;  // uniform over the workgroup
+  const int g = me.g, n = me.n, p = me.p;
+  constexpr int T = kPartSlots;
+  constexpr uint32_t mask = uint32_t(T) - 1u;
+  constexpr int shift = 32 - 13;  // log2(kPartSlots) = 13
+  static_assert((1 << 13) == kPartSlots, "table_shift");
+  unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
+  const uint64_t* gkeys =
+      reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+  uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
+  const GroupIndex gi(pb, g, n);
+  const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+
+  {  // T + 1 entries (entry T belongs to the all-ones key), 16 bytes per store
+    uint4* t4 = reinterpret_cast<uint4*>(table);
+    for (int s = tid; s < T / 2; s += nt) t4[s] = make_uint4(~0u, ~0u, ~0u, ~0u);
+    if (tid == 0) table[T] = kFreeEntry;
+  }
+  __syncthreads();
+
+  // Pass 1 in chunks of kPartChunk keys.  Only one key in P belongs to this partition, so the
+  // members of a chunk are first gathered (their position in the chunk, 16 bits) into an LDS
+  // list and then inserted by full wavefronts; inserting where they stand would leave P - 1 of
+  // P lanes idle in every probe loop.
+  uint16_t* list = reinterpret_cast<uint16_t*>(smem + size_t(T + 2) * 8);
+  bool lost = false;  // a probe sequence ran through the whole table
+  const int lane = tid & (kWave - 1);
+  for (int chunk = 0; chunk < count; chunk += kPartChunk) {
+    if (tid == 0) list_count = 0;
+    __syncthreads();
+    {
+      uint64_t key[kPartChunk / kPartThreads];
+#pragma unroll
+      for (int u = 0; u < kPartChunk / kPartThreads; ++u)
+        key[u] = gkeys[min(chunk + u * nt + tid, count - 1)];
+#pragma unroll
+      for (int u = 0; u < kPartChunk / kPartThreads; ++u) {
+        const int k = chunk + u * nt + tid;
+        const bool member =
+            k < count && (key[u] == kFreeEntry ? p == 0
+                                               : part_of(part_hash(key[u]), a.log2_parts) == p);
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(member);
+        int first = 0;
+        if (lane == 0 && m) first = atomicAdd(&list_count, __popcll(m));
+        first = __builtin_amdgcn_readfirstlane(first);
+        const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
+            uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), 0u));
+        if (member) list[first + int(rank)] = uint16_t(k - chunk);
+      }
+    }
+    __syncthreads();
+    const int members = list_count;
+    for (int e = tid; e < members; e += nt) {
+      const int k = chunk + int(list[e]);
+      const uint64_t key = gkeys[k];
+      if (key == kFreeEntry) {  // the all-ones key lives in partition 0, entry T
+        atomicCAS(&table[T], kFreeEntry, 0ull);
+        ginv[k] = uint32_t(T);
+        continue;
+      }
+      const uint32_t h = part_hash(key);
+      const uint32_t step = (h >> 3) | 1u;
+      uint32_t s = h >> shift;
+      unsigned long long old = atomicCAS(&table[s], kFreeEntry, key);
+      int rounds = 0;
+      while (int(old != kFreeEntry) & int(old != key) & int(rounds < T)) {
+        s = (s + step) & mask;
+        old = atomicCAS(&table[s], kFreeEntry, key);
+        ++rounds;
+      }
+      lost |= (old != kFreeEntry && old != key);
+      ginv[k] = s;
+    }
+  }
+  __syncthreads();
+
+  // number the occupied entries: every thread owns a run of consecutive slots, one
+  // workgroup-wide scan over the runs' counts gives each run its first id
+  int distinct = 0;
+  {
+    const int per_thread = (T + nt - 1) / nt;
+    const int s_begin = tid * per_thread, s_end = min(s_begin + per_thread, T);
+    int mine = 0;
+    for (int s = s_begin; s < s_end; ++s) mine += (table[s] != kFreeEntry) ? 1 : 0;
+    int id = block_exclusive_scan(mine, scan_scratch, &distinct);
+    for (int s = s_begin; s < s_end; ++s)
+      if (table[s] != kFreeEntry) table[s] = uint64_t(id++);
+    if (tid == 0 && table[T] != kFreeEntry) table[T] = uint64_t(distinct);  // the all-ones key
+    distinct += (table[T] != kFreeEntry) ? 1 : 0;  // read before or after thread 0's write: same
+  }
+  __syncthreads();
+  if ((lost || distinct > kPartIdCap) && pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
+
+  const uint32_t id_base =
+      uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
+  for (int base = 0; base < count; base += kPartUnroll * nt) {
+    uint64_t key[kPartUnroll];
+    uint32_t parked[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int k = min(base + u * nt + tid, count - 1);
+      key[u] = gkeys[k];
+      parked[u] = ginv[k];
+    }
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int k = base + u * nt + tid;
+      if (k >= count) continue;
+      const bool mine = key[u] == kFreeEntry
+                            ? p == 0
+                            : part_of(part_hash(key[u]), a.log2_parts) == p;
+      if (mine) ginv[k] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
+    }
+  }
+  if (tid == 0) {
+    a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
+    atomicAdd(&a.st.distinct[int64_t(g) * pb.N + n - 1], distinct);
+  }
+}
+
+// Count and clip the ids of one partition of one (group, order): one 16-bit LDS field per
+// (id, sequence) as in the LDS count kernel, filled while streaming all of the group's ids; then
+// a sweep over the partition's entries takes the maximum over the reference fields and the
+// minimum with the candidate field.
+__global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int red_scratch[17];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+  const Role me = role_of_block(a);
+  if (me.g < 0) return;  // uniform over the workgroup
+  const int g = me.g, n = me.n, p = me.p;
+  const int W = a.words;
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
+  const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
+  const uint32_t id_base =
+      uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
+  const int U = min(
+      max(a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p], 0),
+      kPartIdCap);
+  GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
+  gi.set_order(n);
+  const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+  const int ccnt = gi.start(1);
+  const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
+
+  {
+    uint4* c4 = reinterpret_cast<uint4*>(cnt);
+    const int quads = (U * W + 3) / 4;
+    for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  __syncthreads();
+
+  // a wavefront takes 64 consecutive slots at a time; their sequence (the number of sequences
+  // ending at or before the slot) is one scalar when the block lies inside one sequence
+  const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
+  for (int base = 0; base < count; base += kPartUnroll * nt) {
+    uint32_t id[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u)
+      id[u] = ginv[min(base + u * nt + tid, count - 1)] - id_base;
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int k0 = base + u * nt + wave_first;
+      if (k0 >= count) break;
+      const int k = k0 + lane;
+      const int f0 = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0));
+      const int f1 = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0 + kWave - 1));
+      int f = f0;
+      for (int j = f0; j < f1; ++j) f += (k >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
+      if (k < count && f <= pb.R && id[u] < uint32_t(U))
+        atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
+                  (f & 1) ? 0x10000u : 1u);
+    }
+  }
+  __syncthreads();
+
+  int part = 0;
+  for (int u = tid; u < U; u += nt) {
+    const uint32_t* e = &cnt[__umul24(uint32_t(u), uint32_t(W))];
+    const uint32_t w0 = e[0];
+    uint32_t m = w0 >> 16;
+    for (int q = 1; q < W; ++q) {
+      const uint32_t w = e[q];
+      m = max(m, max(w & 0xFFFFu, w >> 16));
+    }
+    part += int(min(w0 & 0xFFFFu, m));
+  }
+  const int clipped = block_sum(part, red_scratch);
+  if (tid == 0) {
+    if (clipped) atomicAdd(&a.st.clipped[int64_t(g) * pb.N + n - 1], clipped);
+    if (p == 0) a.st.total[int64_t(g) * pb.N + n - 1] = ccnt;
+  }
+}
+
+PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
+                   const StatPtrs& st) {
+  PartArgs a;
+  a.pb = pb;
+  a.ws = ws;
+  a.st = st;
+  a.part_distinct = static_cast<int32_t*>(ws.tables);
+  a.log2_parts = plan.log2_parts;
+  a.words = plan.words;
+  a.id_stride = plan.id_stride;
+  return a;
+}
+
+hipError_t zero_ints(int32_t* p, int64_t count, hipStream_t s) {
+  const int64_t blocks = (count + 255) / 256;
+  if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(zero_ints_kernel, dim3(uint32_t(blocks)), dim3(256), 0, s, p, count);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
+               const int32_t* key_bytes, PartPlan* plan) {
+  for (int n = 0; n < N; ++n)
+    if (key_bytes[n] != 8) return false;  // 16-byte keys: the workspace-table kernels
+  if (R >= kWave - 1 || cand_stride > 65535 || ref_stride > 65535) return false;
+  int lg = 1;
+  while ((int64_t(kPartTarget) << lg) < group_cap) ++lg;
+  if (lg > 4) return false;  // more than 16 partitions: the streaming reads stop paying
+  plan->log2_parts = lg;
+  plan->id_cap = kPartIdCap;
+  plan->words = (R + 2) / 2;
+  plan->id_stride = group_cap;
+  if ((int64_t(kPartIdCap) << lg) > plan->id_stride) plan->id_stride = int64_t(kPartIdCap) << lg;
+  plan->dict_lds = size_t(kPartSlots + 2) * 8 + size_t(kPartChunk) * 2;
+  plan->count_lds = (size_t(kPartIdCap) * plan->words * 4 + 15) & ~size_t(15);
+  return plan->count_lds + 256 <= size_t(kLdsBudget);
+}
+
+hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
+                                  const StatPtrs& st, hipStream_t s) {
+  const PartArgs a = make_args(pb, ws, plan, st);
+  const int64_t blocks = part_grid(pb, plan);
+  if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipError_t e = zero_ints(st.distinct, int64_t(pb.B) * pb.N, s);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(part_dictionary_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
+                     plan.dict_lds, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
+                                  const StatPtrs& st, hipStream_t s) {
+  const PartArgs a = make_args(pb, ws, plan, st);
+  const int64_t blocks = part_grid(pb, plan);
+  if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_count_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.count_lds));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(part_count_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
+                     plan.count_lds, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace tb

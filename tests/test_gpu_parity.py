@@ -227,13 +227,19 @@ def test_sixty_three_references(path):
 
 
 @pytest.mark.parametrize("vocab", [50, 50257, 262144])
-def test_group_too_large_for_lds_is_scored_with_tables_in_hbm(vocab):
-    # cand_stride + R * ref_stride = 16400 > 12288: neither LDS plan applies
+def test_group_too_large_for_one_lds_table(vocab):
+    # cand_stride + R * ref_stride = 16400 > 12288: neither single-table LDS plan applies.  With
+    # 8-byte keys the dictionary is split over eight workgroups per (group, order); the 72-bit
+    # 4-grams of the largest vocabulary send the group to the tables in the workspace.
     w = cached_small(144, B=3, R=3, vocab=vocab, max_len=4100, min_len=3500)
     cfg = tb.make_config(vocab_size=w.vocab, path="auto")
     lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
-    assert lay.fused_ok == 0 and lay.global_ok == 1 and lay.global_tables_in_hbm == 1
-    assert lay.path == 2
+    assert lay.fused_ok == 0 and lay.global_ok == 1 and lay.path == 2
+    if vocab == 262144:
+        assert lay.global_tables_in_hbm == 1 and lay.global_partitions == 0
+    else:
+        assert lay.global_tables_in_hbm == 0 and lay.global_partitions == 8
+        assert lay.id_stride == 8 * 6144
     d = Device(w)
     for run in (syn.Run("exp"), syn.Run("add-k", 1.0)):
         check(w, run, "auto", d=d)

@@ -98,3 +98,64 @@ def test_staged_calls_equal_the_single_call_on_config1():
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="add-k", smooth_param=1.0)
     np.testing.assert_array_equal(cstats.corpus_stats.cpu().numpy(), ref.corpus_stats)
     assert abs(cout[0] - ref.corpus_bleu) <= 1e-5
+
+
+def test_partitioned_dictionary_ids_are_a_bijection_within_the_group():
+    """Groups of 12 289 .. 65 536 slots: the dictionary is split over P workgroups and ids are
+    p * 6144 + a number dense within partition p.  What is unique: equal n-gram <=> equal id, ids
+    below id_stride, and the distinct count."""
+    w = syn.random_small(205, B=2, R=2, vocab=300, max_len=5000, min_len=4200)
+    lay, wsb, stats, out = stage_all(w)
+    assert lay.global_partitions == 4 and lay.id_stride == 4 * 6144 and lay.global_tables_in_hbm == 0
+    cap, stride = lay.group_cap, lay.id_stride
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+    for n in range(1, 5):
+        inv = wsb[lay.inv_off[n - 1]: lay.inv_off[n - 1] + w.B * cap * 4].view(np.uint32)
+        for g in range(w.B):
+            rows = [(w.cand[g], w.cand_len[g])] + [
+                (w.refs[g, j], w.ref_len[g, j]) for j in range(w.R)]
+            seen, slot = {}, g * cap
+            for row, ln in rows:
+                for p in range(max(ln - n + 1, 0)):
+                    gram = tuple(int(t) for t in row[p:p + n])
+                    local = int(inv[slot]) - g * stride
+                    assert 0 <= local < stride
+                    assert seen.setdefault(gram, local) == local
+                    slot += 1
+            assert len(set(seen.values())) == len(seen) == ref.group_distinct[g, n - 1]
+    assert stats.device_status.item() == 0
+    np.testing.assert_array_equal(stats.group_distinct.cpu().numpy(), ref.group_distinct)
+    np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
+    np.testing.assert_array_equal(stats.total.cpu().numpy(), ref.total)
+    assert np.abs(out - ref.bleu).max() <= 1e-5
+
+
+def test_partition_overflow_is_reported_not_hidden():
+    """More distinct n-grams in one hash partition than it can hold (6144) is only possible with
+    tokens chosen to collide; the kernels then finish normally and set TB_DEV_TABLE_OVERFLOW."""
+    M = 1 << 32
+    part = lambda t: ((((t * 0x9E3779B1) % M) * 0x85EBCA6B + 0x27D4EB2F) % M) >> 30   # P = 4
+    colliding = [t for t in range(40000) if part(t) == 0][:7000]
+    assert len(colliding) == 7000
+    L = 8000
+    cand = np.zeros((1, L), np.int32)
+    cand[0, :7000] = colliding
+    refs = np.zeros((1, 1, L), np.int32)
+    refs[0, 0, :7000] = colliding[::-1]
+    cl, rl = np.array([7000], np.int32), np.array([[7000]], np.int32)
+    cfg = tb.make_config(vocab_size=40000, path="global")
+    lay = tb.tensorbleu_workspace_layout(1, 1, L, L, cfg)
+    assert lay.global_partitions == 4
+    st = tb.Stats.allocate(1, 4, DEV)
+    out = tb.tensorbleu_sentence(dev(cand), dev(cl), dev(refs), dev(rl), cfg, stats=st)
+    torch.cuda.synchronize()
+    assert st.device_status.item() & tb.TB_DEV_TABLE_OVERFLOW
+    assert np.isfinite(out.cpu().numpy()).all()
+    # the same shape with ordinary tokens is scored and not flagged
+    w = syn.random_small(206, B=1, R=1, vocab=40000, max_len=L, min_len=7000)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len)
+    st = tb.Stats.allocate(1, 4, DEV)
+    tb.tensorbleu_sentence(dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len), cfg, stats=st)
+    torch.cuda.synchronize()
+    assert st.device_status.item() == 0
+    np.testing.assert_array_equal(st.clipped.cpu().numpy(), ref.clipped)
