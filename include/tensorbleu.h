@@ -138,7 +138,9 @@ typedef struct tb_layout {
   int32_t global_partitions; /* P > 0: groups beyond the single-table LDS kernels (12 288 slots)
                               but within 65 536 are handled by P workgroups per (group, order),
                               each keeping one hash partition of the dictionary in LDS; ids are
-                              then p*6144 + a number dense within partition p */
+                              then p*6144 + a number dense within partition p.  Orders whose
+                              packed keys take 16 bytes are keyed there by (id of the (n-1)-gram
+                              at the same position, last token) */
 } tb_layout_t;
 
 /* Workspace size in bytes for a problem shape (pure host function of the shapes; 0 on invalid

@@ -12,6 +12,12 @@
 // Keys are spread over the partitions by a multiplicative hash; a partition that receives more
 // than id_cap distinct keys (possible only for keys built to collide) is reported through
 // TB_DEV_TABLE_OVERFLOW instead of being scored wrongly in silence.
+//
+// Orders whose packed n-grams need 16 bytes get an 8-byte key of their own here: (id of the
+// (n-1)-gram that starts at the same position, last token).  Two n-grams are equal exactly when
+// their (n-1)-gram prefixes are equal -- i.e. have the same id -- and their last tokens are equal,
+// so this key identifies the n-gram as exactly as the packed one does; it needs the dictionary of
+// order n - 1 to be complete, hence one launch per such order after the others.
 #include "tb_group_index.h"
 #include "tb_kernels.h"
 
@@ -33,6 +39,9 @@ struct PartArgs {
   StatPtrs st;
   int32_t* part_distinct;  // [B, N, P] distinct n-grams per partition (dictionary -> count/clip)
   int log2_parts;          // P = 1 << log2_parts, P >= 2
+  int orders[8];           // dictionary: the orders of this launch, and how many
+  int num_orders;
+  int derived;             // dictionary: 1 if this launch's orders use (prefix id, last token) keys
   int words;               // count/clip: 32-bit counter words per id (two 16-bit fields each)
   int64_t id_stride;       // ids of group g lie in [g * id_stride, (g + 1) * id_stride)
 };
@@ -55,18 +64,21 @@ constexpr int kXcds = 8;
 struct Role {
   int g, n, p;
 };
-__device__ __forceinline__ Role role_of_block(const PartArgs& a) {
+// `orders` / `num_orders`: the orders this launch handles (null: all of 1..N).
+__device__ __forceinline__ Role role_of_block(const PartArgs& a, const int* orders,
+                                              int num_orders) {
   const int parts = 1 << a.log2_parts;
   const int xcd = int(blockIdx.x) % kXcds, j = int(blockIdx.x) / kXcds;
   Role r;
   r.p = j & (parts - 1);
   const int64_t gn = int64_t(j >> a.log2_parts) * kXcds + xcd;
-  r.g = gn < int64_t(a.pb.B) * a.pb.N ? int(gn / a.pb.N) : -1;
-  r.n = int(gn % a.pb.N) + 1;
+  r.g = gn < int64_t(a.pb.B) * num_orders ? int(gn / num_orders) : -1;
+  const int idx = int(gn % num_orders);
+  r.n = orders ? orders[idx] : idx + 1;
   return r;
 }
-__host__ inline int64_t part_grid(const Problem& pb, const PartPlan& plan) {
-  const int64_t gn = int64_t(pb.B) * pb.N;
+__host__ inline int64_t part_grid(const Problem& pb, const PartPlan& plan, int num_orders) {
+  const int64_t gn = int64_t(pb.B) * num_orders;
   return (((gn + kXcds - 1) / kXcds * kXcds)) << plan.log2_parts;
 }
 
@@ -84,7 +96,7 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   __shared__ int list_count;
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
-  const Role me = role_of_block(a);
+  const Role me = role_of_block(a, a.orders, a.num_orders);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
   constexpr int T = kPartSlots;
@@ -92,11 +104,41 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   constexpr int shift = 32 - 13;  // log2(kPartSlots) = 13
   static_assert((1 << 13) == kPartSlots, "table_shift");
   unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
-  const uint64_t* gkeys =
-      reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
-  const GroupIndex gi(pb, g, n);
+  GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
+  // derived keys: lane j holds how far sequence j's slots of order n - 1 lie behind its slots
+  // of order n (every earlier sequence has up to one (n-1)-gram more), and the end of sequence j
+  int shift_lane = 0;
+  if (a.derived) {
+    gi.set_order(n - 1);
+    shift_lane = gi.end_in_lane();
+  }
+  gi.set_order(n);
+  const int end_lane = gi.end_in_lane();
+  {
+    const int d = shift_lane - end_lane;  // lane j: start_{n-1}(j + 1) - start_n(j + 1)
+    shift_lane = __shfl_up(d, 1, kWave);
+    if ((tid & (kWave - 1)) == 0) shift_lane = 0;
+  }
   const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+  const uint64_t* narrow_keys =
+      reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+  const Key128* wide_keys =
+      reinterpret_cast<const Key128*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+  const uint32_t* prev_inv = a.ws.inv[max(n - 2, 0)] + int64_t(g) * pb.group_cap;
+  const uint32_t prev_base = uint32_t(int64_t(g) * a.id_stride);
+  const uint64_t token_mask = (uint64_t(1) << pb.bits) - 1u;
+  // the key of slot k (k < count) of this (group, order)
+  auto load_key = [&](int k) -> uint64_t {
+    if (!a.derived) return narrow_keys[k];
+    int shift = 0;  // of the sequence that slot k belongs to
+    for (int j = 0; j < pb.R; ++j) {
+      const bool past = k >= __builtin_amdgcn_readlane(end_lane, j);
+      shift = past ? __builtin_amdgcn_readlane(shift_lane, j + 1) : shift;
+    }
+    const uint64_t prefix = prev_inv[k + shift] - prev_base;
+    return (prefix << pb.bits) | (wide_keys[k].lo & token_mask);
+  };
 
   {  // T + 1 entries (entry T belongs to the all-ones key), 16 bytes per store
     uint4* t4 = reinterpret_cast<uint4*>(table);
@@ -119,7 +161,7 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
       uint64_t key[kPartChunk / kPartThreads];
 #pragma unroll
       for (int u = 0; u < kPartChunk / kPartThreads; ++u)
-        key[u] = gkeys[min(chunk + u * nt + tid, count - 1)];
+        key[u] = load_key(min(chunk + u * nt + tid, count - 1));
 #pragma unroll
       for (int u = 0; u < kPartChunk / kPartThreads; ++u) {
         const int k = chunk + u * nt + tid;
@@ -139,7 +181,7 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
     const int members = list_count;
     for (int e = tid; e < members; e += nt) {
       const int k = chunk + int(list[e]);
-      const uint64_t key = gkeys[k];
+      const uint64_t key = load_key(k);
       if (key == kFreeEntry) {  // the all-ones key lives in partition 0, entry T
         atomicCAS(&table[T], kFreeEntry, 0ull);
         ginv[k] = uint32_t(T);
@@ -186,7 +228,7 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       const int k = min(base + u * nt + tid, count - 1);
-      key[u] = gkeys[k];
+      key[u] = load_key(k);
       parked[u] = ginv[k];
     }
 #pragma unroll
@@ -214,7 +256,7 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   __shared__ int red_scratch[17];
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
-  const Role me = role_of_block(a);
+  const Role me = role_of_block(a, nullptr, a.pb.N);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
   const int W = a.words;
@@ -290,6 +332,9 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
   a.id_stride = plan.id_stride;
+  for (int k = 0; k < 8; ++k) a.orders[k] = 0;
+  a.num_orders = 0;
+  a.derived = 0;
   return a;
 }
 
@@ -304,8 +349,7 @@ hipError_t zero_ints(int32_t* p, int64_t count, hipStream_t s) {
 
 bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
                const int32_t* key_bytes, PartPlan* plan) {
-  for (int n = 0; n < N; ++n)
-    if (key_bytes[n] != 8) return false;  // 16-byte keys: the workspace-table kernels
+  (void)key_bytes;  // orders with 16-byte keys are keyed by (prefix id, last token) instead
   if (R >= kWave - 1 || cand_stride > 65535 || ref_stride > 65535) return false;
   int lg = 1;
   while ((int64_t(kPartTarget) << lg) < group_cap) ++lg;
@@ -322,23 +366,37 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s) {
-  const PartArgs a = make_args(pb, ws, plan, st);
-  const int64_t blocks = part_grid(pb, plan);
-  if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipError_t e = zero_ints(st.distinct, int64_t(pb.B) * pb.N, s);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(part_dictionary_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
-                     plan.dict_lds, s, a);
-  return hipGetLastError();
+  // one launch for the orders with 8-byte packed keys, then one per order with 16-byte keys in
+  // ascending order (each is keyed by the ids of the order below it)
+  PartArgs a = make_args(pb, ws, plan, st);
+  for (int n = 1; n <= pb.N; ++n)
+    if (!ws.wide[n - 1]) a.orders[a.num_orders++] = n;
+  for (int next_wide = 1; next_wide <= pb.N + 1; ++next_wide) {
+    if (a.num_orders) {
+      const int64_t blocks = part_grid(pb, plan, a.num_orders);
+      if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+      hipLaunchKernelGGL(part_dictionary_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
+                         plan.dict_lds, s, a);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    a.num_orders = 0;
+    a.derived = 1;
+    while (next_wide <= pb.N && !ws.wide[next_wide - 1]) ++next_wide;
+    if (next_wide <= pb.N) a.orders[a.num_orders++] = next_wide;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s) {
   const PartArgs a = make_args(pb, ws, plan, st);
-  const int64_t blocks = part_grid(pb, plan);
+  const int64_t blocks = part_grid(pb, plan, pb.N);
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
   if (e != hipSuccess) return e;

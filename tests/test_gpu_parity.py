@@ -229,17 +229,14 @@ def test_sixty_three_references(path):
 @pytest.mark.parametrize("vocab", [50, 50257, 262144])
 def test_group_too_large_for_one_lds_table(vocab):
     # cand_stride + R * ref_stride = 16400 > 12288: neither single-table LDS plan applies.  With
-    # 8-byte keys the dictionary is split over eight workgroups per (group, order); the 72-bit
-    # 4-grams of the largest vocabulary send the group to the tables in the workspace.
+    # The dictionary is split over eight workgroups per (group, order); the 72-bit 4-grams of the
+    # largest vocabulary are keyed there by (id of the 3-gram prefix, last token).
     w = cached_small(144, B=3, R=3, vocab=vocab, max_len=4100, min_len=3500)
     cfg = tb.make_config(vocab_size=w.vocab, path="auto")
     lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
     assert lay.fused_ok == 0 and lay.global_ok == 1 and lay.path == 2
-    if vocab == 262144:
-        assert lay.global_tables_in_hbm == 1 and lay.global_partitions == 0
-    else:
-        assert lay.global_tables_in_hbm == 0 and lay.global_partitions == 8
-        assert lay.id_stride == 8 * 6144
+    assert lay.global_tables_in_hbm == 0 and lay.global_partitions == 8
+    assert lay.id_stride == 8 * 6144
     d = Device(w)
     for run in (syn.Run("exp"), syn.Run("add-k", 1.0)):
         check(w, run, "auto", d=d)
@@ -380,8 +377,14 @@ def test_more_than_four_orders(N, seed, B, R, V, L):
 def test_more_than_four_orders_on_the_global_path_large_and_tiny_groups(N):
     w = cached_small(304, B=3, R=2, vocab=65536, max_len=1500)        # 16-byte keys from n = 5
     check(w, syn.Run("exp"), "global", max_n=N, weights=[1.0 / N] * N)
-    w = cached_small(305, B=2, R=1, vocab=4, max_len=9000)            # tables in the workspace
+    w = cached_small(305, B=2, R=1, vocab=4, max_len=9000)            # partitioned LDS tables
     check(w, syn.Run("floor", 0.1), "global", max_n=N, weights=[1.0 / N] * N)
+    # partitioned tables where every order from 3 (93 bits) to 4 needs 16-byte packed keys and is
+    # keyed by (id of its prefix, last token) instead, each on the ids of the order below
+    w = cached_small(307, B=2, R=2, vocab=2 ** 31 - 1, max_len=5000, min_len=4000)
+    check(w, syn.Run("exp"), "global", max_n=min(N, 4), weights=[1.0 / min(N, 4)] * min(N, 4))
+    w = cached_small(308, B=2, R=1, vocab=60000, max_len=8000, min_len=7000)   # 16 bits: wide from 5
+    check(w, syn.Run("exp"), "global", max_n=N, weights=[1.0 / N] * N)
     w = cached_small(306, B=600, R=1, vocab=200, max_len=40)          # many groups: paired orders
     check(w, syn.Run("none"), "global", max_n=N, weights=[1.0 / N] * N)
 
