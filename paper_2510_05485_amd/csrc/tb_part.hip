@@ -151,7 +151,11 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   // members of a chunk are first gathered (their position in the chunk, 16 bits) into an LDS
   // list and then inserted by full wavefronts; inserting where they stand would leave P - 1 of
   // P lanes idle in every probe loop.
+  // Which slots are members is also kept, one bit per slot (the ballot of a wavefront's 64
+  // consecutive slots is the 64-bit word): pass 2 then needs neither the keys nor their hashes.
   uint16_t* list = reinterpret_cast<uint16_t*>(smem + size_t(T + 2) * 8);
+  unsigned long long* member_bits =
+      reinterpret_cast<unsigned long long*>(smem + size_t(T + 2) * 8 + size_t(kPartChunk) * 2);
   bool lost = false;  // a probe sequence ran through the whole table
   const int lane = tid & (kWave - 1);
   for (int chunk = 0; chunk < count; chunk += kPartChunk) {
@@ -170,7 +174,10 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
                                                : part_of(part_hash(key[u]), a.log2_parts) == p);
         const unsigned long long m = __builtin_amdgcn_ballot_w64(member);
         int first = 0;
-        if (lane == 0 && m) first = atomicAdd(&list_count, __popcll(m));
+        if (lane == 0) {
+          if (k < count) member_bits[k >> 6] = m;  // k is a multiple of 64 in lane 0
+          if (m) first = atomicAdd(&list_count, __popcll(m));
+        }
         first = __builtin_amdgcn_readfirstlane(first);
         const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
             uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), 0u));
@@ -203,16 +210,15 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   }
   __syncthreads();
 
-  // number the occupied entries: every thread owns a run of consecutive slots, one
-  // workgroup-wide scan over the runs' counts gives each run its first id
+  // number the occupied entries (any numbering that is dense and unique will do): thread t owns
+  // the slots t, t + nt, t + 2 nt, ... -- neighbouring lanes then touch neighbouring LDS words --
+  // and one workgroup-wide scan over the threads' counts gives each thread its first id
   int distinct = 0;
   {
-    const int per_thread = (T + nt - 1) / nt;
-    const int s_begin = tid * per_thread, s_end = min(s_begin + per_thread, T);
     int mine = 0;
-    for (int s = s_begin; s < s_end; ++s) mine += (table[s] != kFreeEntry) ? 1 : 0;
+    for (int s = tid; s < T; s += nt) mine += (table[s] != kFreeEntry) ? 1 : 0;
     int id = block_exclusive_scan(mine, scan_scratch, &distinct);
-    for (int s = s_begin; s < s_end; ++s)
+    for (int s = tid; s < T; s += nt)
       if (table[s] != kFreeEntry) table[s] = uint64_t(id++);
     if (tid == 0 && table[T] != kFreeEntry) table[T] = uint64_t(distinct);  // the all-ones key
     distinct += (table[T] != kFreeEntry) ? 1 : 0;  // read before or after thread 0's write: same
@@ -223,22 +229,15 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   const uint32_t id_base =
       uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
   for (int base = 0; base < count; base += kPartUnroll * nt) {
-    uint64_t key[kPartUnroll];
     uint32_t parked[kPartUnroll];
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) {
-      const int k = min(base + u * nt + tid, count - 1);
-      key[u] = load_key(k);
-      parked[u] = ginv[k];
-    }
+    for (int u = 0; u < kPartUnroll; ++u) parked[u] = ginv[min(base + u * nt + tid, count - 1)];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       const int k = base + u * nt + tid;
       if (k >= count) continue;
-      const bool mine = key[u] == kFreeEntry
-                            ? p == 0
-                            : part_of(part_hash(key[u]), a.log2_parts) == p;
-      if (mine) ginv[k] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
+      if ((member_bits[k >> 6] >> (k & 63)) & 1ull)
+        ginv[k] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
     }
   }
   if (tid == 0) {
@@ -359,7 +358,9 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
   plan->words = (R + 2) / 2;
   plan->id_stride = group_cap;
   if ((int64_t(kPartIdCap) << lg) > plan->id_stride) plan->id_stride = int64_t(kPartIdCap) << lg;
-  plan->dict_lds = size_t(kPartSlots + 2) * 8 + size_t(kPartChunk) * 2;
+  // table, member list of a chunk, one membership bit per slot of the group
+  plan->dict_lds = size_t(kPartSlots + 2) * 8 + size_t(kPartChunk) * 2 +
+                   size_t((group_cap + 63) / 64) * 8;
   plan->count_lds = (size_t(kPartIdCap) * plan->words * 4 + 15) & ~size_t(15);
   return plan->count_lds + 256 <= size_t(kLdsBudget);
 }
