@@ -158,9 +158,9 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
       reinterpret_cast<unsigned long long*>(smem + size_t(T + 2) * 8 + size_t(kPartChunk) * 2);
   bool lost = false;  // a probe sequence ran through the whole table
   const int lane = tid & (kWave - 1);
+  if (tid == 0) list_count = 0;
   for (int chunk = 0; chunk < count; chunk += kPartChunk) {
-    if (tid == 0) list_count = 0;
-    __syncthreads();
+    __syncthreads();  // the counter is zero and the previous chunk's list has been consumed
     {
       uint64_t key[kPartChunk / kPartThreads];
 #pragma unroll
@@ -186,6 +186,8 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
     }
     __syncthreads();
     const int members = list_count;
+    __syncthreads();  // every thread has the count: the counter may be reset for the next chunk
+    if (tid == 0) list_count = 0;
     for (int e = tid; e < members; e += nt) {
       const int k = chunk + int(list[e]);
       const uint64_t key = load_key(k);
