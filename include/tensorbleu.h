@@ -70,7 +70,7 @@ enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0,
                                    hold; cannot happen unless keys are built to collide */ };
 
 typedef struct tb_config {
-  int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1: "typically n=1 to 4");
+  int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1 names 1 to 4 as the usual range);
                            the GLOBAL path packs whole n-grams into keys and so needs
                            N * bits <= 128, the FUSED path has no such limit */
   float   weights[8];   /* w_1..w_N of the BLEU equation, used as given (not renormalised);
