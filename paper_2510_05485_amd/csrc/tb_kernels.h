@@ -60,10 +60,10 @@ struct BigPlan {
   int64_t slots;          // hash-table slots per (group, order): power of two >= 2 * group_cap
   int64_t table_entries;  // slots + padding, 8 bytes each
 };
-// Groups of up to 65 536 n-gram slots beyond the LDS plans: P workgroups per (group, order), each
+// Groups of up to 131 072 n-gram slots beyond the LDS plans: P workgroups per (group, order), each
 // with the dictionary entries / counters of one hash partition in LDS.
 struct PartPlan {
-  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 16
+  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 32
   int id_cap;         // ids a partition may hand out
   int words;          // count/clip: 32-bit counter words per id
   int64_t id_stride;  // id range per group: max(group_cap, P * id_cap)

@@ -1,4 +1,4 @@
-// GLOBAL path for sentence groups of 12 289 .. 65 536 n-gram slots: too many for one LDS hash
+// GLOBAL path for sentence groups of 12 289 .. 131 072 n-gram slots: too many for one LDS hash
 // table, few enough that the table can be split.  The dictionary and count/clip passes
 // (paper Sections 3.2-3.3) run with P workgroups per (group, order); workgroup p owns the
 // n-grams whose key hashes into partition p.  Every workgroup streams all of the group's keys
@@ -354,7 +354,7 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
   if (R >= kWave - 1 || cand_stride > 65535 || ref_stride > 65535) return false;
   int lg = 1;
   while ((int64_t(kPartTarget) << lg) < group_cap) ++lg;
-  if (lg > 4) return false;  // more than 16 partitions: the streaming reads stop paying
+  if (lg > 5) return false;  // more than 32 partitions: the streaming reads stop paying
   plan->log2_parts = lg;
   plan->id_cap = kPartIdCap;
   plan->words = (R + 2) / 2;

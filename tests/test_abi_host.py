@@ -103,15 +103,32 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
 def test_group_too_large_for_lds_falls_back_to_tables_in_the_workspace(lib):
     cfg = tb.make_config(vocab_size=50257, path="global")
     lay = binding.tb_layout_t()
-    rc = lib.tensorbleu_workspace_layout(2, 8, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
+    # 17 * 8192 slots: beyond the single-table kernels (12 288) and the partitioned ones (131 072)
+    rc = lib.tensorbleu_workspace_layout(2, 16, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
     assert rc == 0 and lay.global_ok == 1 and lay.global_tables_in_hbm == 1
-    cap = 9 * 8192
+    assert lay.global_partitions == 0 and lay.id_stride == lay.group_cap
+    cap = 17 * 8192
     slots = 1 << (2 * cap - 1).bit_length()
     assert lay.bytes >= lay.tables_off + 2 * 4 * (slots + 8) * 8
     fused = tb.make_config(vocab_size=50257, path="fused")
-    assert lib.tensorbleu_workspace_layout(2, 8, 8192, 8192, ctypes.byref(fused),
+    assert lib.tensorbleu_workspace_layout(2, 16, 8192, 8192, ctypes.byref(fused),
                                            ctypes.byref(lay)) == 3
-    assert tb.tensorbleu_workspace_bytes(2, 8, 8192, 8192, fused) == 0
+    assert tb.tensorbleu_workspace_bytes(2, 16, 8192, 8192, fused) == 0
+
+
+def test_partitioned_layout_between_the_lds_kernels_and_the_workspace_tables(lib):
+    cfg = tb.make_config(vocab_size=50257, path="global")
+    lay = tb.tensorbleu_workspace_layout(2, 8, 8192, 8192, cfg)       # 73 728 slots
+    assert lay.global_ok == 1 and lay.global_tables_in_hbm == 0
+    assert lay.global_partitions == 32 and lay.id_stride == 32 * 6144
+    assert lay.bytes >= lay.tables_off + 2 * 4 * 32 * 4               # int32 [B, N, P]
+    small = tb.tensorbleu_workspace_layout(2, 1, 8192, 8192, cfg)     # 16 384 slots
+    assert small.global_partitions == 4 and small.id_stride == 4 * 6144
+    # more references than the partitioned count kernel has LDS for: tables in the workspace
+    many = tb.tensorbleu_workspace_layout(2, 12, 2048, 2048, cfg)
+    assert many.global_partitions == 0 and many.global_tables_in_hbm == 1
+    # ids must still fit 32 bits
+    assert tb.tensorbleu_workspace_bytes(1 << 16, 8, 8192, 8192, cfg) == 0
 
 
 def test_lengths_from_padding():
