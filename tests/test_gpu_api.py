@@ -112,6 +112,32 @@ def test_hip_graph_capture_and_replay(path):
         np.testing.assert_array_equal(out.cpu().numpy(), eager.cpu().numpy())
 
 
+def test_hip_graph_replay_of_the_partitioned_kernels():
+    """A long group (several launches: zero fill, partitioned dictionary per key kind, count/clip,
+    finalize) captured and replayed with fresh inputs."""
+    V = 200000                                        # 18 bits: the 4-grams take the derived keys
+    ws = [syn.random_small(s, B=3, R=1, vocab=V, max_len=7000, min_len=6500) for s in (411, 412)]
+    scorer = tb.BleuScorer(3, 1, ws[0].cand.shape[1], ws[0].refs.shape[2], vocab_size=V,
+                           smoothing="exp", path="auto", device=DEV)
+    lay = tb.tensorbleu_workspace_layout(3, 1, ws[0].cand.shape[1], ws[0].refs.shape[2], scorer.cfg)
+    assert lay.global_partitions == 4
+    cand, cl = dev(ws[0].cand), dev(ws[0].cand_len)
+    refs, rl = dev(ws[0].refs), dev(ws[0].ref_len)
+    scorer(cand, cl, refs, rl)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = scorer(cand, cl, refs, rl)
+    for rep, w in enumerate([ws[0], ws[1], ws[0]]):
+        cand.copy_(dev(w.cand)); cl.copy_(dev(w.cand_len))
+        refs.copy_(dev(w.refs)); rl.copy_(dev(w.ref_len))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+        assert np.abs(out.cpu().numpy() - ref.bleu).max() <= 1e-5, rep
+
+
 def test_scorer_accepts_reference_counts():
     w = syn.random_small(61, B=20, R=3, vocab=30, max_len=50)
     rc = syn.ref_counts(61, w.B, w.R)
