@@ -208,6 +208,9 @@ def main():
                     help="also time ROUGE-N (tensorrouge_n, order N) on the same batch")
     ap.add_argument("--int64", action="store_true",
                     help="feed int64 token ids (the usual tokenizer dtype) instead of int32")
+    ap.add_argument("--long-form", type=int, default=0, metavar="L",
+                    help="instead of a BASELINE configuration: 128 candidates of about L tokens "
+                         "with one reference each (groups beyond one LDS table for L > 6144)")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short measurements of the other BASELINE configurations")
     ap.add_argument("--no-global-passes", action="store_true",
@@ -242,7 +245,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    w = syn.make(a.config)
+    w = syn.long_form(L=a.long_form) if a.long_form else syn.make(a.config)
     run = [r for r in w.runs if not r.corpus][-1]
     N = w.max_n
     to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
@@ -359,7 +362,8 @@ def main():
                            "sentences_per_s": round(w.B / (r_ms * 1e-3), 1),
                            "frac_hbm": round(alg["fused"] / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
     if not a.no_other_configs:
-        result["other_configs"] = other_configs(a.config, min(a.steps, 100), torch, tb, syn, np, dev)
+        result["other_configs"] = other_configs(0 if a.long_form else a.config, min(a.steps, 100),
+                                                torch, tb, syn, np, dev)
     if not a.no_hbm_ceiling:
         result["achievable_hbm_GBps"] = achievable_hbm(torch, dev)
     if not a.no_cpu_baseline:

@@ -104,7 +104,9 @@ typedef struct tb_stats {
   int32_t* closest_ref_len; /* [B] reference length closest to the candidate's (shorter on ties) */
   int32_t* group_distinct;  /* [B, N] size of the group's dictionary: distinct n-grams over the
                                candidate and its references (GLOBAL path only; FUSED writes the
-                               candidate's distinct count, its dictionary holds candidates only) */
+                               candidate's distinct count, its dictionary holds candidates only).
+                               Written by the dictionary pass; with global_partitions > 0 by the
+                               count/clip pass, which sums the partitions' sizes */
   int64_t* corpus_stats;    /* [2N+2] clipped_1..N, total_1..N, sum of candidate lengths, sum of
                                closest reference lengths (Section 3.4, corpus variant) */
   int32_t* device_status;   /* [1] OR of TB_DEV_* bits; cleared by the caller */

@@ -242,10 +242,9 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
         ginv[k] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
     }
   }
-  if (tid == 0) {
+  // (the group's dictionary size, the sum over the partitions, is formed by the count pass)
+  if (tid == 0)
     a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
-    atomicAdd(&a.st.distinct[int64_t(g) * pb.N + n - 1], distinct);
-  }
 }
 
 // Count and clip the ids of one partition of one (group, order): one 16-bit LDS field per
@@ -319,7 +318,14 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const int clipped = block_sum(part, red_scratch);
   if (tid == 0) {
     if (clipped) atomicAdd(&a.st.clipped[int64_t(g) * pb.N + n - 1], clipped);
-    if (p == 0) a.st.total[int64_t(g) * pb.N + n - 1] = ccnt;
+    if (p == 0) {
+      a.st.total[int64_t(g) * pb.N + n - 1] = ccnt;
+      const int32_t* sizes =
+          a.part_distinct + (int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts);
+      int group_distinct = 0;
+      for (int q = 0; q < (1 << a.log2_parts); ++q) group_distinct += sizes[q];
+      a.st.distinct[int64_t(g) * pb.N + n - 1] = group_distinct;
+    }
   }
 }
 
@@ -369,9 +375,7 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s) {
-  hipError_t e = zero_ints(st.distinct, int64_t(pb.B) * pb.N, s);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
   if (e != hipSuccess) return e;
   // one launch for the orders with 8-byte packed keys, then one per order with 16-byte keys in

@@ -281,6 +281,28 @@ def random_small(seed: int, B: int, R: int, vocab: int, max_len: int, min_len: i
     return Workload(f"small_s{seed}_B{B}_R{R}_V{vocab}", vocab, cand, cl, refs, rl)
 
 
+def long_form(B: int = 128, L: int = 8192, vocab: int = 50257) -> Workload:
+    """Long generations (the paper's Section 6 names them as a direction): B candidates of about
+    L tokens with one reference each, Zipf(1.1) tokens, the reference a 0.3-substitution of the
+    candidate's base text with its own length in [0.9 L, L].  Groups of ~2 L tokens: beyond one
+    LDS table for L > 6144."""
+    seed = 0x7B1E0100 + L
+    smp = TokenSampler(vocab, 1.1)
+    cand = np.zeros((B, L), dtype=np.int32)
+    refs = np.zeros((B, 1, L), dtype=np.int32)
+    cl = np.zeros(B, dtype=np.int32)
+    rl = np.zeros((B, 1), dtype=np.int32)
+    lo = (9 * L) // 10
+    for i in range(B):
+        ul = uniforms(seed, i, _S_LEN, 2)
+        lc = lo + min(int(ul[0] * (L - lo + 1)), L - lo)
+        lr = lo + min(int(ul[1] * (L - lo + 1)), L - lo)
+        base = smp.draw(uniforms(seed, i, _S_BASE, L))
+        cand[i, :lc], cl[i] = _substitute(base[:lc], 0.3, smp, seed, i, 1), lc
+        refs[i, 0, :lr], rl[i, 0] = _substitute(base[:lr], 0.3, smp, seed, i, 2), lr
+    return Workload(f"long_B{B}_L{L}_R1_V{vocab}", vocab, cand, cl, refs, rl, runs=[Run("exp")])
+
+
 def ref_counts(seed: int, B: int, R: int) -> np.ndarray:
     """Per-candidate number of references in use, uniform in 1..R (for ragged reference counts)."""
     u = uniforms(seed, 0, 15, B)

@@ -252,6 +252,16 @@ def test_long_form_sequences_of_300k_tokens():
     check(w, syn.Run("add-k", 1.0), "global")
 
 
+def test_long_form_workload_at_full_size():
+    """The long-generation workload bench.py --long-form times (128 groups of ~16 000 tokens, four
+    partitions per group and order), every sentence against the oracle."""
+    w = syn.long_form()
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.path == 2 and lay.global_partitions == 4
+    check(w, syn.Run("exp"), "auto")
+
+
 def test_determinism_of_integer_statistics():
     w = syn.make(1)
     d = Device(w)
