@@ -94,9 +94,9 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
       L.tables_off = off;
       off = align_up(off + size_t(B) * N * size_t(p->big.table_entries) * 8);
     }
-    if (p->use_part) {  // int32 [B, N, P]: dictionary size of every partition
+    if (p->use_part) {  // per partition: dictionary size, segment start; slots by partition
       L.tables_off = off;
-      off = align_up(off + ((size_t(B) * N) << p->part.log2_parts) * 4);
+      off = align_up(off + part_workspace_bytes(B, N, L.group_cap, p->part));
     }
   }
   L.bytes = off < kAlign ? kAlign : off;

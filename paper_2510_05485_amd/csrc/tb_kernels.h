@@ -60,10 +60,10 @@ struct BigPlan {
   int64_t slots;          // hash-table slots per (group, order): power of two >= 2 * group_cap
   int64_t table_entries;  // slots + padding, 8 bytes each
 };
-// Groups of up to 131 072 n-gram slots beyond the LDS plans: P workgroups per (group, order), each
+// Groups of up to 524 288 n-gram slots beyond the LDS plans: P workgroups per (group, order), each
 // with the dictionary entries / counters of one hash partition in LDS.
 struct PartPlan {
-  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 32
+  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 128
   int id_cap;         // ids a partition may hand out
   int words;          // count/clip: 32-bit counter words per id
   int64_t id_stride;  // id range per group: max(group_cap, P * id_cap)
@@ -71,6 +71,8 @@ struct PartPlan {
 };
 bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
                const int32_t* key_bytes, PartPlan* plan);
+// bytes the partitioned kernels need at GlobalWs::tables
+size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan& plan);
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s);
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,

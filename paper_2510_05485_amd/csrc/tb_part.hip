@@ -1,10 +1,11 @@
-// GLOBAL path for sentence groups of 12 289 .. 131 072 n-gram slots: too many for one LDS hash
+// GLOBAL path for sentence groups of 12 289 .. 524 288 n-gram slots: too many for one LDS hash
 // table, few enough that the table can be split.  The dictionary and count/clip passes
 // (paper Sections 3.2-3.3) run with P workgroups per (group, order); workgroup p owns the
-// n-grams whose key hashes into partition p.  Every workgroup streams all of the group's keys
-// (or ids), which costs P sequential reads of data that sits in cache, and keeps its share of the
-// dictionary (or of the counters) in LDS, where random access is cheap -- the same kernels with
-// the table in HBM are about ten times slower per n-gram.
+// n-grams whose key hashes into partition p and keeps its share of the dictionary (or of the
+// counters) in LDS, where random access is cheap -- the same kernels with the table in HBM are
+// several times slower per n-gram.  A scatter kernel first sorts each (group, order)'s slots by
+// partition (one workgroup each: histogram, prefix sums, scatter), so every key is hashed once
+// and the P workgroups read only their own members.
 //
 // Ids: partition p numbers its distinct n-grams 0, 1, ... and publishes them as p * id_cap + local,
 // so ids stay unique inside the group without any exchange between workgroups; they are no
@@ -30,7 +31,7 @@ constexpr int kPartSlots = 8192;     // 8-byte table entries: 64 KB of LDS
 constexpr int kPartIdCap = 6144;     // distinct n-grams a partition may hold (3/4 of its slots)
 constexpr int kPartTarget = 4096;    // expected distinct n-grams per partition at most
 constexpr int kPartUnroll = 8;       // loads in flight per thread while streaming
-constexpr int kPartChunk = 4096;     // keys gathered per round of the dictionary's first pass
+constexpr int kMaxParts = 128;       // partitions per (group, order): groups of up to 524 288 slots
 constexpr unsigned long long kFreeEntry = ~0ull;
 
 struct PartArgs {
@@ -38,6 +39,8 @@ struct PartArgs {
   GlobalWs ws;
   StatPtrs st;
   int32_t* part_distinct;  // [B, N, P] distinct n-grams per partition (dictionary -> count/clip)
+  int32_t* part_start;     // [B, N, P + 1] where each partition's members start in member_slot
+  uint32_t* member_slot;   // [N][B * group_cap] the slots of a (group, order), grouped by partition
   int log2_parts;          // P = 1 << log2_parts, P >= 2
   int orders[8];           // dictionary: the orders of this launch, and how many
   int num_orders;
@@ -87,58 +90,136 @@ __global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int64_t coun
   if (i < count) p[i] = 0;
 }
 
-// Dictionary of one partition of one (group, order).  Pass 1 inserts the partition's keys into
-// the LDS table and parks each occurrence's slot in the id array; the occupied entries are then
-// numbered; pass 2 replaces the parked slots by ids.
+// The 8-byte key of slot k of one (group, order): the packed n-gram, or for an order with 16-byte
+// packed keys (id of the (n-1)-gram at the same position, last token).  Construct in
+// wave-uniform control flow (it scans the group's lengths).
+struct KeySource {
+  const uint64_t* narrow_keys;
+  const Key128* wide_keys;
+  const uint32_t* prev_inv;
+  uint32_t prev_base;
+  uint64_t token_mask;
+  int bits, R, derived;
+  int end_lane;    // lane j: end of sequence j among the order's slots
+  int shift_lane;  // lane j: how far sequence j's slots of order n - 1 lie behind those of order n
+  int count;       // n-grams of this (group, order)
+
+  __device__ __forceinline__ KeySource(const PartArgs& a, int g, int n) {
+    const Problem& pb = a.pb;
+    GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
+    derived = a.derived;
+    shift_lane = 0;
+    if (derived) {
+      gi.set_order(n - 1);
+      shift_lane = gi.end_in_lane();
+    }
+    gi.set_order(n);
+    end_lane = gi.end_in_lane();
+    {
+      const int d = shift_lane - end_lane;  // lane j: start_{n-1}(j + 1) - start_n(j + 1)
+      shift_lane = __shfl_up(d, 1, kWave);
+      if ((threadIdx.x & (kWave - 1)) == 0) shift_lane = 0;
+    }
+    count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+    narrow_keys = reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+    wide_keys = reinterpret_cast<const Key128*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+    prev_inv = a.ws.inv[max(n - 2, 0)] + int64_t(g) * pb.group_cap;
+    prev_base = uint32_t(int64_t(g) * a.id_stride);
+    token_mask = (uint64_t(1) << pb.bits) - 1u;
+    bits = pb.bits;
+    R = pb.R;
+  }
+  // k < count
+  __device__ __forceinline__ uint64_t operator()(int k) const {
+    if (!derived) return narrow_keys[k];
+    int shift = 0;  // of the sequence that slot k belongs to
+    for (int j = 0; j < R; ++j) {
+      const bool past = k >= __builtin_amdgcn_readlane(end_lane, j);
+      shift = past ? __builtin_amdgcn_readlane(shift_lane, j + 1) : shift;
+    }
+    const uint64_t prefix = prev_inv[k + shift] - prev_base;
+    return (prefix << bits) | (wide_keys[k].lo & token_mask);
+  }
+};
+
+__device__ __forceinline__ int partition_of_key(uint64_t key, int log2_parts) {
+  // the all-ones key (the table's empty marker) lives in partition 0
+  return key == kFreeEntry ? 0 : part_of(part_hash(key), log2_parts);
+}
+
+// One workgroup per (group, order) of the launch sorts the order's slots by partition: a
+// histogram over the keys' partitions, its prefix sums (published as part_start), then every slot
+// is written to its partition's segment of member_slot.  Each key is hashed here and nowhere
+// else; the P dictionary workgroups read only their own members.
+__global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) {
+  __shared__ int hist[kMaxParts], cursor[kMaxParts];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int g = int(blockIdx.x) / a.num_orders, n = a.orders[int(blockIdx.x) % a.num_orders];
+  const int parts = 1 << a.log2_parts;
+  const KeySource key_of(a, g, n);
+  const int count = key_of.count;
+  uint32_t* members = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
+  int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
+  if (tid < kMaxParts) hist[tid] = 0;
+  __syncthreads();
+  for (int base = 0; base < count; base += kPartUnroll * nt) {
+    uint64_t key[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, count - 1));
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u)
+      if (base + u * nt + tid < count) atomicAdd(&hist[partition_of_key(key[u], a.log2_parts)], 1);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int q = 0; q < parts; ++q) {
+      cursor[q] = run;
+      start[q] = run;
+      run += hist[q];
+    }
+    start[parts] = run;
+  }
+  __syncthreads();
+  for (int base = 0; base < count; base += kPartUnroll * nt) {
+    uint64_t key[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, count - 1));
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int k = base + u * nt + tid;
+      if (k < count)
+        members[atomicAdd(&cursor[partition_of_key(key[u], a.log2_parts)], 1)] = uint32_t(k);
+    }
+  }
+}
+
+// Dictionary of one partition of one (group, order): its members' keys are inserted into the LDS
+// table and each occurrence's slot in the table is parked in the id array; the occupied entries
+// are then numbered; a second walk over the members replaces the parked slots by ids.
 __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int scan_scratch[17];
-  __shared__ int list_count;
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
   const Role me = role_of_block(a, a.orders, a.num_orders);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
+  const int parts = 1 << a.log2_parts;
   constexpr int T = kPartSlots;
   constexpr uint32_t mask = uint32_t(T) - 1u;
   constexpr int shift = 32 - 13;  // log2(kPartSlots) = 13
   static_assert((1 << 13) == kPartSlots, "table_shift");
   unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
-  GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
-  // derived keys: lane j holds how far sequence j's slots of order n - 1 lie behind its slots
-  // of order n (every earlier sequence has up to one (n-1)-gram more), and the end of sequence j
-  int shift_lane = 0;
-  if (a.derived) {
-    gi.set_order(n - 1);
-    shift_lane = gi.end_in_lane();
-  }
-  gi.set_order(n);
-  const int end_lane = gi.end_in_lane();
-  {
-    const int d = shift_lane - end_lane;  // lane j: start_{n-1}(j + 1) - start_n(j + 1)
-    shift_lane = __shfl_up(d, 1, kWave);
-    if ((tid & (kWave - 1)) == 0) shift_lane = 0;
-  }
-  const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
-  const uint64_t* narrow_keys =
-      reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
-  const Key128* wide_keys =
-      reinterpret_cast<const Key128*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
-  const uint32_t* prev_inv = a.ws.inv[max(n - 2, 0)] + int64_t(g) * pb.group_cap;
-  const uint32_t prev_base = uint32_t(int64_t(g) * a.id_stride);
-  const uint64_t token_mask = (uint64_t(1) << pb.bits) - 1u;
-  // the key of slot k (k < count) of this (group, order)
-  auto load_key = [&](int k) -> uint64_t {
-    if (!a.derived) return narrow_keys[k];
-    int shift = 0;  // of the sequence that slot k belongs to
-    for (int j = 0; j < pb.R; ++j) {
-      const bool past = k >= __builtin_amdgcn_readlane(end_lane, j);
-      shift = past ? __builtin_amdgcn_readlane(shift_lane, j + 1) : shift;
-    }
-    const uint64_t prefix = prev_inv[k + shift] - prev_base;
-    return (prefix << pb.bits) | (wide_keys[k].lo & token_mask);
-  };
+  const KeySource key_of(a, g, n);
+  const int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
+  const int first = min(max(start[p], 0), key_of.count);
+  const int members = min(max(start[p + 1] - first, 0), key_of.count - first);
+  const uint32_t* member =
+      a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
+  const uint32_t last_slot = uint32_t(max(key_of.count - 1, 0));
 
   {  // T + 1 entries (entry T belongs to the all-ones key), 16 bytes per store
     uint4* t4 = reinterpret_cast<uint4*>(table);
@@ -147,67 +228,35 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   }
   __syncthreads();
 
-  // Pass 1 in chunks of kPartChunk keys.  Only one key in P belongs to this partition, so the
-  // members of a chunk are first gathered (their position in the chunk, 16 bits) into an LDS
-  // list and then inserted by full wavefronts; inserting where they stand would leave P - 1 of
-  // P lanes idle in every probe loop.
-  // Which slots are members is also kept, one bit per slot (the ballot of a wavefront's 64
-  // consecutive slots is the 64-bit word): pass 2 then needs neither the keys nor their hashes.
-  uint16_t* list = reinterpret_cast<uint16_t*>(smem + size_t(T + 2) * 8);
-  unsigned long long* member_bits =
-      reinterpret_cast<unsigned long long*>(smem + size_t(T + 2) * 8 + size_t(kPartChunk) * 2);
   bool lost = false;  // a probe sequence ran through the whole table
-  const int lane = tid & (kWave - 1);
-  if (tid == 0) list_count = 0;
-  for (int chunk = 0; chunk < count; chunk += kPartChunk) {
-    __syncthreads();  // the counter is zero and the previous chunk's list has been consumed
-    {
-      uint64_t key[kPartChunk / kPartThreads];
+  for (int base = 0; base < members; base += kPartUnroll * nt) {
+    uint32_t k[kPartUnroll];
+    uint64_t key[kPartUnroll];
 #pragma unroll
-      for (int u = 0; u < kPartChunk / kPartThreads; ++u)
-        key[u] = load_key(min(chunk + u * nt + tid, count - 1));
+    for (int u = 0; u < kPartUnroll; ++u)
+      k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
 #pragma unroll
-      for (int u = 0; u < kPartChunk / kPartThreads; ++u) {
-        const int k = chunk + u * nt + tid;
-        const bool member =
-            k < count && (key[u] == kFreeEntry ? p == 0
-                                               : part_of(part_hash(key[u]), a.log2_parts) == p);
-        const unsigned long long m = __builtin_amdgcn_ballot_w64(member);
-        int first = 0;
-        if (lane == 0) {
-          if (k < count) member_bits[k >> 6] = m;  // k is a multiple of 64 in lane 0
-          if (m) first = atomicAdd(&list_count, __popcll(m));
-        }
-        first = __builtin_amdgcn_readfirstlane(first);
-        const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
-            uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), 0u));
-        if (member) list[first + int(rank)] = uint16_t(k - chunk);
-      }
-    }
-    __syncthreads();
-    const int members = list_count;
-    __syncthreads();  // every thread has the count: the counter may be reset for the next chunk
-    if (tid == 0) list_count = 0;
-    for (int e = tid; e < members; e += nt) {
-      const int k = chunk + int(list[e]);
-      const uint64_t key = load_key(k);
-      if (key == kFreeEntry) {  // the all-ones key lives in partition 0, entry T
+    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(int(k[u]));
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      if (base + u * nt + tid >= members) continue;
+      if (key[u] == kFreeEntry) {
         atomicCAS(&table[T], kFreeEntry, 0ull);
-        ginv[k] = uint32_t(T);
+        ginv[k[u]] = uint32_t(T);
         continue;
       }
-      const uint32_t h = part_hash(key);
+      const uint32_t h = part_hash(key[u]);
       const uint32_t step = (h >> 3) | 1u;
       uint32_t s = h >> shift;
-      unsigned long long old = atomicCAS(&table[s], kFreeEntry, key);
+      unsigned long long old = atomicCAS(&table[s], kFreeEntry, key[u]);
       int rounds = 0;
-      while (int(old != kFreeEntry) & int(old != key) & int(rounds < T)) {
+      while (int(old != kFreeEntry) & int(old != key[u]) & int(rounds < T)) {
         s = (s + step) & mask;
-        old = atomicCAS(&table[s], kFreeEntry, key);
+        old = atomicCAS(&table[s], kFreeEntry, key[u]);
         ++rounds;
       }
-      lost |= (old != kFreeEntry && old != key);
-      ginv[k] = s;
+      lost |= (old != kFreeEntry && old != key[u]);
+      ginv[k[u]] = s;
     }
   }
   __syncthreads();
@@ -230,17 +279,17 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
 
   const uint32_t id_base =
       uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
-  for (int base = 0; base < count; base += kPartUnroll * nt) {
-    uint32_t parked[kPartUnroll];
+  for (int base = 0; base < members; base += kPartUnroll * nt) {
+    uint32_t k[kPartUnroll], parked[kPartUnroll];
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) parked[u] = ginv[min(base + u * nt + tid, count - 1)];
+    for (int u = 0; u < kPartUnroll; ++u)
+      k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) {
-      const int k = base + u * nt + tid;
-      if (k >= count) continue;
-      if ((member_bits[k >> 6] >> (k & 63)) & 1ull)
-        ginv[k] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
-    }
+    for (int u = 0; u < kPartUnroll; ++u) parked[u] = ginv[k[u]];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u)
+      if (base + u * nt + tid < members)
+        ginv[k[u]] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
   }
   // (the group's dictionary size, the sum over the partitions, is formed by the count pass)
   if (tid == 0)
@@ -248,7 +297,7 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
 }
 
 // Count and clip the ids of one partition of one (group, order): one 16-bit LDS field per
-// (id, sequence) as in the LDS count kernel, filled while streaming all of the group's ids; then
+// (id, sequence) as in the LDS count kernel, filled from the partition's members; then
 // a sweep over the partition's entries takes the maximum over the reference fields and the
 // minimum with the candidate field.
 __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
@@ -280,24 +329,28 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   }
   __syncthreads();
 
-  // a wavefront takes 64 consecutive slots at a time; their sequence (the number of sequences
-  // ending at or before the slot) is one scalar when the block lies inside one sequence
-  const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
-  for (int base = 0; base < count; base += kPartUnroll * nt) {
-    uint32_t id[kPartUnroll];
+  // the partition's members (their slots, gathered by the dictionary pass) are exactly the
+  // n-grams whose ids lie in this partition's id range; the sequence of a slot is the number of
+  // sequences that end at or before it
+  const int parts = 1 << a.log2_parts;
+  const int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
+  const int first = min(max(start[p], 0), count);
+  const int members = min(max(start[p + 1] - first, 0), count - first);
+  const uint32_t* member = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
+  const uint32_t last_slot = uint32_t(max(count - 1, 0));
+  for (int base = 0; base < members; base += kPartUnroll * nt) {
+    uint32_t k[kPartUnroll], id[kPartUnroll];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
-      id[u] = ginv[min(base + u * nt + tid, count - 1)] - id_base;
+      k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) id[u] = ginv[k[u]] - id_base;
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
-      const int k0 = base + u * nt + wave_first;
-      if (k0 >= count) break;
-      const int k = k0 + lane;
-      const int f0 = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0));
-      const int f1 = __popcll(__builtin_amdgcn_ballot_w64(seq_end <= k0 + kWave - 1));
-      int f = f0;
-      for (int j = f0; j < f1; ++j) f += (k >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
-      if (k < count && f <= pb.R && id[u] < uint32_t(U))
+      int f = 0;
+      for (int j = 0; j < pb.R; ++j)
+        f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
+      if (base + u * nt + tid < members && id[u] < uint32_t(U))
         atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
                   (f & 1) ? 0x10000u : 1u);
     }
@@ -329,13 +382,28 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   }
 }
 
+// The partitioned kernels' share of the workspace: int32 [B, N, P] dictionary sizes, int32
+// [B, N, P + 1] segment starts, uint32 [N][B * group_cap] slots grouped by partition; each part
+// rounded up to 256 bytes.
+size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
+size_t sizes_bytes(int64_t B, int N, int log2_parts) {
+  return round256(((size_t(B) * N) << log2_parts) * 4);
+}
+size_t starts_bytes(int64_t B, int N, int log2_parts) {
+  return round256(size_t(B) * N * ((size_t(1) << log2_parts) + 1) * 4);
+}
+
 PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                    const StatPtrs& st) {
   PartArgs a;
   a.pb = pb;
   a.ws = ws;
   a.st = st;
-  a.part_distinct = static_cast<int32_t*>(ws.tables);
+  unsigned char* base = static_cast<unsigned char*>(ws.tables);
+  a.part_distinct = reinterpret_cast<int32_t*>(base);
+  a.part_start = reinterpret_cast<int32_t*>(base + sizes_bytes(pb.B, pb.N, plan.log2_parts));
+  a.member_slot = reinterpret_cast<uint32_t*>(base + sizes_bytes(pb.B, pb.N, plan.log2_parts) +
+                                              starts_bytes(pb.B, pb.N, plan.log2_parts));
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
   a.id_stride = plan.id_stride;
@@ -354,21 +422,24 @@ hipError_t zero_ints(int32_t* p, int64_t count, hipStream_t s) {
 
 }  // namespace
 
+size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan& plan) {
+  return sizes_bytes(B, N, plan.log2_parts) + starts_bytes(B, N, plan.log2_parts) +
+         round256(size_t(B) * size_t(group_cap) * N * 4);
+}
+
 bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
                const int32_t* key_bytes, PartPlan* plan) {
   (void)key_bytes;  // orders with 16-byte keys are keyed by (prefix id, last token) instead
   if (R >= kWave - 1 || cand_stride > 65535 || ref_stride > 65535) return false;
   int lg = 1;
   while ((int64_t(kPartTarget) << lg) < group_cap) ++lg;
-  if (lg > 5) return false;  // more than 32 partitions: the streaming reads stop paying
+  if ((1 << lg) > kMaxParts) return false;
   plan->log2_parts = lg;
   plan->id_cap = kPartIdCap;
   plan->words = (R + 2) / 2;
   plan->id_stride = group_cap;
   if ((int64_t(kPartIdCap) << lg) > plan->id_stride) plan->id_stride = int64_t(kPartIdCap) << lg;
-  // table, member list of a chunk, one membership bit per slot of the group
-  plan->dict_lds = size_t(kPartSlots + 2) * 8 + size_t(kPartChunk) * 2 +
-                   size_t((group_cap + 63) / 64) * 8;
+  plan->dict_lds = size_t(kPartSlots + 2) * 8;
   plan->count_lds = (size_t(kPartIdCap) * plan->words * 4 + 15) & ~size_t(15);
   return plan->count_lds + 256 <= size_t(kLdsBudget);
 }
@@ -387,6 +458,10 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
     if (a.num_orders) {
       const int64_t blocks = part_grid(pb, plan, a.num_orders);
       if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+      hipLaunchKernelGGL(part_scatter_kernel, dim3(uint32_t(int64_t(pb.B) * a.num_orders)),
+                         dim3(kPartThreads), 0, s, a);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
       hipLaunchKernelGGL(part_dictionary_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
                          plan.dict_lds, s, a);
       e = hipGetLastError();

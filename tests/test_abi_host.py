@@ -103,7 +103,8 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
 def test_group_too_large_for_lds_falls_back_to_tables_in_the_workspace(lib):
     cfg = tb.make_config(vocab_size=50257, path="global")
     lay = binding.tb_layout_t()
-    # 17 * 8192 slots: beyond the single-table kernels (12 288) and the partitioned ones (131 072)
+    # 17 sequences: beyond the single-table kernels (12 288 slots) and, with more than 11
+    # references, not for the partitioned ones either
     rc = lib.tensorbleu_workspace_layout(2, 16, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
     assert rc == 0 and lay.global_ok == 1 and lay.global_tables_in_hbm == 1
     assert lay.global_partitions == 0 and lay.id_stride == lay.group_cap
@@ -127,6 +128,11 @@ def test_partitioned_layout_between_the_lds_kernels_and_the_workspace_tables(lib
     # more references than the partitioned count kernel has LDS for: tables in the workspace
     many = tb.tensorbleu_workspace_layout(2, 12, 2048, 2048, cfg)
     assert many.global_partitions == 0 and many.global_tables_in_hbm == 1
+    # 128 partitions at most: 9 * 65 535 slots would need more
+    far = tb.tensorbleu_workspace_layout(1, 8, 65535, 65535, cfg)
+    assert far.global_partitions == 0 and far.global_tables_in_hbm == 1
+    wide = tb.tensorbleu_workspace_layout(1, 7, 65535, 65535, cfg)     # 524 280 slots
+    assert wide.global_partitions == 128
     # ids must still fit 32 bits
     assert tb.tensorbleu_workspace_bytes(1 << 16, 8, 8192, 8192, cfg) == 0
 

@@ -252,6 +252,18 @@ def test_long_form_sequences_of_300k_tokens():
     check(w, syn.Run("add-k", 1.0), "global")
 
 
+def test_sixty_four_partitions():
+    # groups of ~150 000 slots: 64 workgroups per (group, order); the second case has 72-bit
+    # 4-grams, keyed by (id of the 3-gram prefix, last token)
+    w = cached_small(147, B=2, R=3, vocab=3000, max_len=40000, min_len=35000)
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_partitions == 64 and lay.global_tables_in_hbm == 0
+    check(w, syn.Run("exp"), "auto")
+    w = cached_small(148, B=1, R=2, vocab=200000, max_len=50000, min_len=45000)
+    check(w, syn.Run("add-k", 1.0), "auto")
+
+
 def test_long_form_workload_at_full_size():
     """The long-generation workload bench.py --long-form times (128 groups of ~16 000 tokens, four
     partitions per group and order), every sentence against the oracle."""
