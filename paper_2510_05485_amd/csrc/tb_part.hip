@@ -45,7 +45,8 @@ struct PartArgs {
   int orders[8];           // dictionary: the orders of this launch, and how many
   int num_orders;
   int derived;             // dictionary: 1 if this launch's orders use (prefix id, last token) keys
-  int words;               // count/clip: 32-bit counter words per id (two 16-bit fields each)
+  int words;               // count/clip: 32-bit counter words per id
+  int fields_per_word;     // 2: 16-bit counters (sequences of at most 65 535 tokens); 1: 32-bit
   int64_t id_stride;       // ids of group g lie in [g * id_stride, (g + 1) * id_stride)
 };
 
@@ -350,9 +351,13 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
       int f = 0;
       for (int j = 0; j < pb.R; ++j)
         f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
-      if (base + u * nt + tid < members && id[u] < uint32_t(U))
-        atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
-                  (f & 1) ? 0x10000u : 1u);
+      if (base + u * nt + tid < members && id[u] < uint32_t(U)) {
+        if (a.fields_per_word == 2)
+          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
+                    (f & 1) ? 0x10000u : 1u);
+        else
+          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f)], 1u);
+      }
     }
   }
   __syncthreads();
@@ -361,12 +366,18 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   for (int u = tid; u < U; u += nt) {
     const uint32_t* e = &cnt[__umul24(uint32_t(u), uint32_t(W))];
     const uint32_t w0 = e[0];
-    uint32_t m = w0 >> 16;
-    for (int q = 1; q < W; ++q) {
-      const uint32_t w = e[q];
-      m = max(m, max(w & 0xFFFFu, w >> 16));
+    if (a.fields_per_word == 2) {
+      uint32_t m = w0 >> 16;
+      for (int q = 1; q < W; ++q) {
+        const uint32_t w = e[q];
+        m = max(m, max(w & 0xFFFFu, w >> 16));
+      }
+      part += int(min(w0 & 0xFFFFu, m));
+    } else {  // word 0: candidate, word 1 + j: reference j
+      uint32_t m = 0;
+      for (int q = 1; q < W; ++q) m = max(m, e[q]);
+      part += int(min(w0, m));
     }
-    part += int(min(w0 & 0xFFFFu, m));
   }
   const int clipped = block_sum(part, red_scratch);
   if (tid == 0) {
@@ -406,6 +417,7 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                               starts_bytes(pb.B, pb.N, plan.log2_parts));
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
+  a.fields_per_word = plan.fields_per_word;
   a.id_stride = plan.id_stride;
   for (int k = 0; k < 8; ++k) a.orders[k] = 0;
   a.num_orders = 0;
@@ -430,13 +442,15 @@ size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan&
 bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
                const int32_t* key_bytes, PartPlan* plan) {
   (void)key_bytes;  // orders with 16-byte keys are keyed by (prefix id, last token) instead
-  if (R >= kWave - 1 || cand_stride > 65535 || ref_stride > 65535) return false;
+  if (R >= kWave - 1) return false;
   int lg = 1;
   while ((int64_t(kPartTarget) << lg) < group_cap) ++lg;
   if ((1 << lg) > kMaxParts) return false;
   plan->log2_parts = lg;
   plan->id_cap = kPartIdCap;
-  plan->words = (R + 2) / 2;
+  // 16-bit counters while no sequence can hold an n-gram more than 65 535 times
+  plan->fields_per_word = (cand_stride > 65535 || ref_stride > 65535) ? 1 : 2;
+  plan->words = plan->fields_per_word == 2 ? (R + 2) / 2 : R + 1;
   plan->id_stride = group_cap;
   if ((int64_t(kPartIdCap) << lg) > plan->id_stride) plan->id_stride = int64_t(kPartIdCap) << lg;
   plan->dict_lds = size_t(kPartSlots + 2) * 8;

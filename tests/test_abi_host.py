@@ -133,6 +133,9 @@ def test_partitioned_layout_between_the_lds_kernels_and_the_workspace_tables(lib
     assert far.global_partitions == 0 and far.global_tables_in_hbm == 1
     wide = tb.tensorbleu_workspace_layout(1, 7, 65535, 65535, cfg)     # 524 280 slots
     assert wide.global_partitions == 128
+    # strides above 65 535 are fine there (32-bit counters)
+    long_rows = tb.tensorbleu_workspace_layout(2, 1, 100000, 100000, cfg)
+    assert long_rows.global_partitions == 64 and long_rows.global_tables_in_hbm == 0
     # ids must still fit 32 bits
     assert tb.tensorbleu_workspace_bytes(1 << 16, 8, 8192, 8192, cfg) == 0
 

@@ -264,6 +264,19 @@ def test_sixty_four_partitions():
     check(w, syn.Run("add-k", 1.0), "auto")
 
 
+def test_partitions_with_sequences_beyond_65535_tokens():
+    # 32-bit counters in the partitioned count kernel: with three tokens in the vocabulary single
+    # n-grams occur more than 65 535 times in a sequence of 100 000
+    w = cached_small(149, B=2, R=1, vocab=3, max_len=100000, min_len=90000)
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_partitions == 64 and lay.global_tables_in_hbm == 0
+    assert np.bincount(w.cand[0, :w.cand_len[0]]).max() > 20000
+    check(w, syn.Run("exp"), "auto")
+    w = cached_small(150, B=1, R=2, vocab=50257, max_len=70000, min_len=66000)
+    check(w, syn.Run("floor", 0.1), "auto")
+
+
 def test_long_form_workload_at_full_size():
     """The long-generation workload bench.py --long-form times (128 groups of ~16 000 tokens, four
     partitions per group and order), every sentence against the oracle."""
