@@ -29,8 +29,8 @@ namespace {
 constexpr int kPartThreads = 1024;
 constexpr int kPartSlots = 8192;     // 8-byte table entries: 64 KB of LDS
 constexpr int kPartIdCap = 6144;     // distinct n-grams a partition may hold (3/4 of its slots)
-constexpr int kPartTarget = 4096;    // expected distinct n-grams per partition at most
-constexpr int kPartUnroll = 8;       // loads in flight per thread while streaming
+constexpr int kPartTarget = 4096;    // P is chosen so that a partition expects at most this many slots
+constexpr int kPartUnroll = 8;       // loads in flight per thread
 constexpr int kMaxParts = 128;       // partitions per (group, order): groups of up to 524 288 slots
 constexpr unsigned long long kFreeEntry = ~0ull;
 
@@ -61,9 +61,9 @@ __device__ __forceinline__ int part_of(uint32_t h, int log2_parts) {
 }
 
 // Workgroup -> (group, order, partition).  Workgroups are handed to the eight XCDs in turn
-// (workgroup i runs on XCD i mod 8) and each XCD has its own L2, so the P workgroups that stream
-// the same keys are given indices that are equal mod 8: the keys then come from HBM once and
-// from that XCD's L2 the other P - 1 times.  g < 0: no work (the grid is rounded up).
+// (workgroup i runs on XCD i mod 8) and each XCD has its own L2, so the P workgroups of one
+// (group, order) are given indices that are equal mod 8: the keys, member lists and ids they
+// share then stay in that XCD's L2.  g < 0: no work (the grid is rounded up).
 constexpr int kXcds = 8;
 struct Role {
   int g, n, p;
