@@ -32,6 +32,7 @@ constexpr int kPartIdCap = 6144;     // distinct n-grams a partition may hold (3
 constexpr int kPartTarget = 4096;    // P is chosen so that a partition expects at most this many slots
 constexpr int kPartUnroll = 8;       // loads in flight per thread
 constexpr int kMaxParts = 128;       // partitions per (group, order): groups of up to 524 288 slots
+constexpr int kScatterChunk = 16384; // slots per workgroup of the chunked scatter
 constexpr unsigned long long kFreeEntry = ~0ull;
 
 struct PartArgs {
@@ -41,6 +42,10 @@ struct PartArgs {
   int32_t* part_distinct;  // [B, N, P] distinct n-grams per partition (dictionary -> count/clip)
   int32_t* part_start;     // [B, N, P + 1] where each partition's members start in member_slot
   uint32_t* member_slot;   // [N][B * group_cap] the slots of a (group, order), grouped by partition
+  uint64_t* member_key;    // [N][B * group_cap] their 8-byte keys, in the same order
+  uint32_t* member_id;     // [N][B * group_cap] their ids within the partition, same order
+  int32_t* chunk_hist;     // [B, N, chunks, P] chunked scatter: per-chunk partition histograms
+  int xcd_aware;           // block -> (group, order, partition): see role_of_block
   int log2_parts;          // P = 1 << log2_parts, P >= 2
   int orders[8];           // dictionary: the orders of this launch, and how many
   int num_orders;
@@ -72,17 +77,23 @@ struct Role {
 __device__ __forceinline__ Role role_of_block(const PartArgs& a, const int* orders,
                                               int num_orders) {
   const int parts = 1 << a.log2_parts;
-  const int xcd = int(blockIdx.x) % kXcds, j = int(blockIdx.x) / kXcds;
+  const int xcd = a.xcd_aware ? int(blockIdx.x) % kXcds : 0;
+  const int j = a.xcd_aware ? int(blockIdx.x) / kXcds : int(blockIdx.x);
   Role r;
   r.p = j & (parts - 1);
-  const int64_t gn = int64_t(j >> a.log2_parts) * kXcds + xcd;
+  const int64_t gn = int64_t(j >> a.log2_parts) * (a.xcd_aware ? kXcds : 1) + xcd;
   r.g = gn < int64_t(a.pb.B) * num_orders ? int(gn / num_orders) : -1;
   const int idx = int(gn % num_orders);
   r.n = orders ? orders[idx] : idx + 1;
   return r;
 }
+// Few (group, order)s: blocks in plain order, so that their partitions spread over all XCDs.
+__host__ inline bool part_xcd_aware(const Problem& pb, int num_orders) {
+  return int64_t(pb.B) * num_orders >= 8 * kXcds;
+}
 __host__ inline int64_t part_grid(const Problem& pb, const PartPlan& plan, int num_orders) {
   const int64_t gn = int64_t(pb.B) * num_orders;
+  if (!part_xcd_aware(pb, num_orders)) return gn << plan.log2_parts;
   return (((gn + kXcds - 1) / kXcds * kXcds)) << plan.log2_parts;
 }
 
@@ -161,6 +172,7 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
   const KeySource key_of(a, g, n);
   const int count = key_of.count;
   uint32_t* members = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
+  uint64_t* member_keys = a.member_key + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
   int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
   if (tid < kMaxParts) hist[tid] = 0;
   __syncthreads();
@@ -190,8 +202,95 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       const int k = base + u * nt + tid;
-      if (k < count)
-        members[atomicAdd(&cursor[partition_of_key(key[u], a.log2_parts)], 1)] = uint32_t(k);
+      if (k < count) {
+        const int at = atomicAdd(&cursor[partition_of_key(key[u], a.log2_parts)], 1);
+        members[at] = uint32_t(k);
+        member_keys[at] = key[u];
+      }
+    }
+  }
+}
+
+// The same in two kernels with one workgroup per 16 384 slots, for batches of few, very long
+// groups (one workgroup per (group, order) would leave most of the GPU idle): per-chunk
+// histograms, then the scatter, in which every workgroup derives its own cursors (and chunk 0
+// publishes part_start) from all the chunks' histograms of its (group, order).
+__global__ __launch_bounds__(kPartThreads) void part_chunk_hist_kernel(PartArgs a, int chunks) {
+  __shared__ int hist[kMaxParts];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int c = int(blockIdx.x) % chunks, gn = int(blockIdx.x) / chunks;
+  const int g = gn / a.num_orders, n = a.orders[gn % a.num_orders];
+  const int parts = 1 << a.log2_parts;
+  const KeySource key_of(a, g, n);
+  const int begin = min(c * kScatterChunk, key_of.count);
+  const int end = min(begin + kScatterChunk, key_of.count);
+  if (tid < kMaxParts) hist[tid] = 0;
+  __syncthreads();
+  for (int base = begin; base < end; base += kPartUnroll * nt) {
+    uint64_t key[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, end - 1));
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u)
+      if (base + u * nt + tid < end) atomicAdd(&hist[partition_of_key(key[u], a.log2_parts)], 1);
+  }
+  __syncthreads();
+  int32_t* out = a.chunk_hist + ((int64_t(g) * pb.N + n - 1) * chunks + c) * parts;
+  if (tid < parts) out[tid] = hist[tid];
+}
+
+__global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartArgs a,
+                                                                         int chunks) {
+  __shared__ int total[kMaxParts], before[kMaxParts], cursor[kMaxParts];
+  __shared__ int scan_scratch[17];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int c = int(blockIdx.x) % chunks, gn = int(blockIdx.x) / chunks;
+  const int g = gn / a.num_orders, n = a.orders[gn % a.num_orders];
+  const int parts = 1 << a.log2_parts;
+  const KeySource key_of(a, g, n);
+  const int begin = min(c * kScatterChunk, key_of.count);
+  const int end = min(begin + kScatterChunk, key_of.count);
+  uint32_t* members = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
+  uint64_t* member_keys = a.member_key + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
+  const int32_t* h = a.chunk_hist + (int64_t(g) * pb.N + n - 1) * chunks * parts;
+  int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
+
+  // partition q's segment starts at the sum of the smaller partitions' sizes; within it this
+  // chunk writes behind the chunks before it
+  if (tid < kMaxParts) total[tid] = before[tid] = 0;
+  __syncthreads();
+  for (int i = tid; i < chunks * parts; i += nt) {
+    const int v = h[i], q = i & (parts - 1);
+    atomicAdd(&total[q], v);
+    if ((i >> a.log2_parts) < c) atomicAdd(&before[q], v);
+  }
+  __syncthreads();
+  int all = 0;
+  const int first = block_exclusive_scan(tid < parts ? total[tid] : 0, scan_scratch, &all);
+  if (tid < parts) {
+    cursor[tid] = first + before[tid];
+    if (c == 0) start[tid] = first;
+  }
+  if (c == 0 && tid == 0) start[parts] = all;
+  __syncthreads();
+
+  const int last = max(key_of.count - 1, 0);
+  for (int base = begin; base < end; base += kPartUnroll * nt) {
+    uint64_t key[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, end - 1));
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int k = base + u * nt + tid;
+      if (k < end) {
+        // (clamped: the cursors come from memory)
+        const int at = min(
+            max(atomicAdd(&cursor[partition_of_key(key[u], a.log2_parts)], 1), 0), last);
+        members[at] = uint32_t(k);
+        member_keys[at] = key[u];
+      }
     }
   }
 }
@@ -214,13 +313,17 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   static_assert((1 << 13) == kPartSlots, "table_shift");
   unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
-  const KeySource key_of(a, g, n);
+  GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
+  gi.set_order(n);
+  const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
   const int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
-  const int first = min(max(start[p], 0), key_of.count);
-  const int members = min(max(start[p + 1] - first, 0), key_of.count - first);
-  const uint32_t* member =
-      a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
-  const uint32_t last_slot = uint32_t(max(key_of.count - 1, 0));
+  const int first = min(max(start[p], 0), count);
+  const int members = min(max(start[p + 1] - first, 0), count - first);
+  const int64_t list = (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
+  const uint32_t* member = a.member_slot + list;
+  const uint64_t* member_keys = a.member_key + list;
+  uint32_t* member_ids = a.member_id + list;  // first the table entry, then the id
+  const uint32_t last_slot = uint32_t(max(count - 1, 0));
 
   {  // T + 1 entries (entry T belongs to the all-ones key), 16 bytes per store
     uint4* t4 = reinterpret_cast<uint4*>(table);
@@ -231,19 +334,16 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
 
   bool lost = false;  // a probe sequence ran through the whole table
   for (int base = 0; base < members; base += kPartUnroll * nt) {
-    uint32_t k[kPartUnroll];
     uint64_t key[kPartUnroll];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
-      k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(int(k[u]));
+      key[u] = member_keys[min(base + u * nt + tid, members - 1)];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       if (base + u * nt + tid >= members) continue;
       if (key[u] == kFreeEntry) {
         atomicCAS(&table[T], kFreeEntry, 0ull);
-        ginv[k[u]] = uint32_t(T);
+        member_ids[base + u * nt + tid] = uint32_t(T);
         continue;
       }
       const uint32_t h = part_hash(key[u]);
@@ -257,7 +357,7 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
         ++rounds;
       }
       lost |= (old != kFreeEntry && old != key[u]);
-      ginv[k[u]] = s;
+      member_ids[base + u * nt + tid] = s;
     }
   }
   __syncthreads();
@@ -286,11 +386,15 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
     for (int u = 0; u < kPartUnroll; ++u)
       k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) parked[u] = ginv[k[u]];
+    for (int u = 0; u < kPartUnroll; ++u)
+      parked[u] = member_ids[min(base + u * nt + tid, members - 1)];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
-      if (base + u * nt + tid < members)
-        ginv[k[u]] = id_base + uint32_t(table[min(parked[u], uint32_t(T))]);
+      if (base + u * nt + tid < members) {
+        const uint32_t id = uint32_t(table[min(parked[u], uint32_t(T))]);
+        ginv[k[u]] = id_base + id;
+        member_ids[base + u * nt + tid] = id;
+      }
   }
   // (the group's dictionary size, the sum over the partitions, is formed by the count pass)
   if (tid == 0)
@@ -311,9 +415,6 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const int g = me.g, n = me.n, p = me.p;
   const int W = a.words;
   uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
-  const uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
-  const uint32_t id_base =
-      uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
   const int U = min(
       max(a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p], 0),
       kPartIdCap);
@@ -338,6 +439,8 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const int first = min(max(start[p], 0), count);
   const int members = min(max(start[p + 1] - first, 0), count - first);
   const uint32_t* member = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
+  const uint32_t* member_ids =
+      a.member_id + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
   const uint32_t last_slot = uint32_t(max(count - 1, 0));
   for (int base = 0; base < members; base += kPartUnroll * nt) {
     uint32_t k[kPartUnroll], id[kPartUnroll];
@@ -345,7 +448,8 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
     for (int u = 0; u < kPartUnroll; ++u)
       k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) id[u] = ginv[k[u]] - id_base;
+    for (int u = 0; u < kPartUnroll; ++u)
+      id[u] = member_ids[min(base + u * nt + tid, members - 1)];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       int f = 0;
@@ -415,6 +519,12 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   a.part_start = reinterpret_cast<int32_t*>(base + sizes_bytes(pb.B, pb.N, plan.log2_parts));
   a.member_slot = reinterpret_cast<uint32_t*>(base + sizes_bytes(pb.B, pb.N, plan.log2_parts) +
                                               starts_bytes(pb.B, pb.N, plan.log2_parts));
+  const size_t slots4 = round256(size_t(pb.B) * size_t(pb.group_cap) * pb.N * 4);
+  unsigned char* after_slots = reinterpret_cast<unsigned char*>(a.member_slot) + slots4;
+  a.member_id = reinterpret_cast<uint32_t*>(after_slots);
+  a.member_key = reinterpret_cast<uint64_t*>(after_slots + slots4);
+  a.chunk_hist = reinterpret_cast<int32_t*>(after_slots + 3 * slots4);
+  a.xcd_aware = 1;
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
   a.fields_per_word = plan.fields_per_word;
@@ -435,8 +545,10 @@ hipError_t zero_ints(int32_t* p, int64_t count, hipStream_t s) {
 }  // namespace
 
 size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan& plan) {
+  const size_t chunks = size_t((group_cap + kScatterChunk - 1) / kScatterChunk);
   return sizes_bytes(B, N, plan.log2_parts) + starts_bytes(B, N, plan.log2_parts) +
-         round256(size_t(B) * size_t(group_cap) * N * 4);
+         4 * round256(size_t(B) * size_t(group_cap) * N * 4) +  // slots, ids, 8-byte keys
+         round256(((size_t(B) * N * chunks) << plan.log2_parts) * 4);
 }
 
 bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
@@ -470,10 +582,20 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
     if (!ws.wide[n - 1]) a.orders[a.num_orders++] = n;
   for (int next_wide = 1; next_wide <= pb.N + 1; ++next_wide) {
     if (a.num_orders) {
+      a.xcd_aware = part_xcd_aware(pb, a.num_orders) ? 1 : 0;
       const int64_t blocks = part_grid(pb, plan, a.num_orders);
       if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-      hipLaunchKernelGGL(part_scatter_kernel, dim3(uint32_t(int64_t(pb.B) * a.num_orders)),
-                         dim3(kPartThreads), 0, s, a);
+      const int64_t pairs = int64_t(pb.B) * a.num_orders;  // (group, order)s of this launch
+      const int chunks = int((pb.group_cap + kScatterChunk - 1) / kScatterChunk);
+      if (chunks > 1 && pairs < 256) {  // few long groups: one workgroup per 16 384 slots
+        hipLaunchKernelGGL(part_chunk_hist_kernel, dim3(uint32_t(pairs * chunks)),
+                           dim3(kPartThreads), 0, s, a, chunks);
+        hipLaunchKernelGGL(part_chunk_scatter_kernel, dim3(uint32_t(pairs * chunks)),
+                           dim3(kPartThreads), 0, s, a, chunks);
+      } else {
+        hipLaunchKernelGGL(part_scatter_kernel, dim3(uint32_t(pairs)), dim3(kPartThreads), 0, s,
+                           a);
+      }
       e = hipGetLastError();
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL(part_dictionary_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
@@ -491,7 +613,8 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
 
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s) {
-  const PartArgs a = make_args(pb, ws, plan, st);
+  PartArgs a = make_args(pb, ws, plan, st);
+  a.xcd_aware = part_xcd_aware(pb, pb.N) ? 1 : 0;
   const int64_t blocks = part_grid(pb, plan, pb.N);
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
