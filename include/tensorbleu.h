@@ -135,7 +135,9 @@ typedef struct tb_layout {
   int32_t global_tables_in_hbm; /* 1 if the group is too large for the LDS kernels: the GLOBAL
                               path then keeps its hash tables and counters at tables_off */
   size_t  tables_off;      /* ... or, with global_partitions > 0, int32 [B, N, P]: the dictionary
-                              size of every partition */
+                              size of every partition, followed by the partitioned kernels'
+                              private arrays (per order and slot: the n-grams sorted by
+                              partition as slot number, partition-local id and 8-byte key) */
   int64_t id_stride;       /* id range per group on the GLOBAL path: group_cap, or more when
                               global_partitions > 0 */
   int32_t global_partitions; /* P > 0: groups beyond the single-table LDS kernels (12 288 slots)

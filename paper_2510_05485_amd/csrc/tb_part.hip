@@ -159,6 +159,71 @@ __device__ __forceinline__ int partition_of_key(uint64_t key, int log2_parts) {
   return key == kFreeEntry ? 0 : part_of(part_hash(key), log2_parts);
 }
 
+// Writes the slots [begin, end) of one (group, order), with their keys, behind the partitions'
+// cursors (LDS, one per partition; advanced here).  The slots go through LDS in rounds of 4096,
+// sorted by partition there, so that each partition's share of a round is one contiguous run of
+// stores rather than one store per cache line.  Call from all threads of the workgroup.
+constexpr int kRound = 4096, kRoundUnroll = kRound / kPartThreads;
+struct ScatterLds {
+  uint64_t key[kRound];
+  uint32_t slot[kRound];  // slot number | partition << 24
+  int count[kMaxParts];   // of the round, per partition; zero between rounds
+  int first[kMaxParts];   // where the partition's run starts in the round's sorted order
+  int shift[kMaxParts];   // sorted position + shift = position in the partition's segment
+  int scan_scratch[17];
+};
+__device__ __forceinline__ void scatter_range(const PartArgs& a, const KeySource& key_of,
+                                              int begin, int end, int* cursor, ScatterLds& lds,
+                                              uint32_t* members, uint64_t* member_keys) {
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int parts = 1 << a.log2_parts;
+  const int last = max(key_of.count - 1, 0);
+  if (tid < kMaxParts) lds.count[tid] = 0;
+  __syncthreads();
+  for (int base = begin; base < end; base += kRound) {
+    uint64_t key[kRoundUnroll];
+    int where[kRoundUnroll];  // rank within the partition's run | partition << 16
+#pragma unroll
+    for (int u = 0; u < kRoundUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, end - 1));
+#pragma unroll
+    for (int u = 0; u < kRoundUnroll; ++u) {
+      const int q = partition_of_key(key[u], a.log2_parts);
+      where[u] = q << 16;
+      if (base + u * nt + tid < end) where[u] |= atomicAdd(&lds.count[q], 1);
+    }
+    __syncthreads();
+    int total = 0;
+    const int mine = tid < parts ? lds.count[tid] : 0;
+    const int run = block_exclusive_scan(mine, lds.scan_scratch, &total);
+    if (tid < parts) {
+      lds.first[tid] = run;
+      lds.shift[tid] = cursor[tid] - run;
+      cursor[tid] += mine;
+      lds.count[tid] = 0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kRoundUnroll; ++u) {
+      const int k = base + u * nt + tid;
+      if (k < end) {
+        const int q = where[u] >> 16;
+        const int pos = min(lds.first[q] + (where[u] & 0xFFFF), kRound - 1);
+        lds.key[pos] = key[u];
+        lds.slot[pos] = uint32_t(k) | (uint32_t(q) << 24);
+      }
+    }
+    __syncthreads();
+    const int in_round = min(kRound, end - base);
+    for (int i = tid; i < in_round; i += nt) {
+      const uint32_t v = lds.slot[i];
+      const int at = min(max(lds.shift[v >> 24] + i, 0), last);  // (clamped: see the callers)
+      members[at] = v & 0xFFFFFFu;
+      member_keys[at] = lds.key[i];
+    }
+    __syncthreads();
+  }
+}
+
 // One workgroup per (group, order) of the launch sorts the order's slots by partition: a
 // histogram over the keys' partitions, its prefix sums (published as part_start), then every slot
 // is written to its partition's segment of member_slot.  Each key is hashed here and nowhere
@@ -195,6 +260,7 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
     start[parts] = run;
   }
   __syncthreads();
+  // (a partition's share of a wave's stores is a run of neighbouring addresses already)
   for (int base = 0; base < count; base += kPartUnroll * nt) {
     uint64_t key[kPartUnroll];
 #pragma unroll
@@ -244,6 +310,7 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartAr
                                                                          int chunks) {
   __shared__ int total[kMaxParts], before[kMaxParts], cursor[kMaxParts];
   __shared__ int scan_scratch[17];
+  __shared__ ScatterLds lds;
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
   const int c = int(blockIdx.x) % chunks, gn = int(blockIdx.x) / chunks;
@@ -276,23 +343,7 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartAr
   if (c == 0 && tid == 0) start[parts] = all;
   __syncthreads();
 
-  const int last = max(key_of.count - 1, 0);
-  for (int base = begin; base < end; base += kPartUnroll * nt) {
-    uint64_t key[kPartUnroll];
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, end - 1));
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) {
-      const int k = base + u * nt + tid;
-      if (k < end) {
-        // (clamped: the cursors come from memory)
-        const int at = min(
-            max(atomicAdd(&cursor[partition_of_key(key[u], a.log2_parts)], 1), 0), last);
-        members[at] = uint32_t(k);
-        member_keys[at] = key[u];
-      }
-    }
-  }
+  scatter_range(a, key_of, begin, end, cursor, lds, members, member_keys);
 }
 
 // Dictionary of one partition of one (group, order): its members' keys are inserted into the LDS
