@@ -137,7 +137,8 @@ typedef struct tb_layout {
   size_t  tables_off;      /* ... or, with global_partitions > 0, int32 [B, N, P]: the dictionary
                               size of every partition, followed by the partitioned kernels'
                               private arrays (per order and slot: the n-grams sorted by
-                              partition as slot number, partition-local id and 8-byte key) */
+                              partition as slot number, partition-local id | sequence index << 16,
+                              and 8-byte key) */
   int64_t id_stride;       /* id range per group on the GLOBAL path: group_cap, or more when
                               global_partitions > 0 */
   int32_t global_partitions; /* P > 0: groups beyond the single-table LDS kernels (12 288 slots)

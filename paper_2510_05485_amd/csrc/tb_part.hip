@@ -347,13 +347,13 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartAr
 }
 
 // Dictionary of one partition of one (group, order): its members' keys are inserted into the LDS
-// table and each occurrence's slot in the table is parked in the id array; the occupied entries
-// are then numbered; a second walk over the members replaces the parked slots by ids.
+// table and each occurrence's table entry is remembered; the occupied entries are then numbered;
+// a second walk over the members turns the remembered entries into ids.
 __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int scan_scratch[17];
   const Problem& pb = a.pb;
-  const int nt = blockDim.x, tid = threadIdx.x;
+  const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
   const Role me = role_of_block(a, a.orders, a.num_orders);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
@@ -367,13 +367,19 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
   GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
   gi.set_order(n);
   const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+  const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
   const int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
   const int first = min(max(start[p], 0), count);
   const int members = min(max(start[p + 1] - first, 0), count - first);
   const int64_t list = (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
   const uint32_t* member = a.member_slot + list;
   const uint64_t* member_keys = a.member_key + list;
-  uint32_t* member_ids = a.member_id + list;  // first the table entry, then the id
+  // in the end: id within the partition | sequence within the group << 16; meanwhile the table
+  // entries of the members beyond the first 8192 (those of the first 8192 stay in registers)
+  uint32_t* member_ids = a.member_id + list;
+  uint32_t parked0[kPartUnroll];
+#pragma unroll
+  for (int u = 0; u < kPartUnroll; ++u) parked0[u] = 0;
   const uint32_t last_slot = uint32_t(max(count - 1, 0));
 
   {  // T + 1 entries (entry T belongs to the all-ones key), 16 bytes per store
@@ -394,7 +400,10 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
       if (base + u * nt + tid >= members) continue;
       if (key[u] == kFreeEntry) {
         atomicCAS(&table[T], kFreeEntry, 0ull);
-        member_ids[base + u * nt + tid] = uint32_t(T);
+        if (base == 0)
+          parked0[u] = uint32_t(T);
+        else
+          member_ids[base + u * nt + tid] = uint32_t(T);
         continue;
       }
       const uint32_t h = part_hash(key[u]);
@@ -408,7 +417,10 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
         ++rounds;
       }
       lost |= (old != kFreeEntry && old != key[u]);
-      member_ids[base + u * nt + tid] = s;
+      if (base == 0)
+        parked0[u] = s;
+      else
+        member_ids[base + u * nt + tid] = s;
     }
   }
   __syncthreads();
@@ -438,14 +450,18 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
       k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
-      parked[u] = member_ids[min(base + u * nt + tid, members - 1)];
+      parked[u] = base == 0 ? parked0[u] : member_ids[min(base + u * nt + tid, members - 1)];
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u)
+    for (int u = 0; u < kPartUnroll; ++u) {
+      int f = 0;  // the sequence of a slot: how many sequences end at or before it
+      for (int j = 0; j < pb.R; ++j)
+        f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
       if (base + u * nt + tid < members) {
         const uint32_t id = uint32_t(table[min(parked[u], uint32_t(T))]);
         ginv[k[u]] = id_base + id;
-        member_ids[base + u * nt + tid] = id;
+        member_ids[base + u * nt + tid] = id | (uint32_t(f) << 16);
       }
+    }
   }
   // (the group's dictionary size, the sum over the partitions, is formed by the count pass)
   if (tid == 0)
@@ -460,7 +476,7 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int red_scratch[17];
   const Problem& pb = a.pb;
-  const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int nt = blockDim.x, tid = threadIdx.x;
   const Role me = role_of_block(a, nullptr, a.pb.N);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
@@ -473,7 +489,6 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   gi.set_order(n);
   const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
   const int ccnt = gi.start(1);
-  const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
 
   {
     uint4* c4 = reinterpret_cast<uint4*>(cnt);
@@ -482,30 +497,23 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   }
   __syncthreads();
 
-  // the partition's members (their slots, gathered by the dictionary pass) are exactly the
-  // n-grams whose ids lie in this partition's id range; the sequence of a slot is the number of
-  // sequences that end at or before it
+  // the partition's members are exactly the n-grams whose ids lie in this partition's id range;
+  // the dictionary pass left each one's id within the partition and its sequence's index
   const int parts = 1 << a.log2_parts;
   const int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
   const int first = min(max(start[p], 0), count);
   const int members = min(max(start[p + 1] - first, 0), count - first);
-  const uint32_t* member = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
   const uint32_t* member_ids =
       a.member_id + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
-  const uint32_t last_slot = uint32_t(max(count - 1, 0));
   for (int base = 0; base < members; base += kPartUnroll * nt) {
-    uint32_t k[kPartUnroll], id[kPartUnroll];
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u)
-      k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
+    uint32_t id[kPartUnroll];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
       id[u] = member_ids[min(base + u * nt + tid, members - 1)];
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
-      int f = 0;
-      for (int j = 0; j < pb.R; ++j)
-        f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
+      const int f = min(int(id[u] >> 16), pb.R);
+      id[u] &= 0xFFFFu;
       if (base + u * nt + tid < members && id[u] < uint32_t(U)) {
         if (a.fields_per_word == 2)
           atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
