@@ -100,13 +100,18 @@ def test_staged_calls_equal_the_single_call_on_config1():
     assert abs(cout[0] - ref.corpus_bleu) <= 1e-5
 
 
-def test_partitioned_dictionary_ids_are_a_bijection_within_the_group():
+@pytest.mark.parametrize("seed,B,R,L,P", [
+    (205, 2, 2, 5000, 4),    # one scatter workgroup per (group, order)
+    (206, 1, 1, 12000, 8),   # few long groups: the scatter is split over chunks of 16 384 slots
+])
+def test_partitioned_dictionary_ids_are_a_bijection_within_the_group(seed, B, R, L, P):
     """Groups of 12 289 .. 65 536 slots: the dictionary is split over P workgroups and ids are
     p * 6144 + a number dense within partition p.  What is unique: equal n-gram <=> equal id, ids
     below id_stride, and the distinct count."""
-    w = syn.random_small(205, B=2, R=2, vocab=300, max_len=5000, min_len=4200)
+    w = syn.random_small(seed, B=B, R=R, vocab=300, max_len=L, min_len=L * 17 // 20)
     lay, wsb, stats, out = stage_all(w)
-    assert lay.global_partitions == 4 and lay.id_stride == 4 * 6144 and lay.global_tables_in_hbm == 0
+    assert lay.global_partitions == P and lay.id_stride == P * 6144
+    assert lay.global_tables_in_hbm == 0
     cap, stride = lay.group_cap, lay.id_stride
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
     for n in range(1, 5):
