@@ -81,9 +81,11 @@ __device__ __forceinline__ Role role_of_block(const PartArgs& a, const int* orde
   const int j = a.xcd_aware ? int(blockIdx.x) / kXcds : int(blockIdx.x);
   Role r;
   r.p = j & (parts - 1);
-  const int64_t gn = int64_t(j >> a.log2_parts) * (a.xcd_aware ? kXcds : 1) + xcd;
-  r.g = gn < int64_t(a.pb.B) * num_orders ? int(gn / num_orders) : -1;
-  const int idx = int(gn % num_orders);
+  // (32-bit: the grid, at least P times the number of pairs, fits an int)
+  const uint32_t gn = uint32_t(j >> a.log2_parts) * uint32_t(a.xcd_aware ? kXcds : 1) + xcd;
+  const uint32_t group = gn / uint32_t(num_orders);
+  r.g = int64_t(gn) < int64_t(a.pb.B) * num_orders ? int(group) : -1;
+  const int idx = int(gn - group * uint32_t(num_orders));
   r.n = orders ? orders[idx] : idx + 1;
   return r;
 }
