@@ -183,8 +183,15 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 
-hipError_t run_dictionary(const Call& c) {
-  if (c.plans.use_part) return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st, c.stream);
+// with_count: a whole call, where the partitioned dictionary kernel may take over the count/clip
+// pass (counts_in_dictionary says whether it does)
+bool counts_in_dictionary(const Call& c) {
+  return c.plans.use_part && c.plans.part.count_in_dictionary;
+}
+hipError_t run_dictionary(const Call& c, bool with_count) {
+  if (c.plans.use_part)
+    return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st,
+                                  with_count && counts_in_dictionary(c), c.stream);
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }
@@ -216,8 +223,8 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
     return TB_OK;
   }
   if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
-  if ((rc = hip_rc(run_dictionary(c))) != TB_OK) return rc;
-  if ((rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
+  if ((rc = hip_rc(run_dictionary(c, true))) != TB_OK) return rc;
+  if (!counts_in_dictionary(c) && (rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
   return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
                                 out_bleu, c.stream));
 }
@@ -305,7 +312,7 @@ int tensorbleu_dictionary(const int32_t* cand_len, const int32_t* ref_len, int64
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
-  return hip_rc(run_dictionary(c));
+  return hip_rc(run_dictionary(c, false));
 }
 
 int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,

@@ -69,13 +69,16 @@ struct PartPlan {
   int fields_per_word;  // 2: 16-bit counters, 1: 32-bit (a stride above 65 535)
   int64_t id_stride;  // id range per group: max(group_cap, P * id_cap)
   size_t dict_lds, count_lds;
+  int count_in_dictionary;  // the counter fields of a partition fit the dictionary table's LDS
 };
 bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N,
                const int32_t* key_bytes, PartPlan* plan);
 // bytes the partitioned kernels need at GlobalWs::tables
 size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan& plan);
+// with_count (only if plan.count_in_dictionary): the dictionary kernel also does the count/clip
+// pass's work, which is then not to be launched
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, hipStream_t s);
+                                  const StatPtrs& st, bool with_count, hipStream_t s);
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s);
 

@@ -46,6 +46,7 @@ struct PartArgs {
   uint32_t* member_id;     // [N][B * group_cap] their ids within the partition, same order
   int32_t* chunk_hist;     // [B, N, chunks, P] chunked scatter: per-chunk partition histograms
   int xcd_aware;           // block -> (group, order, partition): see role_of_block
+  int with_count;          // the dictionary kernel also counts and clips its partition
   int log2_parts;          // P = 1 << log2_parts, P >= 2
   int orders[8];           // dictionary: the orders of this launch, and how many
   int num_orders;
@@ -99,9 +100,13 @@ __host__ inline int64_t part_grid(const Problem& pb, const PartPlan& plan, int n
   return (((gn + kXcds - 1) / kXcds * kXcds)) << plan.log2_parts;
 }
 
-__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int64_t count) {
+// zeroes p[0 .. count) and, if q is not null, q[0 .. count)
+__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int32_t* q, int64_t count) {
   const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i < count) p[i] = 0;
+  if (i < count) {
+    p[i] = 0;
+    if (q) q[i] = 0;
+  }
 }
 
 // The 8-byte key of slot k of one (group, order): the packed n-gram, or for an order with 16-byte
@@ -348,10 +353,69 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartAr
   scatter_range(a, key_of, begin, end, cursor, lds, members, member_keys);
 }
 
+// Counts a partition's members into one counter field per (id, sequence) -- `cnt`, LDS, U * W
+// words, zeroed here -- and clips: returns this thread's share of the sum over the ids of
+// min(candidate count, largest reference count).  member_ids[i] is member i's (id within the
+// partition | index of its sequence << 16); with kFirstRoundInRegs, first_round[u] holds it for
+// member u * nt + tid.  Contains barriers: call from all threads, after everyone's last use of
+// what `cnt` overlays.
+template <bool kFirstRoundInRegs>
+__device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
+                                                    int fields_per_word, int R, int members,
+                                                    const uint32_t* member_ids,
+                                                    const uint32_t (&first_round)[kPartUnroll]) {
+  const int nt = blockDim.x, tid = threadIdx.x;
+  {
+    uint4* c4 = reinterpret_cast<uint4*>(cnt);
+    const int quads = (U * W + 3) / 4;
+    for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  __syncthreads();
+  for (int base = 0; base < members; base += kPartUnroll * nt) {
+    uint32_t id[kPartUnroll];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u)
+      id[u] = (kFirstRoundInRegs && base == 0)
+                  ? first_round[u]
+                  : member_ids[min(base + u * nt + tid, members - 1)];
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int f = min(int(id[u] >> 16), R);
+      id[u] &= 0xFFFFu;
+      if (base + u * nt + tid < members && id[u] < uint32_t(U)) {
+        if (fields_per_word == 2)
+          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
+                    (f & 1) ? 0x10000u : 1u);
+        else
+          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f)], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  int part = 0;
+  for (int u = tid; u < U; u += nt) {
+    const uint32_t* e = &cnt[__umul24(uint32_t(u), uint32_t(W))];
+    const uint32_t w0 = e[0];
+    if (fields_per_word == 2) {
+      uint32_t m = w0 >> 16;
+      for (int q = 1; q < W; ++q) {
+        const uint32_t w = e[q];
+        m = max(m, max(w & 0xFFFFu, w >> 16));
+      }
+      part += int(min(w0 & 0xFFFFu, m));
+    } else {  // word 0: candidate, word 1 + j: reference j
+      uint32_t m = 0;
+      for (int q = 1; q < W; ++q) m = max(m, e[q]);
+      part += int(min(w0, m));
+    }
+  }
+  return part;
+}
+
 // Dictionary of one partition of one (group, order): its members' keys are inserted into the LDS
 // table and each occurrence's table entry is remembered; the occupied entries are then numbered;
 // a second walk over the members turns the remembered entries into ids.
-__global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs a) {
+__global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int scan_scratch[17];
   const Problem& pb = a.pb;
@@ -460,14 +524,30 @@ __global__ __launch_bounds__(kPartThreads) void part_dictionary_kernel(PartArgs 
         f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
       if (base + u * nt + tid < members) {
         const uint32_t id = uint32_t(table[min(parked[u], uint32_t(T))]);
+        const uint32_t packed = id | (uint32_t(f) << 16);
         ginv[k[u]] = id_base + id;
-        member_ids[base + u * nt + tid] = id | (uint32_t(f) << 16);
+        member_ids[base + u * nt + tid] = packed;
+        if (base == 0) parked0[u] = packed;
       }
     }
   }
-  // (the group's dictionary size, the sum over the partitions, is formed by the count pass)
   if (tid == 0)
     a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
+  if (!a.with_count) return;  // (then the count pass also forms the group's dictionary size)
+
+  // the count pass's work for this partition, in the table's memory (the host checked that the
+  // counter fields fit); the statistics were zeroed before the launch
+  __syncthreads();
+  const int part = count_clip_partition<true>(
+      reinterpret_cast<uint32_t*>(smem), min(distinct, kPartIdCap), a.words, a.fields_per_word,
+      pb.R, members, member_ids, parked0);
+  const int clipped = block_sum(part, scan_scratch);
+  if (tid == 0) {
+    const int64_t stat = int64_t(g) * pb.N + n - 1;
+    if (clipped) atomicAdd(&a.st.clipped[stat], clipped);
+    if (distinct) atomicAdd(&a.st.distinct[stat], distinct);
+    if (p == 0) a.st.total[stat] = gi.start(1);
+  }
 }
 
 // Count and clip the ids of one partition of one (group, order): one 16-bit LDS field per
@@ -478,7 +558,7 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int red_scratch[17];
   const Problem& pb = a.pb;
-  const int nt = blockDim.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const Role me = role_of_block(a, nullptr, a.pb.N);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
@@ -492,13 +572,6 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
   const int ccnt = gi.start(1);
 
-  {
-    uint4* c4 = reinterpret_cast<uint4*>(cnt);
-    const int quads = (U * W + 3) / 4;
-    for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
-  }
-  __syncthreads();
-
   // the partition's members are exactly the n-grams whose ids lie in this partition's id range;
   // the dictionary pass left each one's id within the partition and its sequence's index
   const int parts = 1 << a.log2_parts;
@@ -507,43 +580,9 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const int members = min(max(start[p + 1] - first, 0), count - first);
   const uint32_t* member_ids =
       a.member_id + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
-  for (int base = 0; base < members; base += kPartUnroll * nt) {
-    uint32_t id[kPartUnroll];
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u)
-      id[u] = member_ids[min(base + u * nt + tid, members - 1)];
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) {
-      const int f = min(int(id[u] >> 16), pb.R);
-      id[u] &= 0xFFFFu;
-      if (base + u * nt + tid < members && id[u] < uint32_t(U)) {
-        if (a.fields_per_word == 2)
-          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
-                    (f & 1) ? 0x10000u : 1u);
-        else
-          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f)], 1u);
-      }
-    }
-  }
-  __syncthreads();
-
-  int part = 0;
-  for (int u = tid; u < U; u += nt) {
-    const uint32_t* e = &cnt[__umul24(uint32_t(u), uint32_t(W))];
-    const uint32_t w0 = e[0];
-    if (a.fields_per_word == 2) {
-      uint32_t m = w0 >> 16;
-      for (int q = 1; q < W; ++q) {
-        const uint32_t w = e[q];
-        m = max(m, max(w & 0xFFFFu, w >> 16));
-      }
-      part += int(min(w0 & 0xFFFFu, m));
-    } else {  // word 0: candidate, word 1 + j: reference j
-      uint32_t m = 0;
-      for (int q = 1; q < W; ++q) m = max(m, e[q]);
-      part += int(min(w0, m));
-    }
-  }
+  const uint32_t none[kPartUnroll] = {};
+  const int part = count_clip_partition<false>(cnt, U, W, a.fields_per_word, pb.R, members,
+                                               member_ids, none);
   const int clipped = block_sum(part, red_scratch);
   if (tid == 0) {
     if (clipped) atomicAdd(&a.st.clipped[int64_t(g) * pb.N + n - 1], clipped);
@@ -586,6 +625,7 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   a.member_key = reinterpret_cast<uint64_t*>(after_slots + slots4);
   a.chunk_hist = reinterpret_cast<int32_t*>(after_slots + 3 * slots4);
   a.xcd_aware = 1;
+  a.with_count = 0;
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
   a.fields_per_word = plan.fields_per_word;
@@ -596,10 +636,10 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   return a;
 }
 
-hipError_t zero_ints(int32_t* p, int64_t count, hipStream_t s) {
+hipError_t zero_ints(int32_t* p, int32_t* q, int64_t count, hipStream_t s) {
   const int64_t blocks = (count + 255) / 256;
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(zero_ints_kernel, dim3(uint32_t(blocks)), dim3(256), 0, s, p, count);
+  hipLaunchKernelGGL(zero_ints_kernel, dim3(uint32_t(blocks)), dim3(256), 0, s, p, q, count);
   return hipGetLastError();
 }
 
@@ -628,17 +668,25 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
   if ((int64_t(kPartIdCap) << lg) > plan->id_stride) plan->id_stride = int64_t(kPartIdCap) << lg;
   plan->dict_lds = size_t(kPartSlots + 2) * 8;
   plan->count_lds = (size_t(kPartIdCap) * plan->words * 4 + 15) & ~size_t(15);
+  plan->count_in_dictionary = plan->count_lds <= size_t(kPartSlots) * 8 ? 1 : 0;
   return plan->count_lds + 256 <= size_t(kLdsBudget);
 }
 
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
+                                  const StatPtrs& st, bool with_count, hipStream_t s) {
+  if (with_count && !plan.count_in_dictionary) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  if (with_count) {  // the partitions add into these
+    e = zero_ints(st.clipped, st.distinct, int64_t(pb.B) * pb.N, s);
+    if (e != hipSuccess) return e;
+  }
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
   if (e != hipSuccess) return e;
   // one launch for the orders with 8-byte packed keys, then one per order with 16-byte keys in
   // ascending order (each is keyed by the ids of the order below it)
   PartArgs a = make_args(pb, ws, plan, st);
+  a.with_count = with_count ? 1 : 0;
   for (int n = 1; n <= pb.N; ++n)
     if (!ws.wide[n - 1]) a.orders[a.num_orders++] = n;
   for (int next_wide = 1; next_wide <= pb.N + 1; ++next_wide) {
@@ -678,7 +726,7 @@ hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const P
   a.xcd_aware = part_xcd_aware(pb, pb.N) ? 1 : 0;
   const int64_t blocks = part_grid(pb, plan, pb.N);
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
+  hipError_t e = zero_ints(st.clipped, nullptr, int64_t(pb.B) * pb.N, s);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_count_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.count_lds));
