@@ -100,13 +100,9 @@ __host__ inline int64_t part_grid(const Problem& pb, const PartPlan& plan, int n
   return (((gn + kXcds - 1) / kXcds * kXcds)) << plan.log2_parts;
 }
 
-// zeroes p[0 .. count) and, if q is not null, q[0 .. count)
-__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int32_t* q, int64_t count) {
+__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int64_t count) {
   const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i < count) {
-    p[i] = 0;
-    if (q) q[i] = 0;
-  }
+  if (i < count) p[i] = 0;
 }
 
 // The 8-byte key of slot k of one (group, order): the packed n-gram, or for an order with 16-byte
@@ -247,6 +243,10 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
   uint64_t* member_keys = a.member_key + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
   int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
   if (tid < kMaxParts) hist[tid] = 0;
+  if (a.with_count && tid == 0) {  // the dictionary workgroups of this (group, order) add into these
+    a.st.clipped[int64_t(g) * pb.N + n - 1] = 0;
+    a.st.distinct[int64_t(g) * pb.N + n - 1] = 0;
+  }
   __syncthreads();
   for (int base = 0; base < count; base += kPartUnroll * nt) {
     uint64_t key[kPartUnroll];
@@ -311,6 +311,10 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_hist_kernel(PartArgs 
   __syncthreads();
   int32_t* out = a.chunk_hist + ((int64_t(g) * pb.N + n - 1) * chunks + c) * parts;
   if (tid < parts) out[tid] = hist[tid];
+  if (a.with_count && c == 0 && tid == 0) {  // see part_scatter_kernel
+    a.st.clipped[int64_t(g) * pb.N + n - 1] = 0;
+    a.st.distinct[int64_t(g) * pb.N + n - 1] = 0;
+  }
 }
 
 __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartArgs a,
@@ -536,7 +540,7 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   if (!a.with_count) return;  // (then the count pass also forms the group's dictionary size)
 
   // the count pass's work for this partition, in the table's memory (the host checked that the
-  // counter fields fit); the statistics were zeroed before the launch
+  // counter fields fit); the scatter kernel zeroed the group's statistics
   __syncthreads();
   const int part = count_clip_partition<true>(
       reinterpret_cast<uint32_t*>(smem), min(distinct, kPartIdCap), a.words, a.fields_per_word,
@@ -636,10 +640,10 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   return a;
 }
 
-hipError_t zero_ints(int32_t* p, int32_t* q, int64_t count, hipStream_t s) {
+hipError_t zero_ints(int32_t* p, int64_t count, hipStream_t s) {
   const int64_t blocks = (count + 255) / 256;
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(zero_ints_kernel, dim3(uint32_t(blocks)), dim3(256), 0, s, p, q, count);
+  hipLaunchKernelGGL(zero_ints_kernel, dim3(uint32_t(blocks)), dim3(256), 0, s, p, count);
   return hipGetLastError();
 }
 
@@ -675,12 +679,7 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, bool with_count, hipStream_t s) {
   if (with_count && !plan.count_in_dictionary) return hipErrorInvalidValue;
-  hipError_t e = hipSuccess;
-  if (with_count) {  // the partitions add into these
-    e = zero_ints(st.clipped, st.distinct, int64_t(pb.B) * pb.N, s);
-    if (e != hipSuccess) return e;
-  }
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
   if (e != hipSuccess) return e;
   // one launch for the orders with 8-byte packed keys, then one per order with 16-byte keys in
@@ -726,7 +725,7 @@ hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const P
   a.xcd_aware = part_xcd_aware(pb, pb.N) ? 1 : 0;
   const int64_t blocks = part_grid(pb, plan, pb.N);
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipError_t e = zero_ints(st.clipped, nullptr, int64_t(pb.B) * pb.N, s);
+  hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_count_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.count_lds));
