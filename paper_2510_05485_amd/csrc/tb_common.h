@@ -90,6 +90,17 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* scratch, int* to
   return scratch[wave] + incl - v;
 }
 
+// Dense ids for the table entries this thread created (any bijection onto 0..U-1 is a valid
+// dictionary): every wavefront reserves a block of ids with one LDS atomic, lanes take their
+// share in lane order.  Returns the first id of this thread.  All 64 lanes must be active.
+__device__ __forceinline__ uint32_t reserve_ids(int created, int* next_id) {
+  const int incl = wave_inclusive_scan(created);
+  const int total = lane_value(incl, kWave - 1);
+  int base = 0;
+  if ((threadIdx.x & (kWave - 1)) == 0 && total) base = atomicAdd(next_id, total);
+  return uint32_t(lane_value(base, 0) + incl - created);
+}
+
 // Sum of one int per thread over the workgroup; result valid in every thread.
 // `scratch` needs 17 ints of LDS.  Contains two barriers.
 __device__ __forceinline__ int block_sum(int v, int* scratch) {

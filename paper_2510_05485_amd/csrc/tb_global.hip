@@ -169,17 +169,6 @@ bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, int bit
   return ok;
 }
 
-// Dense ids for the table entries this thread created (any bijection onto 0..U-1 is a valid
-// dictionary): every wavefront reserves a block of ids with one LDS atomic, lanes take their
-// share in lane order.  Returns the first id of this thread.  All 64 lanes must be active.
-__device__ __forceinline__ uint32_t reserve_ids(int created, int* next_id) {
-  const int incl = wave_inclusive_scan(created);
-  const int total = lane_value(incl, kWave - 1);
-  int base = 0;
-  if ((threadIdx.x & (kWave - 1)) == 0 && total) base = atomicAdd(next_id, total);
-  return uint32_t(lane_value(base, 0) + incl - created);
-}
-
 // Keys of at most 64 bits.  The open-addressing table holds the keys themselves, as 4-byte
 // entries when the order's keys fit 32 bits (twice the slots in the same LDS, cheaper atomics)
 // and as 8-byte entries otherwise; an insertion is one LDS compare-and-swap per probe (double

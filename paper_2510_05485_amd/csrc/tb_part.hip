@@ -417,11 +417,13 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
 }
 
 // Dictionary of one partition of one (group, order): its members' keys are inserted into the LDS
-// table and each occurrence's table entry is remembered; the occupied entries are then numbered;
-// a second walk over the members turns the remembered entries into ids.
+// table and each occurrence's table entry is remembered; the entries are then numbered by the
+// threads that created them; a second walk over the members turns the remembered entries into
+// ids.
 __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int scan_scratch[17];
+  __shared__ int scan_scratch[18];
+  int* next_id = &scan_scratch[17];
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
   const Role me = role_of_block(a, a.orders, a.num_orders);
@@ -456,10 +458,13 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
     uint4* t4 = reinterpret_cast<uint4*>(table);
     for (int s = tid; s < T / 2; s += nt) t4[s] = make_uint4(~0u, ~0u, ~0u, ~0u);
     if (tid == 0) table[T] = kFreeEntry;
+    if (tid == 0) *next_id = 0;
   }
   __syncthreads();
 
   bool lost = false;  // a probe sequence ran through the whole table
+  int created = 0;    // table entries that this thread's compare-and-swaps created ...
+  uint32_t created0 = 0;  // ... bit u: among them the one of member u * nt + tid
   for (int base = 0; base < members; base += kPartUnroll * nt) {
     uint64_t key[kPartUnroll];
 #pragma unroll
@@ -469,11 +474,14 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
     for (int u = 0; u < kPartUnroll; ++u) {
       if (base + u * nt + tid >= members) continue;
       if (key[u] == kFreeEntry) {
-        atomicCAS(&table[T], kFreeEntry, 0ull);
-        if (base == 0)
+        const uint32_t made = atomicCAS(&table[T], kFreeEntry, 0ull) == kFreeEntry ? 1u : 0u;
+        created += int(made);
+        if (base == 0) {
           parked0[u] = uint32_t(T);
-        else
-          member_ids[base + u * nt + tid] = uint32_t(T);
+          created0 |= made << u;
+        } else {
+          member_ids[base + u * nt + tid] = uint32_t(T) | (made << 31);
+        }
         continue;
       }
       const uint32_t h = part_hash(key[u]);
@@ -487,28 +495,35 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
         ++rounds;
       }
       lost |= (old != kFreeEntry && old != key[u]);
-      if (base == 0)
+      const uint32_t made = old == kFreeEntry ? 1u : 0u;
+      created += int(made);
+      if (base == 0) {
         parked0[u] = s;
-      else
-        member_ids[base + u * nt + tid] = s;
+        created0 |= made << u;
+      } else {
+        member_ids[base + u * nt + tid] = s | (made << 31);
+      }
+    }
+  }
+  // number the entries (any numbering that is dense and unique will do): the thread whose
+  // compare-and-swap created an entry names it, from a block of ids its wavefront reserves
+  uint32_t next = reserve_ids(created, next_id);
+  __syncthreads();  // nobody compares keys any more: entries may now hold ids
+#pragma unroll
+  for (int u = 0; u < kPartUnroll; ++u)
+    if ((created0 >> u) & 1u) table[min(parked0[u], uint32_t(T))] = uint64_t(next++);
+  for (int base = kPartUnroll * nt; base < members; base += kPartUnroll * nt) {
+#pragma unroll
+    for (int u = 0; u < kPartUnroll; ++u) {
+      const int i = base + u * nt + tid;
+      if (i < members) {
+        const uint32_t w = member_ids[i];
+        if (w >> 31) table[min(w & 0x7FFFFFFFu, uint32_t(T))] = uint64_t(next++);
+      }
     }
   }
   __syncthreads();
-
-  // number the occupied entries (any numbering that is dense and unique will do): thread t owns
-  // the slots t, t + nt, t + 2 nt, ... -- neighbouring lanes then touch neighbouring LDS words --
-  // and one workgroup-wide scan over the threads' counts gives each thread its first id
-  int distinct = 0;
-  {
-    int mine = 0;
-    for (int s = tid; s < T; s += nt) mine += (table[s] != kFreeEntry) ? 1 : 0;
-    int id = block_exclusive_scan(mine, scan_scratch, &distinct);
-    for (int s = tid; s < T; s += nt)
-      if (table[s] != kFreeEntry) table[s] = uint64_t(id++);
-    if (tid == 0 && table[T] != kFreeEntry) table[T] = uint64_t(distinct);  // the all-ones key
-    distinct += (table[T] != kFreeEntry) ? 1 : 0;  // read before or after thread 0's write: same
-  }
-  __syncthreads();
+  const int distinct = *next_id;
   if ((lost || distinct > kPartIdCap) && pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
 
   const uint32_t id_base =
@@ -520,7 +535,9 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
       k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
-      parked[u] = base == 0 ? parked0[u] : member_ids[min(base + u * nt + tid, members - 1)];
+      parked[u] = base == 0
+                      ? parked0[u]
+                      : (member_ids[min(base + u * nt + tid, members - 1)] & 0x7FFFFFFFu);
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       int f = 0;  // the sequence of a slot: how many sequences end at or before it
