@@ -66,6 +66,7 @@ struct PartPlan {
   int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 128
   int id_cap;         // ids a partition may hand out
   int words;          // count/clip: 32-bit counter words per id
+  int refs_per_pass;  // count/clip: 0 = every sequence has its field; else references per pass
   int fields_per_word;  // 2: 16-bit counters, 1: 32-bit (a stride above 65 535)
   int64_t id_stride;  // id range per group: max(group_cap, P * id_cap)
   size_t dict_lds, count_lds;

@@ -47,6 +47,7 @@ struct PartArgs {
   int32_t* chunk_hist;     // [B, N, chunks, P] chunked scatter: per-chunk partition histograms
   int xcd_aware;           // block -> (group, order, partition): see role_of_block
   int with_count;          // the dictionary kernel also counts and clips its partition
+  int refs_per_pass;       // count kernel: 0, or references per pass when they do not fit LDS
   int log2_parts;          // P = 1 << log2_parts, P >= 2
   int orders[8];           // dictionary: the orders of this launch, and how many
   int num_orders;
@@ -416,6 +417,75 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
   return part;
 }
 
+// The same when one counter field per sequence does not fit LDS: the references are taken
+// `refs_per_pass` at a time.  Per id, W = kPassWords words: the candidate's count and the largest
+// reference count so far (two 16-bit halves of word 0, or words 0 and 1 with 32-bit counters),
+// then the fields of the pass's references.  Every pass walks the members, keeps those of its
+// references (and, in the first, the candidate's), folds the fields' maximum into the running one
+// and clears them.
+constexpr int kPassWords = 6;
+__device__ __forceinline__ int count_clip_partition_in_passes(uint32_t* cnt, int U,
+                                                              int fields_per_word, int R,
+                                                              int refs_per_pass, int members,
+                                                              const uint32_t* member_ids) {
+  const int nt = blockDim.x, tid = threadIdx.x;
+  constexpr int W = kPassWords;
+  const int first_word = fields_per_word == 2 ? 1 : 2;  // of the pass's reference fields
+  {
+    uint4* c4 = reinterpret_cast<uint4*>(cnt);
+    const int quads = (U * W + 3) / 4;
+    for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  __syncthreads();
+  for (int pass_first = 0; pass_first < R; pass_first += refs_per_pass) {  // first reference
+    for (int base = 0; base < members; base += kPartUnroll * nt) {
+      uint32_t id[kPartUnroll];
+#pragma unroll
+      for (int u = 0; u < kPartUnroll; ++u)
+        id[u] = member_ids[min(base + u * nt + tid, members - 1)];
+#pragma unroll
+      for (int u = 0; u < kPartUnroll; ++u) {
+        const int f = min(int(id[u] >> 16), R);  // 0: candidate, 1 + j: reference j
+        id[u] &= 0xFFFFu;
+        if (base + u * nt + tid >= members || id[u] >= uint32_t(U)) continue;
+        uint32_t* e = &cnt[id[u] * uint32_t(W)];
+        const int r = f - 1 - pass_first;  // reference within the pass
+        if (f == 0) {
+          if (pass_first == 0) atomicAdd(&e[0], 1u);
+        } else if (r >= 0 && r < refs_per_pass) {
+          if (fields_per_word == 2)
+            atomicAdd(&e[first_word + (r >> 1)], (r & 1) ? 0x10000u : 1u);
+          else
+            atomicAdd(&e[first_word + r], 1u);
+        }
+      }
+    }
+    __syncthreads();
+    for (int u = tid; u < U; u += nt) {
+      uint32_t* e = &cnt[uint32_t(u) * uint32_t(W)];
+      uint32_t m = 0;
+      for (int q = first_word; q < W; ++q) {
+        const uint32_t w = e[q];
+        m = fields_per_word == 2 ? max(m, max(w & 0xFFFFu, w >> 16)) : max(m, w);
+        e[q] = 0;
+      }
+      if (fields_per_word == 2) {
+        const uint32_t w0 = e[0];
+        e[0] = (w0 & 0xFFFFu) | (max(w0 >> 16, m) << 16);
+      } else {
+        e[1] = max(e[1], m);
+      }
+    }
+    __syncthreads();
+  }
+  int part = 0;
+  for (int u = tid; u < U; u += nt) {
+    const uint32_t* e = &cnt[uint32_t(u) * uint32_t(W)];
+    part += fields_per_word == 2 ? int(min(e[0] & 0xFFFFu, e[0] >> 16)) : int(min(e[0], e[1]));
+  }
+  return part;
+}
+
 // Dictionary of one partition of one (group, order): its members' keys are inserted into the LDS
 // table and each occurrence's table entry is remembered; the entries are then numbered by the
 // threads that created them; a second walk over the members turns the remembered entries into
@@ -602,8 +672,12 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const uint32_t* member_ids =
       a.member_id + (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
   const uint32_t none[kPartUnroll] = {};
-  const int part = count_clip_partition<false>(cnt, U, W, a.fields_per_word, pb.R, members,
-                                               member_ids, none);
+  const int part =
+      a.refs_per_pass
+          ? count_clip_partition_in_passes(cnt, U, a.fields_per_word, pb.R, a.refs_per_pass,
+                                           members, member_ids)
+          : count_clip_partition<false>(cnt, U, W, a.fields_per_word, pb.R, members, member_ids,
+                                        none);
   const int clipped = block_sum(part, red_scratch);
   if (tid == 0) {
     if (clipped) atomicAdd(&a.st.clipped[int64_t(g) * pb.N + n - 1], clipped);
@@ -650,6 +724,7 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
   a.fields_per_word = plan.fields_per_word;
+  a.refs_per_pass = plan.refs_per_pass;
   a.id_stride = plan.id_stride;
   for (int k = 0; k < 8; ++k) a.orders[k] = 0;
   a.num_orders = 0;
@@ -685,6 +760,11 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
   // 16-bit counters while no sequence can hold an n-gram more than 65 535 times
   plan->fields_per_word = (cand_stride > 65535 || ref_stride > 65535) ? 1 : 2;
   plan->words = plan->fields_per_word == 2 ? (R + 2) / 2 : R + 1;
+  plan->refs_per_pass = 0;
+  if (plan->words > kPassWords) {  // several passes over the references: see the count kernel
+    plan->words = kPassWords;
+    plan->refs_per_pass = plan->fields_per_word == 2 ? 2 * (kPassWords - 1) : kPassWords - 2;
+  }
   plan->id_stride = group_cap;
   if ((int64_t(kPartIdCap) << lg) > plan->id_stride) plan->id_stride = int64_t(kPartIdCap) << lg;
   plan->dict_lds = size_t(kPartSlots + 2) * 8;

@@ -103,18 +103,22 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
 def test_group_too_large_for_lds_falls_back_to_tables_in_the_workspace(lib):
     cfg = tb.make_config(vocab_size=50257, path="global")
     lay = binding.tb_layout_t()
-    # 17 sequences: beyond the single-table kernels (12 288 slots) and, with more than 11
+    # 64 sequences: beyond the single-table kernels (12 288 slots) and, with more than 62
     # references, not for the partitioned ones either
-    rc = lib.tensorbleu_workspace_layout(2, 16, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
+    rc = lib.tensorbleu_workspace_layout(2, 63, 8192, 8192, ctypes.byref(cfg), ctypes.byref(lay))
     assert rc == 0 and lay.global_ok == 1 and lay.global_tables_in_hbm == 1
     assert lay.global_partitions == 0 and lay.id_stride == lay.group_cap
-    cap = 17 * 8192
+    cap = 64 * 8192
     slots = 1 << (2 * cap - 1).bit_length()
     assert lay.bytes >= lay.tables_off + 2 * 4 * (slots + 8) * 8
     fused = tb.make_config(vocab_size=50257, path="fused")
-    assert lib.tensorbleu_workspace_layout(2, 16, 8192, 8192, ctypes.byref(fused),
+    assert lib.tensorbleu_workspace_layout(2, 63, 8192, 8192, ctypes.byref(fused),
                                            ctypes.byref(lay)) == 3
-    assert tb.tensorbleu_workspace_bytes(2, 16, 8192, 8192, fused) == 0
+    assert tb.tensorbleu_workspace_bytes(2, 63, 8192, 8192, fused) == 0
+    # up to 62 references the partitioned kernels take such groups (the count kernel then takes
+    # the references a few at a time)
+    lay = tb.tensorbleu_workspace_layout(2, 16, 8192, 8192, cfg)
+    assert lay.global_tables_in_hbm == 0 and lay.global_partitions == 64
 
 
 def test_partitioned_layout_between_the_lds_kernels_and_the_workspace_tables(lib):
@@ -125,9 +129,12 @@ def test_partitioned_layout_between_the_lds_kernels_and_the_workspace_tables(lib
     assert lay.bytes >= lay.tables_off + 2 * 4 * 32 * 4               # int32 [B, N, P]
     small = tb.tensorbleu_workspace_layout(2, 1, 8192, 8192, cfg)     # 16 384 slots
     assert small.global_partitions == 4 and small.id_stride == 4 * 6144
-    # more references than the partitioned count kernel has LDS for: tables in the workspace
+    # more references than the partitioned count kernel has counter fields for at once: still
+    # partitioned (it takes them in passes); from 63 references on: tables in the workspace
     many = tb.tensorbleu_workspace_layout(2, 12, 2048, 2048, cfg)
-    assert many.global_partitions == 0 and many.global_tables_in_hbm == 1
+    assert many.global_partitions == 8 and many.global_tables_in_hbm == 0
+    most = tb.tensorbleu_workspace_layout(2, 63, 512, 512, cfg)
+    assert most.global_partitions == 0 and most.global_tables_in_hbm == 1
     # 128 partitions at most: 9 * 65 535 slots would need more
     far = tb.tensorbleu_workspace_layout(1, 8, 65535, 65535, cfg)
     assert far.global_partitions == 0 and far.global_tables_in_hbm == 1

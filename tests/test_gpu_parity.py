@@ -277,6 +277,18 @@ def test_partitions_with_sequences_beyond_65535_tokens():
     check(w, syn.Run("floor", 0.1), "auto")
 
 
+def test_partitions_with_more_references_than_counter_fields():
+    # more than 11 references (5 with 32-bit counters): the partitioned count kernel takes the
+    # references in passes of 10 (4) and keeps a running maximum per dictionary entry
+    for seed, B, R, V, L, P in [(151, 2, 16, 1000, 1024, 8), (152, 1, 30, 50, 600, 8),
+                                (153, 1, 6, 5, 70000, 128)]:
+        w = cached_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=L * 4 // 5)
+        cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+        lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+        assert lay.global_partitions == P and lay.global_tables_in_hbm == 0
+        check(w, syn.Run("exp"), "auto")
+
+
 def test_long_form_workload_at_full_size():
     """The long-generation workload bench.py --long-form times (128 groups of ~16 000 tokens, four
     partitions per group and order), every sentence against the oracle."""
@@ -341,7 +353,8 @@ def _ragged_case(seed, B, R, V, L):
     (201, 37, 4, 11, 60),          # LDS kernels, one field per sequence
     (202, 6, 3, 262144, 700),      # 128-bit keys
     (203, 5, 40, 300, 120),        # many references (pair-phase count kernel on the global path)
-    (204, 3, 2, 50, 9000),         # group beyond the LDS plans: tables in the workspace
+    (204, 3, 2, 50, 9000),         # group beyond one LDS table: partitioned kernels
+    (205, 3, 14, 300, 1000),       # the same with the references counted in two passes
 ])
 def test_ragged_reference_counts(path, seed, B, R, V, L):
     w, rc, refs, ref_len = _ragged_case(seed, B, R, V, L)
