@@ -117,7 +117,10 @@ typedef struct tb_stats {
  * [g*group_cap, (g+1)*group_cap) and fills them compactly from the front with its valid n-grams
  * of that order: the candidate's (in position order), then reference 0's, reference 1's, ...
  * Sequence s of the group therefore starts at g*group_cap + sum over earlier sequences of
- * max(len - n + 1, 0).  Slots past the group's last n-gram are never written. */
+ * max(len - n + 1, 0).  Slots past the group's last n-gram are never written.  The staged entry
+ * points below fill these arrays as described; what tensorbleu_sentence / tensorbleu_corpus
+ * leave in the workspace is unspecified (they skip stores that only a staged caller would
+ * read). */
 typedef struct tb_layout {
   int32_t path;            /* path AUTO resolves to for this shape (TB_PATH_FUSED / TB_PATH_GLOBAL) */
   int32_t bits;            /* ceil(log2(vocab_size)), at least 1 */

@@ -183,15 +183,14 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 
-// with_count: a whole call, where the partitioned dictionary kernel may take over the count/clip
-// pass (counts_in_dictionary says whether it does)
+// whole_call: the partitioned dictionary kernel then may take over the count/clip pass
+// (counts_in_dictionary says whether it does) and stores only the ids that later orders need
 bool counts_in_dictionary(const Call& c) {
   return c.plans.use_part && c.plans.part.count_in_dictionary;
 }
-hipError_t run_dictionary(const Call& c, bool with_count) {
+hipError_t run_dictionary(const Call& c, bool whole_call) {
   if (c.plans.use_part)
-    return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st,
-                                  with_count && counts_in_dictionary(c), c.stream);
+    return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st, whole_call, c.stream);
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }

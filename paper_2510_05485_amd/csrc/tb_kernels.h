@@ -76,10 +76,12 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
                const int32_t* key_bytes, PartPlan* plan);
 // bytes the partitioned kernels need at GlobalWs::tables
 size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan& plan);
-// with_count (only if plan.count_in_dictionary): the dictionary kernel also does the count/clip
-// pass's work, which is then not to be launched
+// whole_call: the count/clip pass follows at once and nobody else reads the id array, so ids are
+// stored only where a later order's keys are derived from them and, if
+// plan.count_in_dictionary, the dictionary kernel also does the count/clip pass's work, which is
+// then not to be launched
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, bool with_count, hipStream_t s);
+                                  const StatPtrs& st, bool whole_call, hipStream_t s);
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s);
 

@@ -47,6 +47,7 @@ struct PartArgs {
   int32_t* chunk_hist;     // [B, N, chunks, P] chunked scatter: per-chunk partition histograms
   int xcd_aware;           // block -> (group, order, partition): see role_of_block
   int with_count;          // the dictionary kernel also counts and clips its partition
+  int ids_wanted;          // bit n: order n's ids must reach the id array (ws.inv)
   int refs_per_pass;       // count kernel: 0, or references per pass when they do not fit LDS
   int log2_parts;          // P = 1 << log2_parts, P >= 2
   int orders[8];           // dictionary: the orders of this launch, and how many
@@ -598,6 +599,8 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
 
   const uint32_t id_base =
       uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
+  // a whole call needs the id array only where the next order's keys are derived from it
+  const bool publish_ids = (a.ids_wanted >> n) & 1;
   for (int base = 0; base < members; base += kPartUnroll * nt) {
     uint32_t k[kPartUnroll], parked[kPartUnroll];
 #pragma unroll
@@ -616,8 +619,9 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
       if (base + u * nt + tid < members) {
         const uint32_t id = uint32_t(table[min(parked[u], uint32_t(T))]);
         const uint32_t packed = id | (uint32_t(f) << 16);
-        ginv[k[u]] = id_base + id;
-        member_ids[base + u * nt + tid] = packed;
+        if (publish_ids) ginv[k[u]] = id_base + id;
+        // (when this kernel counts, only the members beyond the first 8192 are read again)
+        if (!a.with_count || base != 0) member_ids[base + u * nt + tid] = packed;
         if (base == 0) parked0[u] = packed;
       }
     }
@@ -721,6 +725,7 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   a.chunk_hist = reinterpret_cast<int32_t*>(after_slots + 3 * slots4);
   a.xcd_aware = 1;
   a.with_count = 0;
+  a.ids_wanted = ~0;
   a.log2_parts = plan.log2_parts;
   a.words = plan.words;
   a.fields_per_word = plan.fields_per_word;
@@ -774,8 +779,8 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 }
 
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, bool with_count, hipStream_t s) {
-  if (with_count && !plan.count_in_dictionary) return hipErrorInvalidValue;
+                                  const StatPtrs& st, bool whole_call, hipStream_t s) {
+  const bool with_count = whole_call && plan.count_in_dictionary;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
   if (e != hipSuccess) return e;
@@ -783,6 +788,11 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
   // ascending order (each is keyed by the ids of the order below it)
   PartArgs a = make_args(pb, ws, plan, st);
   a.with_count = with_count ? 1 : 0;
+  if (whole_call) {  // nobody reads the id array afterwards, except the derived keys
+    a.ids_wanted = 0;
+    for (int n = 1; n < pb.N; ++n)
+      if (ws.wide[n]) a.ids_wanted |= 1 << n;  // order n + 1 is keyed by order n's ids
+  }
   for (int n = 1; n <= pb.N; ++n)
     if (!ws.wide[n - 1]) a.orders[a.num_orders++] = n;
   for (int next_wide = 1; next_wide <= pb.N + 1; ++next_wide) {
