@@ -286,6 +286,54 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
   }
 }
 
+// The same for groups of at most 16 384 slots: every thread keeps its 16 keys in registers
+// between the histogram and the scatter, so the keys are read once.
+constexpr int kScatterRegItems = 16;
+__global__ __launch_bounds__(kPartThreads, 8) void part_scatter_small_kernel(PartArgs a) {
+  __shared__ int hist[kMaxParts], cursor[kMaxParts];
+  const Problem& pb = a.pb;
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int g = int(blockIdx.x) / a.num_orders, n = a.orders[int(blockIdx.x) % a.num_orders];
+  const int parts = 1 << a.log2_parts;
+  const KeySource key_of(a, g, n);
+  const int count = min(key_of.count, kScatterRegItems * nt);
+  uint32_t* members = a.member_slot + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
+  uint64_t* member_keys = a.member_key + (int64_t(n - 1) * pb.B + g) * pb.group_cap;
+  int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
+  if (tid < kMaxParts) hist[tid] = 0;
+  if (a.with_count && tid == 0) {  // see part_scatter_kernel
+    a.st.clipped[int64_t(g) * pb.N + n - 1] = 0;
+    a.st.distinct[int64_t(g) * pb.N + n - 1] = 0;
+  }
+  __syncthreads();
+  uint64_t key[kScatterRegItems];
+#pragma unroll
+  for (int i = 0; i < kScatterRegItems; ++i) key[i] = key_of(max(min(i * nt + tid, count - 1), 0));
+#pragma unroll
+  for (int i = 0; i < kScatterRegItems; ++i)
+    if (i * nt + tid < count) atomicAdd(&hist[partition_of_key(key[i], a.log2_parts)], 1);
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int q = 0; q < parts; ++q) {
+      cursor[q] = run;
+      start[q] = run;
+      run += hist[q];
+    }
+    start[parts] = run;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kScatterRegItems; ++i) {
+    const int k = i * nt + tid;
+    if (k < count) {
+      const int at = atomicAdd(&cursor[partition_of_key(key[i], a.log2_parts)], 1);
+      members[at] = uint32_t(k);
+      member_keys[at] = key[i];
+    }
+  }
+}
+
 // The same in two kernels with one workgroup per 16 384 slots, for batches of few, very long
 // groups (one workgroup per (group, order) would leave most of the GPU idle): per-chunk
 // histograms, then the scatter, in which every workgroup derives its own cursors (and chunk 0
@@ -807,6 +855,9 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
                            dim3(kPartThreads), 0, s, a, chunks);
         hipLaunchKernelGGL(part_chunk_scatter_kernel, dim3(uint32_t(pairs * chunks)),
                            dim3(kPartThreads), 0, s, a, chunks);
+      } else if (pb.group_cap <= int64_t(kScatterRegItems) * kPartThreads) {
+        hipLaunchKernelGGL(part_scatter_small_kernel, dim3(uint32_t(pairs)), dim3(kPartThreads),
+                           0, s, a);
       } else {
         hipLaunchKernelGGL(part_scatter_kernel, dim3(uint32_t(pairs)), dim3(kPartThreads), 0, s,
                            a);
