@@ -242,6 +242,17 @@ def test_group_too_large_for_one_lds_table(vocab):
         check(w, run, "auto", d=d)
 
 
+@pytest.mark.parametrize("vocab", [50, 262144])
+def test_partitioned_group_of_at_most_16384_slots(vocab):
+    # 12 288 < group_cap <= 16 384: four partitions, and the scatter kernel that keeps a group's
+    # keys in registers (with the largest vocabulary also for the derived keys of the 4-grams)
+    w = cached_small(155, B=3, R=3, vocab=vocab, max_len=4000, min_len=3400)
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.path == 2 and lay.global_partitions == 4 and lay.group_cap <= 16384
+    check(w, syn.Run("exp"), "auto")
+
+
 def test_long_form_sequences_of_300k_tokens():
     # two groups of ~600 000 tokens each (a candidate and one reference of up to 300 000): far
     # beyond LDS, and with a 3-token vocabulary single n-gram counts far beyond 16 bits
