@@ -145,7 +145,7 @@ typedef struct tb_layout {
   int64_t id_stride;       /* id range per group on the GLOBAL path: group_cap, or more when
                               global_partitions > 0 */
   int32_t global_partitions; /* P > 0: groups beyond the single-table LDS kernels (12 288 slots)
-                              but within 524 288 are handled by P workgroups per (group, order),
+                              but within 2 097 152 are handled by P workgroups per (group, order),
                               each keeping one hash partition of the dictionary in LDS; ids are
                               then p*6144 + a number dense within partition p.  Orders whose
                               packed keys take 16 bytes are keyed there by (id of the (n-1)-gram

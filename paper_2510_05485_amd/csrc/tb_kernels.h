@@ -60,10 +60,10 @@ struct BigPlan {
   int64_t slots;          // hash-table slots per (group, order): power of two >= 2 * group_cap
   int64_t table_entries;  // slots + padding, 8 bytes each
 };
-// Groups of up to 524 288 n-gram slots beyond the LDS plans: P workgroups per (group, order), each
-// with the dictionary entries / counters of one hash partition in LDS.
+// Groups of up to 2 097 152 n-gram slots beyond the LDS plans: P workgroups per (group, order),
+// each with the dictionary entries / counters of one hash partition in LDS.
 struct PartPlan {
-  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 128
+  int log2_parts;     // P = 1 << log2_parts workgroups per (group, order), 2 .. 512
   int id_cap;         // ids a partition may hand out
   int words;          // count/clip: 32-bit counter words per id
   int refs_per_pass;  // count/clip: 0 = every sequence has its field; else references per pass

@@ -1,4 +1,4 @@
-// GLOBAL path for sentence groups of 12 289 .. 524 288 n-gram slots: too many for one LDS hash
+// GLOBAL path for sentence groups of 12 289 .. 2 097 152 n-gram slots: too many for one LDS hash
 // table, few enough that the table can be split.  The dictionary and count/clip passes
 // (paper Sections 3.2-3.3) run with P workgroups per (group, order); workgroup p owns the
 // n-grams whose key hashes into partition p and keeps its share of the dictionary (or of the
@@ -31,7 +31,7 @@ constexpr int kPartSlots = 8192;     // 8-byte table entries: 64 KB of LDS
 constexpr int kPartIdCap = 6144;     // distinct n-grams a partition may hold (3/4 of its slots)
 constexpr int kPartTarget = 4096;    // P is chosen so that a partition expects at most this many slots
 constexpr int kPartUnroll = 8;       // loads in flight per thread
-constexpr int kMaxParts = 128;       // partitions per (group, order): groups of up to 524 288 slots
+constexpr int kMaxParts = 512;       // partitions per (group, order): groups of up to 2 097 152 slots
 constexpr int kScatterChunk = 16384; // slots per workgroup of the chunked scatter
 constexpr unsigned long long kFreeEntry = ~0ull;
 
@@ -171,7 +171,7 @@ __device__ __forceinline__ int partition_of_key(uint64_t key, int log2_parts) {
 constexpr int kRound = 4096, kRoundUnroll = kRound / kPartThreads;
 struct ScatterLds {
   uint64_t key[kRound];
-  uint32_t slot[kRound];  // slot number | partition << 24
+  uint32_t slot[kRound];  // slot number (below 2^22) | partition << 22
   int count[kMaxParts];   // of the round, per partition; zero between rounds
   int first[kMaxParts];   // where the partition's run starts in the round's sorted order
   int shift[kMaxParts];   // sorted position + shift = position in the partition's segment
@@ -214,15 +214,15 @@ __device__ __forceinline__ void scatter_range(const PartArgs& a, const KeySource
         const int q = where[u] >> 16;
         const int pos = min(lds.first[q] + (where[u] & 0xFFFF), kRound - 1);
         lds.key[pos] = key[u];
-        lds.slot[pos] = uint32_t(k) | (uint32_t(q) << 24);
+        lds.slot[pos] = uint32_t(k) | (uint32_t(q) << 22);
       }
     }
     __syncthreads();
     const int in_round = min(kRound, end - base);
     for (int i = tid; i < in_round; i += nt) {
       const uint32_t v = lds.slot[i];
-      const int at = min(max(lds.shift[v >> 24] + i, 0), last);  // (clamped: see the callers)
-      members[at] = v & 0xFFFFFFu;
+      const int at = min(max(lds.shift[v >> 22] + i, 0), last);  // (clamped: see the callers)
+      members[at] = v & 0x3FFFFFu;
       member_keys[at] = lds.key[i];
     }
     __syncthreads();

@@ -135,9 +135,11 @@ def test_partitioned_layout_between_the_lds_kernels_and_the_workspace_tables(lib
     assert many.global_partitions == 8 and many.global_tables_in_hbm == 0
     most = tb.tensorbleu_workspace_layout(2, 63, 512, 512, cfg)
     assert most.global_partitions == 0 and most.global_tables_in_hbm == 1
-    # 128 partitions at most: 9 * 65 535 slots would need more
-    far = tb.tensorbleu_workspace_layout(1, 8, 65535, 65535, cfg)
+    # 512 partitions at most: 41 * 65 535 slots would need more
+    far = tb.tensorbleu_workspace_layout(1, 40, 65535, 65535, cfg)
     assert far.global_partitions == 0 and far.global_tables_in_hbm == 1
+    most = tb.tensorbleu_workspace_layout(1, 31, 65535, 65535, cfg)     # 2 097 120 slots
+    assert most.global_partitions == 512 and most.global_tables_in_hbm == 0
     wide = tb.tensorbleu_workspace_layout(1, 7, 65535, 65535, cfg)     # 524 280 slots
     assert wide.global_partitions == 128
     # strides above 65 535 are fine there (32-bit counters)

@@ -254,13 +254,30 @@ def test_partitioned_group_of_at_most_16384_slots(vocab):
 
 
 def test_long_form_sequences_of_300k_tokens():
-    # two groups of ~600 000 tokens each (a candidate and one reference of up to 300 000): far
-    # beyond LDS, and with a 3-token vocabulary single n-gram counts far beyond 16 bits
+    # two groups of ~600 000 tokens each (a candidate and one reference of up to 300 000): 256
+    # partitions, and with a 3-token vocabulary single n-gram counts far beyond 16 bits
     w = cached_small(145, B=2, R=1, vocab=3, max_len=300000, min_len=250000)
     assert np.bincount(w.cand[0, :w.cand_len[0]]).max() > 65535
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_partitions == 256 and lay.global_tables_in_hbm == 0
     check(w, syn.Run("exp"), "auto")
     w = cached_small(146, B=2, R=1, vocab=50257, max_len=300000, min_len=250000)
     check(w, syn.Run("add-k", 1.0), "global")
+
+
+def test_groups_beyond_the_partitioned_kernels_use_tables_in_the_workspace():
+    # a candidate and a reference of ~1.1 million tokens: more than 2 097 152 slots per group
+    w = cached_small(156, B=1, R=1, vocab=50257, max_len=1100000, min_len=1060000)
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_partitions == 0 and lay.global_tables_in_hbm == 1
+    check(w, syn.Run("exp"), "auto")
+    # just below: 512 partitions
+    w = cached_small(157, B=1, R=1, vocab=1000, max_len=1040000, min_len=1000000)
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_partitions == 512 and lay.global_tables_in_hbm == 0
+    check(w, syn.Run("floor", 0.1), "auto")
 
 
 def test_sixty_four_partitions():
