@@ -18,9 +18,11 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-# sweep seeds 11..13: small groups (the LDS kernels); 21: groups of up to 126 000 tokens and up to
-# 66 references (hash tables in the workspace, the loop fallback of the group index)
-@pytest.mark.parametrize("sweep_seed", [11, 12, 13, 21])
+# sweep seeds 11..13: small groups (the LDS kernels); 21: groups of up to 126 000 tokens (the
+# partitioned kernels) or with 66 references (hash tables in the workspace, the loop fallback of
+# the group index); 22: 13 to 45 references on groups beyond one LDS table (the partitioned count
+# kernel takes the references in passes)
+@pytest.mark.parametrize("sweep_seed", [11, 12, 13, 21, 22])
 def test_random_sweep(sweep_seed):
     rng = np.random.default_rng(sweep_seed)
     worst = 0.0
@@ -35,6 +37,9 @@ def test_random_sweep(sweep_seed):
             B = int(rng.integers(1, 4))
             R = int(rng.choice([1, 2, 4, 8, 66]))
             L = int(rng.choice([150, 400, 900] if R > 60 else [2000, 3500, 6000, 9000, 14000]))
+            if sweep_seed == 22:
+                R = int(rng.choice([13, 24, 45]))
+                L = int(rng.choice([600, 1500, 4000]))
         seed = int(rng.integers(1, 1 << 30))
         w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=int(rng.integers(0, 2)))
         N = int(rng.choice([1, 2, 3, 4, 4, 4, 5, 8]))
