@@ -212,6 +212,8 @@ def main():
     ap.add_argument("--long-form", type=int, default=0, metavar="L",
                     help="instead of a BASELINE configuration: 128 candidates of about L tokens "
                          "with one reference each (groups beyond one LDS table for L > 6144)")
+    ap.add_argument("--long-batch", type=int, default=128, metavar="B",
+                    help="with --long-form: the number of candidates")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short measurements of the other BASELINE configurations")
     ap.add_argument("--no-global-passes", action="store_true",
@@ -246,7 +248,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    w = syn.long_form(L=a.long_form) if a.long_form else syn.make(a.config)
+    w = syn.long_form(B=a.long_batch, L=a.long_form) if a.long_form else syn.make(a.config)
     run = [r for r in w.runs if not r.corpus][-1]
     N = w.max_n
     to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
@@ -363,7 +365,7 @@ def main():
                            "sentences_per_s": round(w.B / (r_ms * 1e-3), 1),
                            "frac_hbm": round(alg["fused"] / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
     if not a.no_other_configs:
-        result["other_configs"] = other_configs("long" if a.long_form == 8192 else
+        result["other_configs"] = other_configs("long" if (a.long_form, a.long_batch) == (8192, 128) else
                                                 0 if a.long_form else a.config, min(a.steps, 100),
                                                 torch, tb, syn, np, dev)
     if not a.no_hbm_ceiling:

@@ -19,6 +19,8 @@
 // their (n-1)-gram prefixes are equal -- i.e. have the same id -- and their last tokens are equal,
 // so this key identifies the n-gram as exactly as the packed one does; it needs the dictionary of
 // order n - 1 to be complete, hence one launch per such order after the others.
+#include <type_traits>
+
 #include "tb_group_index.h"
 #include "tb_kernels.h"
 
@@ -425,26 +427,49 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
     for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
   }
   __syncthreads();
-  for (int base = 0; base < members; base += kPartUnroll * nt) {
-    uint32_t id[kPartUnroll];
+  // A crowded partition (see the dictionary kernel) holds thousands of occurrences of one
+  // n-gram: there the lanes of a wavefront that hold the same (id, sequence) as its first lane
+  // add up in one atomic instead of queueing at one LDS address.
+  auto tally = [&](auto crowded) {
+    constexpr bool kCrowded = decltype(crowded)::value;
+    for (int base = 0; base < members; base += kPartUnroll * nt) {
+      uint32_t id[kPartUnroll];
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u)
-      id[u] = (kFirstRoundInRegs && base == 0)
-                  ? first_round[u]
-                  : member_ids[min(base + u * nt + tid, members - 1)];
+      for (int u = 0; u < kPartUnroll; ++u)
+        id[u] = (kFirstRoundInRegs && base == 0)
+                    ? first_round[u]
+                    : member_ids[min(base + u * nt + tid, members - 1)];
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) {
-      const int f = min(int(id[u] >> 16), R);
-      id[u] &= 0xFFFFu;
-      if (base + u * nt + tid < members && id[u] < uint32_t(U)) {
-        if (fields_per_word == 2)
-          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
-                    (f & 1) ? 0x10000u : 1u);
-        else
-          atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f)], 1u);
+      for (int u = 0; u < kPartUnroll; ++u) {
+        const int f = min(int(id[u] >> 16), R);
+        const uint32_t word = (id[u] & 0xFFFFu) | (uint32_t(f) << 16);
+        id[u] &= 0xFFFFu;
+        bool mine = base + u * nt + tid < members && id[u] < uint32_t(U);
+        uint32_t times = 1;
+        if (kCrowded) {
+          const unsigned long long live = __ballot(mine);
+          if (live) {  // uniform over the wavefront
+            const int leader = __ffsll(live) - 1;
+            const uint32_t first = uint32_t(__builtin_amdgcn_readlane(int(word), leader));
+            const unsigned long long same = __ballot(mine && word == first);
+            times = word == first ? uint32_t(__popcll(same)) : 1u;  // the leader adds for all
+            mine = mine && (word != first || int(tid & (kWave - 1)) == leader);
+          }
+        }
+        if (mine) {
+          if (fields_per_word == 2)
+            atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f >> 1)],
+                      (f & 1) ? (times << 16) : times);
+          else
+            atomicAdd(&cnt[__umul24(id[u], uint32_t(W)) + uint32_t(f)], times);
+        }
       }
     }
-  }
+  };
+  if (members > 2 * kPartTarget)
+    tally(std::true_type{});
+  else
+    tally(std::false_type{});
   __syncthreads();
   int part = 0;
   for (int u = tid; u < U; u += nt) {
@@ -581,49 +606,101 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   }
   __syncthreads();
 
+  // Far more members than a partition expects means that some n-gram occurs thousands of times
+  // (a frequent token in a long text): its occurrences would queue up at one LDS address.
+  const bool crowded = members > 2 * kPartTarget;
   bool lost = false;  // a probe sequence ran through the whole table
   int created = 0;    // table entries that this thread's compare-and-swaps created ...
   uint32_t created0 = 0;  // ... bit u: among them the one of member u * nt + tid
-  for (int base = 0; base < members; base += kPartUnroll * nt) {
-    uint64_t key[kPartUnroll];
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u)
-      key[u] = member_keys[min(base + u * nt + tid, members - 1)];
-#pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) {
-      if (base + u * nt + tid >= members) continue;
-      if (key[u] == kFreeEntry) {
-        const uint32_t made = atomicCAS(&table[T], kFreeEntry, 0ull) == kFreeEntry ? 1u : 0u;
+  auto insert_members = [&](auto peek) {
+    constexpr bool kPeek = decltype(peek)::value;
+    for (int base = 0; base < members; base += kPartUnroll * nt) {
+      uint64_t key[kPartUnroll];
+  #pragma unroll
+      for (int u = 0; u < kPartUnroll; ++u)
+        key[u] = member_keys[min(base + u * nt + tid, members - 1)];
+  #pragma unroll
+      for (int u = 0; u < kPartUnroll; ++u) {
+        if (base + u * nt + tid >= members) continue;
+        if (key[u] == kFreeEntry) {
+          const uint32_t made = atomicCAS(&table[T], kFreeEntry, 0ull) == kFreeEntry ? 1u : 0u;
+          created += int(made);
+          if (base == 0) {
+            parked0[u] = uint32_t(T);
+            created0 |= made << u;
+          } else {
+            member_ids[base + u * nt + tid] = uint32_t(T) | (made << 31);
+          }
+          continue;
+        }
+        const uint32_t h = part_hash(key[u]);
+        const uint32_t step = (h >> 3) | 1u;
+        uint32_t s = h >> shift;
+        // crowded partition: a plain read answers for a key that is already there, and only an
+        // empty entry is worth an atomic
+        unsigned long long old = kPeek ? table[s] : kFreeEntry;
+        if (old == kFreeEntry) old = atomicCAS(&table[s], kFreeEntry, key[u]);
+        int rounds = 0;
+        while (int(old != kFreeEntry) & int(old != key[u]) & int(rounds < T)) {
+          s = (s + step) & mask;
+          old = kPeek ? table[s] : kFreeEntry;
+          if (old == kFreeEntry) old = atomicCAS(&table[s], kFreeEntry, key[u]);
+          ++rounds;
+        }
+        lost |= (old != kFreeEntry && old != key[u]);
+        const uint32_t made = old == kFreeEntry ? 1u : 0u;
         created += int(made);
         if (base == 0) {
-          parked0[u] = uint32_t(T);
+          parked0[u] = s;
           created0 |= made << u;
         } else {
-          member_ids[base + u * nt + tid] = uint32_t(T) | (made << 31);
+          member_ids[base + u * nt + tid] = s | (made << 31);
         }
-        continue;
-      }
-      const uint32_t h = part_hash(key[u]);
-      const uint32_t step = (h >> 3) | 1u;
-      uint32_t s = h >> shift;
-      unsigned long long old = atomicCAS(&table[s], kFreeEntry, key[u]);
-      int rounds = 0;
-      while (int(old != kFreeEntry) & int(old != key[u]) & int(rounds < T)) {
-        s = (s + step) & mask;
-        old = atomicCAS(&table[s], kFreeEntry, key[u]);
-        ++rounds;
-      }
-      lost |= (old != kFreeEntry && old != key[u]);
-      const uint32_t made = old == kFreeEntry ? 1u : 0u;
-      created += int(made);
-      if (base == 0) {
-        parked0[u] = s;
-        created0 |= made << u;
-      } else {
-        member_ids[base + u * nt + tid] = s | (made << 31);
       }
     }
+  };
+  if (crowded)
+    insert_members(std::true_type{});
+  else
+    insert_members(std::false_type{});
+  // A whole call that needs this order's ids nowhere (no later order is derived from them) and
+  // counts here can count by table entry: no ids, no second look into the table.
+  if (a.with_count && !((a.ids_wanted >> n) & 1)) {
+    const int distinct = block_sum(created, scan_scratch);  // (its barriers end the insertions)
+    if ((lost || distinct > kPartIdCap) && pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
+    if (tid == 0)
+      a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
+    // (table entry | sequence of the slot << 16) per member, as the counting expects it
+    for (int base = 0; base < members; base += kPartUnroll * nt) {
+      uint32_t k[kPartUnroll];
+#pragma unroll
+      for (int u = 0; u < kPartUnroll; ++u)
+        k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
+#pragma unroll
+      for (int u = 0; u < kPartUnroll; ++u) {
+        int f = 0;
+        for (int j = 0; j < pb.R; ++j)
+          f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
+        const int i = base + u * nt + tid;
+        if (base == 0)
+          parked0[u] = min(parked0[u], uint32_t(T)) | (uint32_t(f) << 16);
+        else if (i < members)
+          member_ids[i] = min(member_ids[i] & 0x7FFFFFFFu, uint32_t(T)) | (uint32_t(f) << 16);
+      }
+    }
+    const int part = count_clip_partition<true>(reinterpret_cast<uint32_t*>(smem), T + 1, a.words,
+                                                a.fields_per_word, pb.R, members, member_ids,
+                                                parked0);
+    const int clipped = block_sum(part, scan_scratch);
+    if (tid == 0) {
+      const int64_t stat = int64_t(g) * pb.N + n - 1;
+      if (clipped) atomicAdd(&a.st.clipped[stat], clipped);
+      if (distinct) atomicAdd(&a.st.distinct[stat], distinct);
+      if (p == 0) a.st.total[stat] = gi.start(1);
+    }
+    return;
   }
+
   // number the entries (any numbering that is dense and unique will do): the thread whose
   // compare-and-swap created an entry names it, from a block of ids its wavefront reserves
   uint32_t next = reserve_ids(created, next_id);
