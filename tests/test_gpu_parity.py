@@ -317,6 +317,19 @@ def test_partitions_with_more_references_than_counter_fields():
         check(w, syn.Run("exp"), "auto")
 
 
+def test_long_texts_with_skewed_token_frequencies():
+    # Zipf-distributed tokens: the most frequent token makes up a seventh of a text, so its
+    # unigram's partition holds several times the expected members (the crowded-partition code)
+    w = syn.long_form(B=2, L=60000)
+    group = np.concatenate([w.cand[0, :w.cand_len[0]], w.refs[0, 0, :w.ref_len[0, 0]]])
+    assert np.bincount(group).max() > 2 * 4096
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_partitions == 32
+    check(w, syn.Run("exp"), "auto")
+    check(w, syn.Run("add-k", 1.0), "global")
+
+
 def test_long_form_workload_at_full_size():
     """The long-generation workload bench.py --long-form times (128 groups of ~16 000 tokens, four
     partitions per group and order), every sentence against the oracle."""
