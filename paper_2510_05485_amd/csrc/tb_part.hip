@@ -413,13 +413,17 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartAr
 // words, zeroed here -- and clips: returns this thread's share of the sum over the ids of
 // min(candidate count, largest reference count).  member_ids[i] is member i's (id within the
 // partition | index of its sequence << 16); with kFirstRoundInRegs, first_round[u] holds it for
-// member u * nt + tid.  Contains barriers: call from all threads, after everyone's last use of
-// what `cnt` overlays.
-template <bool kFirstRoundInRegs>
+// member u * nt + tid.  With kSeqFromSlot the words hold only the id (bit 31 is ignored) and the
+// sequence is found from the member's slot number (member_slot[i], clamped to last_slot;
+// seq_end: lane j holds the end of sequence j).  Contains barriers: call from all threads,
+// after everyone's last use of what `cnt` overlays.
+template <bool kFirstRoundInRegs, bool kSeqFromSlot = false>
 __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
                                                     int fields_per_word, int R, int members,
                                                     const uint32_t* member_ids,
-                                                    const uint32_t (&first_round)[kPartUnroll]) {
+                                                    const uint32_t (&first_round)[kPartUnroll],
+                                                    const uint32_t* member_slot = nullptr,
+                                                    uint32_t last_slot = 0, int seq_end = 0) {
   const int nt = blockDim.x, tid = threadIdx.x;
   {
     uint4* c4 = reinterpret_cast<uint4*>(cnt);
@@ -439,9 +443,22 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
         id[u] = (kFirstRoundInRegs && base == 0)
                     ? first_round[u]
                     : member_ids[min(base + u * nt + tid, members - 1)];
+      uint32_t k[kSeqFromSlot ? kPartUnroll : 1];
+      if (kSeqFromSlot) {
+#pragma unroll
+        for (int u = 0; u < kPartUnroll; ++u)
+          k[kSeqFromSlot ? u : 0] =
+              min(member_slot[min(base + u * nt + tid, members - 1)], last_slot);
+      }
 #pragma unroll
       for (int u = 0; u < kPartUnroll; ++u) {
-        const int f = min(int(id[u] >> 16), R);
+        int f = 0;
+        if (kSeqFromSlot) {
+          for (int j = 0; j < R; ++j)
+            f += (int(k[kSeqFromSlot ? u : 0]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
+        } else {
+          f = min(int(id[u] >> 16), R);
+        }
         const uint32_t word = (id[u] & 0xFFFFu) | (uint32_t(f) << 16);
         id[u] &= 0xFFFFu;
         bool mine = base + u * nt + tid < members && id[u] < uint32_t(U);
@@ -670,27 +687,10 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
     if ((lost || distinct > kPartIdCap) && pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
     if (tid == 0)
       a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
-    // (table entry | sequence of the slot << 16) per member, as the counting expects it
-    for (int base = 0; base < members; base += kPartUnroll * nt) {
-      uint32_t k[kPartUnroll];
-#pragma unroll
-      for (int u = 0; u < kPartUnroll; ++u)
-        k[u] = min(member[min(base + u * nt + tid, members - 1)], last_slot);
-#pragma unroll
-      for (int u = 0; u < kPartUnroll; ++u) {
-        int f = 0;
-        for (int j = 0; j < pb.R; ++j)
-          f += (int(k[u]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
-        const int i = base + u * nt + tid;
-        if (base == 0)
-          parked0[u] = min(parked0[u], uint32_t(T)) | (uint32_t(f) << 16);
-        else if (i < members)
-          member_ids[i] = min(member_ids[i] & 0x7FFFFFFFu, uint32_t(T)) | (uint32_t(f) << 16);
-      }
-    }
-    const int part = count_clip_partition<true>(reinterpret_cast<uint32_t*>(smem), T + 1, a.words,
-                                                a.fields_per_word, pb.R, members, member_ids,
-                                                parked0);
+    // (the members' words hold their table entries; their sequences follow from their slots)
+    const int part = count_clip_partition<true, true>(
+        reinterpret_cast<uint32_t*>(smem), T + 1, a.words, a.fields_per_word, pb.R, members,
+        member_ids, parked0, member, last_slot, seq_end);
     const int clipped = block_sum(part, scan_scratch);
     if (tid == 0) {
       const int64_t stat = int64_t(g) * pb.N + n - 1;
