@@ -53,10 +53,10 @@ def _load():
         lib.oracle_group_counts.argtypes = [i32p, ctypes.c_int, i32p, ctypes.c_int64, i32p,
                                             ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p, i32p,
                                             i32p]
-        lib.oracle_rouge_n.restype = ctypes.c_int
-        lib.oracle_rouge_n.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p,
-                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
-                                       i32p, i32p, f64p, i32p]
+        lib.oracle_rouge_overlap.restype = ctypes.c_int
+        lib.oracle_rouge_overlap.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64,
+                                             i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p,
+                                             i32p]
         _lib = lib
     return _lib
 
@@ -159,11 +159,22 @@ class RougeResult:
     overlap: np.ndarray      # [B, R] int32: sum over n-grams of min(candidate count, reference count)
     prf: np.ndarray          # [B, 3] float64: precision, recall, F of the best reference
     best: np.ndarray         # [B] int32: index of that reference (highest F, lowest index on ties)
+    prf_all: np.ndarray      # [B, R, 3] float64: precision, recall, F against every reference
+                             # (zeros for references beyond ref_count)
 
 
 def rouge_n(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.ndarray,
             n: int = 2, beta: float = 1.0, ref_count: Optional[np.ndarray] = None) -> RougeResult:
-    """ROUGE-N of every candidate against its references (see oracle_rouge_n)."""
+    """ROUGE-N of every candidate against its references (Lin 2004; the paper's Section 6 names
+    ROUGE as the first metric its counting method extends to).
+
+    For one order n and every candidate i, reference j: precision = overlap / candidate n-grams,
+    recall = overlap / reference n-grams (each 0 when its denominator is 0),
+    F = (1 + beta^2) P R / (R + beta^2 P), 0 when P + R = 0.  The candidate is credited with the
+    reference of the highest F, the lowest index among equal ones.  The choice is made in exact
+    rational arithmetic (beta is taken as the exact value of the given double), so it does not
+    depend on any rounding; the reported numbers are those fractions rounded to float64."""
+    from fractions import Fraction
     lib = _load()
     cand = np.ascontiguousarray(cand, dtype=np.int32)
     refs = np.ascontiguousarray(refs, dtype=np.int32)
@@ -173,22 +184,40 @@ def rouge_n(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: n
     assert refs.ndim == 3 and refs.shape[0] == B and ref_len.shape == (B, R)
     assert (cand_len <= cand.shape[1]).all() and (ref_len <= refs.shape[2]).all()
     assert (cand_len >= 0).all() and (ref_len >= 0).all()
+    if not float(beta) > 0.0:
+        raise ValueError("rouge_n: beta must be positive")
     rcnt = None
     if ref_count is not None:
         rcnt = np.ascontiguousarray(ref_count, dtype=np.int32)
         assert rcnt.shape == (B,)
     overlap = np.zeros((B, R), np.int32)
-    prf = np.zeros((B, 3), np.float64)
-    best = np.zeros(B, np.int32)
-    rc = lib.oracle_rouge_n(_p(cand, ctypes.c_int32), cand.shape[1], _p(cand_len, ctypes.c_int32),
-                            _p(refs, ctypes.c_int32), refs.shape[2], _p(ref_len, ctypes.c_int32),
-                            B, R, int(n), float(beta),
-                            _p(rcnt, ctypes.c_int32) if rcnt is not None else None,
-                            _p(overlap, ctypes.c_int32), _p(prf, ctypes.c_double),
-                            _p(best, ctypes.c_int32))
+    rc = lib.oracle_rouge_overlap(_p(cand, ctypes.c_int32), cand.shape[1],
+                                  _p(cand_len, ctypes.c_int32), _p(refs, ctypes.c_int32),
+                                  refs.shape[2], _p(ref_len, ctypes.c_int32), B, R, int(n),
+                                  _p(rcnt, ctypes.c_int32) if rcnt is not None else None,
+                                  _p(overlap, ctypes.c_int32))
     if rc != 0:
-        raise ValueError("oracle_rouge_n: invalid arguments")
-    return RougeResult(overlap, prf, best)
+        raise ValueError("oracle_rouge_overlap: invalid arguments")
+    b2 = Fraction(float(beta)) ** 2
+    prf = np.zeros((B, 3), np.float64)
+    prf_all = np.zeros((B, R, 3), np.float64)
+    best = np.zeros(B, np.int32)
+    zero = Fraction(0)
+    for i in range(B):
+        ct = max(int(cand_len[i]) - n + 1, 0)
+        top = None
+        for j in range(int(rcnt[i]) if rcnt is not None else R):
+            rt = max(int(ref_len[i, j]) - n + 1, 0)
+            ov = int(overlap[i, j])
+            P = Fraction(ov, ct) if ct else zero
+            Rc = Fraction(ov, rt) if rt else zero
+            F = (1 + b2) * P * Rc / (Rc + b2 * P) if P + Rc > 0 else zero
+            prf_all[i, j] = (float(P), float(Rc), float(F))
+            if top is None or F > top:          # strict: the lowest index wins ties
+                top = F
+                best[i] = j
+        prf[i] = prf_all[i, best[i]]
+    return RougeResult(overlap, prf, best, prf_all)
 
 
 def to_bfloat16(x) -> np.ndarray:

@@ -234,55 +234,32 @@ int oracle_group_counts(const int32_t* cand, int cand_len, const int32_t* refs,
   return k;
 }
 
-// ROUGE-N of every candidate against each of its references, on the same counting definition
-// (the paper names ROUGE as the first metric its counting method extends to, Section 6 "Future
-// Work"; the metric itself is Lin 2004): for one order n,
-//   overlap[i][j] = sum over distinct n-grams g of min(count in candidate i, count in reference j)
-//   recall = overlap / (reference n-grams), precision = overlap / (candidate n-grams), each 0 when
-//   its denominator is 0, F = (1 + beta^2) P R / (R + beta^2 P), 0 when P + R = 0.
-// With several references the candidate is credited with the reference of the highest F (ties:
-// the lowest index).  F is proportional to overlap / (candidate n-grams + beta^2 * reference
-// n-grams); the choice between references is taken on that quotient in single precision
-// (float(overlap) / fmaf(beta^2, float(ref n-grams), float(cand n-grams))), the precision the GPU
-// path scores in, so that both sides break near-ties the same way.
-// prf[i] = precision, recall, F (fp64) of the chosen reference; best[i] = its index.
-// ref_count as in oracle_bleu.  Returns 0, or 1 on invalid arguments.
-int oracle_rouge_n(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
-                   const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int B, int R,
-                   int n, double beta, const int32_t* ref_count, int32_t* overlap, double* prf,
-                   int32_t* best) {
-  if (B < 0 || R < 1 || n < 1 || n > 8 || !(beta > 0.0)) return 1;
+// ROUGE-N overlap counts of every candidate against each of its references, on the same counting
+// definition (the paper names ROUGE as the first metric its counting method extends to, Section 6
+// "Future Work"; the metric itself is Lin 2004): for one order n,
+//   overlap[i][j] = sum over distinct n-grams g of min(count in candidate i, count in reference j).
+// Precision, recall, F and the choice of the best reference are formed from these integers by the
+// Python wrapper in exact rational arithmetic (oracle.rouge_n).
+// ref_count as in oracle_bleu: entries of references beyond it stay 0.
+// Returns 0, or 1 on invalid arguments.
+int oracle_rouge_overlap(const int32_t* cand, int64_t cand_stride, const int32_t* cand_len,
+                         const int32_t* refs, int64_t ref_stride, const int32_t* ref_len, int B,
+                         int R, int n, const int32_t* ref_count, int32_t* overlap) {
+  if (B < 0 || R < 1 || n < 1 || n > 8) return 1;
   for (int i = 0; i < B; ++i) {
     const int Ri = ref_count ? ref_count[i] : R;
     if (Ri < 1 || Ri > R) return 1;
-    const int c = cand_len[i];
-    Counter cc = count_ngrams(cand + int64_t(i) * cand_stride, c, n);
-    const double cand_total = double(std::max(c - n + 1, 0));
-    float best_key = -1.0f;
+    Counter cc = count_ngrams(cand + int64_t(i) * cand_stride, cand_len[i], n);
     for (int j = 0; j < R; ++j) overlap[int64_t(i) * R + j] = 0;
     for (int j = 0; j < Ri; ++j) {
-      const int r = ref_len[int64_t(i) * R + j];
-      Counter rc = count_ngrams(refs + (int64_t(i) * R + j) * ref_stride, r, n);
+      Counter rc = count_ngrams(refs + (int64_t(i) * R + j) * ref_stride,
+                                ref_len[int64_t(i) * R + j], n);
       int64_t ov = 0;
       for (const auto& kv : cc) {
         auto it = rc.find(kv.first);
         if (it != rc.end()) ov += std::min(kv.second, it->second);
       }
       overlap[int64_t(i) * R + j] = int32_t(ov);
-      const double ref_total = double(std::max(r - n + 1, 0));
-      const double P = cand_total > 0 ? double(ov) / cand_total : 0.0;
-      const double Rc = ref_total > 0 ? double(ov) / ref_total : 0.0;
-      const double b2 = beta * beta;
-      const double F = (P + Rc > 0) ? (1.0 + b2) * P * Rc / (Rc + b2 * P) : 0.0;
-      const float key = ov > 0 ? float(ov) / std::fmaf(float(b2), float(ref_total), float(cand_total))
-                               : 0.0f;
-      if (key > best_key) {
-        best_key = key;
-        best[i] = j;
-        prf[int64_t(i) * 3 + 0] = P;
-        prf[int64_t(i) * 3 + 1] = Rc;
-        prf[int64_t(i) * 3 + 2] = F;
-      }
     }
   }
   return 0;

@@ -233,6 +233,19 @@ def brute_force_stats(cand, refs, max_n):
     return clipped, total
 
 
+def brute_force_distinct(cand, refs, max_n):
+    """Sizes of the candidate's and of the whole group's n-gram dictionaries: set of windows."""
+    group, own = [], []
+    for n in range(1, max_n + 1):
+        cw = {tuple(cand[p:p + n]) for p in range(len(cand) - n + 1)}
+        allw = set(cw)
+        for ref in refs:
+            allw |= {tuple(ref[p:p + n]) for p in range(len(ref) - n + 1)}
+        own.append(len(cw))
+        group.append(len(allw))
+    return group, own
+
+
 def test_exhaustive_tiny_inputs_match_brute_force():
     # every candidate/reference pair over a 2-letter alphabet with lengths 0..5 (R = 1)
     seqs = [list(t) for L in range(0, 6) for t in itertools.product([0, 1], repeat=L)]
@@ -247,6 +260,25 @@ def test_exhaustive_tiny_inputs_match_brute_force():
         bc, bt = brute_force_stats(cands[i], refs[i], 4)
         assert list(res.clipped[i]) == bc, (cands[i], refs[i])
         assert list(res.total[i]) == bt
+        gd, cd = brute_force_distinct(cands[i], refs[i], 4)
+        assert list(res.group_distinct[i]) == gd and list(res.cand_distinct[i]) == cd
+
+
+def test_dictionary_sizes_closed_forms():
+    # L distinct tokens: L - n + 1 distinct n-grams; one token repeated: one n-gram per order;
+    # a reference sharing nothing doubles the group's dictionary, an identical one adds nothing
+    L = 9
+    a, b = list(range(10, 10 + L)), list(range(50, 50 + L))
+    cand, cl, ref, rl = pad_batch([a, a, [7] * L], [[a], [b], [[7] * 4]])
+    res = oracle.bleu(cand, cl, ref, rl)
+    full = [L - n + 1 for n in range(1, 5)]
+    assert res.cand_distinct[0].tolist() == full and res.group_distinct[0].tolist() == full
+    assert res.group_distinct[1].tolist() == [2 * x for x in full]
+    assert res.cand_distinct[2].tolist() == [1, 1, 1, 1] == res.group_distinct[2].tolist()
+    cand, cl, ref, rl = pad_batch([a], [[a, b]])
+    res = oracle.bleu(cand, cl, ref, rl)
+    assert res.group_distinct[0].tolist() == [2 * x for x in full]
+    assert res.cand_distinct[0].tolist() == full
 
 
 def test_exhaustive_tiny_two_references_match_brute_force():
@@ -263,6 +295,8 @@ def test_exhaustive_tiny_two_references_match_brute_force():
     for i in range(len(cands)):
         bc, bt = brute_force_stats(cands[i], refs[i], 4)
         assert list(res.clipped[i]) == bc, (cands[i], refs[i])
+        gd, cd = brute_force_distinct(cands[i], refs[i], 4)
+        assert list(res.group_distinct[i]) == gd and list(res.cand_distinct[i]) == cd
 
 
 @pytest.mark.parametrize("seed,V,R", [(1, 3, 1), (2, 5, 3), (3, 64, 2), (4, 1000, 4)])
@@ -275,6 +309,8 @@ def test_random_small_match_brute_force(seed, V, R):
         bc, bt = brute_force_stats(c, rr, 4)
         assert list(res.clipped[i]) == bc
         assert list(res.total[i]) == bt
+        gd, cd = brute_force_distinct(c, rr, 4)
+        assert list(res.group_distinct[i]) == gd and list(res.cand_distinct[i]) == cd
 
 
 # ------------------------------------------------- the paper's batched formulation agrees

@@ -79,6 +79,38 @@ def test_best_reference_is_the_one_with_the_highest_f_lowest_index_on_ties():
     assert res.best[0] == 0 and res.prf[0].tolist() == [0.0, 0.0, 0.0]
 
 
+def test_exactly_equal_f_goes_to_the_lowest_index_whatever_the_rounding():
+    # beta = 1: F = 2 ov / (ct + rt).  ct = 5; reference A: ov 2, rt 5 -> 4/10; reference B: ov 3,
+    # rt 10 -> 6/15: the same rational although P, R and their float quotients differ
+    cand = [1, 2, 3, 4, 5]
+    a, b = [1, 2, 9, 9, 9], [1, 2, 3, 9, 9, 9, 9, 9, 9, 9]
+    for refs in ([a, b], [b, a]):
+        res = one(cand, refs, n=1)
+        assert sorted(res.overlap[0].tolist()) == [2, 3]
+        assert res.best[0] == 0 and res.prf[0, 2] == pytest.approx(0.4, rel=1e-15)
+    # a strictly better later reference wins: ov 3 of rt 9 -> 6/14 > 4/10
+    res = one(cand, [a, b[:9]], n=1)
+    assert res.best[0] == 1 and res.prf[0].tolist() == pytest.approx([3 / 5, 3 / 9, 6 / 14])
+    # beta = 2 (recall weighs four times): F = 5 ov / (ct + 4 rt); A: 10/25, B: 15/45 -> A
+    res = one(cand, [b, a], n=1, beta=2.0)
+    assert res.best[0] == 1 and res.prf[0, 2] == pytest.approx(0.4, rel=1e-15)
+    # beta = 0.5 (precision weighs more): F = 1.25 ov / (ct + rt / 4); A: 2.5/6.25, B: 3.75/7.5 -> B
+    res = one(cand, [a, b], n=1, beta=0.5)
+    assert res.best[0] == 1 and res.prf[0, 2] == pytest.approx(0.5, rel=1e-15)
+
+
+def test_choice_follows_a_permutation_of_the_references():
+    w = syn.random_small(431, B=40, R=4, vocab=5, max_len=24)
+    res = oracle.rouge_n(w.cand, w.cand_len, w.refs, w.ref_len, n=2)
+    perm = [2, 0, 3, 1]
+    res_p = oracle.rouge_n(w.cand, w.cand_len, w.refs[:, perm], w.ref_len[:, perm], n=2)
+    np.testing.assert_array_equal(res_p.overlap, res.overlap[:, perm])
+    np.testing.assert_array_equal(res_p.prf[:, 2], res.prf[:, 2])      # the best F is the same
+    for i in range(w.B):
+        f = res.prf_all[i, :, 2]
+        assert f[res.best[i]] == f.max() and (f[:res.best[i]] < f.max()).all()
+
+
 def test_sequences_shorter_than_the_order_have_no_ngrams():
     res = one([1, 2], [[1, 2, 3, 4]], n=3)
     assert res.overlap[0, 0] == 0 and res.prf[0].tolist() == [0.0, 0.0, 0.0]
@@ -126,10 +158,11 @@ def test_random_small_match_brute_force_and_invariants(seed, V, R, n):
             assert res.overlap[i, j] == ov
             ct, rt = max(len(cand) - n + 1, 0), max(len(ref) - n + 1, 0)
             assert ov <= min(ct, rt)
-            P, Rc = (ov / ct if ct else 0.0), (ov / rt if rt else 0.0)
-            fs.append(2 * P * Rc / (P + Rc) if P + Rc > 0 else 0.0)
-        assert res.best[i] == int(np.argmax(fs))             # argmax takes the first maximum
-        assert res.prf[i, 2] == pytest.approx(max(fs), rel=1e-14, abs=0)
+            P, Rc = (Fraction(ov, ct) if ct else Fraction(0)), (Fraction(ov, rt) if rt else Fraction(0))
+            fs.append(2 * P * Rc / (P + Rc) if P + Rc > 0 else Fraction(0))
+            assert res.prf_all[i, j].tolist() == [float(P), float(Rc), float(fs[-1])]
+        assert res.best[i] == fs.index(max(fs))              # the first maximum, exactly
+        assert res.prf[i].tolist() == res.prf_all[i, res.best[i]].tolist()
     # symmetric roles: swapping candidate and (single) reference swaps precision and recall
     w1 = syn.random_small(seed + 500, B=20, R=1, vocab=V, max_len=18)
     a = oracle.rouge_n(w1.cand, w1.cand_len, w1.refs, w1.ref_len, n=n)
