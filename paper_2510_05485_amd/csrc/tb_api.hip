@@ -1,8 +1,55 @@
 // C-ABI dispatcher: argument validation, workspace carving, path selection, kernel launches.
 // Nothing here allocates, synchronises or keeps state between calls.
+#include <atomic>
 #include <cstring>
+#include <mutex>
 
 #include "tb_kernels.h"
+
+namespace tb {
+
+// The only process-wide state of the library: which kernels already had their dynamic-LDS limit
+// raised on which device (a cache of an idempotent runtime setting, invisible to callers).
+hipError_t grant_dynamic_lds(const void* kernel, size_t bytes) {
+  struct Grant {
+    const void* kernel;
+    int device;
+    std::atomic<size_t> bytes;
+  };
+  constexpr int kMaxGrants = 512;
+  static Grant grants[kMaxGrants];
+  static std::atomic<int> count{0};
+  static std::mutex mu;
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  // lock-free look-up of what earlier calls published (entries are immutable once counted,
+  // except `bytes`, which only grows under the lock; a stale smaller value just takes the lock)
+  const int seen = count.load(std::memory_order_acquire);
+  for (int i = 0; i < seen; ++i)
+    if (grants[i].kernel == kernel && grants[i].device == device &&
+        grants[i].bytes.load(std::memory_order_relaxed) >= bytes)
+      return hipSuccess;
+  std::lock_guard<std::mutex> lock(mu);
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes));
+  if (e != hipSuccess) return e;
+  const int n = count.load(std::memory_order_relaxed);
+  for (int i = 0; i < n; ++i)
+    if (grants[i].kernel == kernel && grants[i].device == device) {
+      if (grants[i].bytes.load(std::memory_order_relaxed) < bytes)
+        grants[i].bytes.store(bytes, std::memory_order_relaxed);
+      return hipSuccess;
+    }
+  if (n < kMaxGrants) {  // a full table only costs the attribute call again next time
+    grants[n].kernel = kernel;
+    grants[n].device = device;
+    grants[n].bytes.store(bytes, std::memory_order_relaxed);
+    count.store(n + 1, std::memory_order_release);
+  }
+  return hipSuccess;
+}
+
+}  // namespace tb
 
 namespace {
 
@@ -204,7 +251,7 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
             const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B, int32_t R,
             const tb_config_t* cfg, void* out_bleu, const tb_stats_t* stats, void* workspace,
             size_t workspace_bytes, void* hip_stream, bool corpus) {
-  Call c;
+  Call c{};
   int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, true, TB_PATH_AUTO, &c);
   if (rc != TB_OK || B == 0) return rc;
@@ -234,7 +281,7 @@ extern "C" {
 
 size_t tensorbleu_workspace_bytes(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
                                   const tb_config_t* cfg) {
-  Plans p;
+  Plans p{};
   if (make_plans(B, R, cand_stride, ref_stride, cfg, &p) != TB_OK) return 0;
   return p.layout.bytes;
 }
@@ -242,7 +289,7 @@ size_t tensorbleu_workspace_bytes(int32_t B, int32_t R, int64_t cand_stride, int
 int tensorbleu_workspace_layout(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
                                 const tb_config_t* cfg, tb_layout_t* layout) {
   if (!layout) return TB_ERR_INVALID_ARG;
-  Plans p;
+  Plans p{};  // zeroed: on an invalid argument the caller reads an all-zero layout
   int rc = make_plans(B, R, cand_stride, ref_stride, cfg, &p);
   *layout = p.layout;
   return rc;
@@ -270,7 +317,7 @@ int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len
                   int32_t R, const tb_config_t* cfg, void* out_prf, int32_t* overlap,
                   int32_t* best_ref, const tb_stats_t* stats, void* workspace,
                   size_t workspace_bytes, void* hip_stream) {
-  Call c;
+  Call c{};
   int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, true, TB_PATH_FUSED, &c);
   if (rc != TB_OK || B == 0) return rc;
@@ -296,7 +343,7 @@ int tensorbleu_pack(const void* cand, int64_t cand_stride, const int32_t* cand_l
                     const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
                     int32_t R, const tb_config_t* cfg, const tb_stats_t* stats, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
-  Call c;
+  Call c{};
   int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, true, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
@@ -307,7 +354,7 @@ int tensorbleu_dictionary(const int32_t* cand_len, const int32_t* ref_len, int64
                           int64_t ref_stride, int32_t B, int32_t R, const tb_config_t* cfg,
                           const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                           void* hip_stream) {
-  Call c;
+  Call c{};
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
@@ -318,7 +365,7 @@ int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64
                           int64_t ref_stride, int32_t B, int32_t R, const tb_config_t* cfg,
                           const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                           void* hip_stream) {
-  Call c;
+  Call c{};
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
@@ -329,7 +376,7 @@ int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t
                         int64_t cand_stride, int64_t ref_stride, const tb_config_t* cfg,
                         int32_t corpus, void* out_bleu, const tb_stats_t* stats, void* workspace,
                         size_t workspace_bytes, void* hip_stream) {
-  Call c;
+  Call c{};
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;

@@ -440,9 +440,8 @@ void fused_kernel(FusedArgs a) {
 template <typename TokT, int SITEMS, bool ROUGE>
 hipError_t launch_fused_mode(const FusedArgs& a, const FusedPlan& plan, int blocks,
                              hipStream_t s) {
-  hipError_t e =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(fused_kernel<TokT, SITEMS, ROUGE>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.lds_bytes));
+  hipError_t e = grant_dynamic_lds(
+      reinterpret_cast<const void*>(fused_kernel<TokT, SITEMS, ROUGE>), plan.lds_bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((fused_kernel<TokT, SITEMS, ROUGE>), dim3(blocks), dim3(plan.threads),
                      plan.lds_bytes, s, a);

@@ -403,8 +403,7 @@ template <typename Kernel, typename ArgT>
 hipError_t launch_with_lds(Kernel kernel, const ArgT& a, int64_t blocks, int threads, size_t lds,
                            hipStream_t s) {
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+  hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(kernel), lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(uint32_t(blocks)), dim3(threads), lds, s, a);
   return hipGetLastError();

@@ -5,6 +5,11 @@
 
 namespace tb {
 
+// Raises a kernel's dynamic-LDS limit to `bytes` (hipFuncSetAttribute) unless an earlier launch
+// on the same device already raised it at least that far: the attribute call costs a few
+// microseconds, which matters for calls that take ten.  `kernel` is the host-side kernel symbol.
+hipError_t grant_dynamic_lds(const void* kernel, size_t bytes);
+
 // Resolved pointers into the caller's workspace for the GLOBAL path.
 struct GlobalWs {
   void* keys[8];      // packed keys per order, B * group_cap entries of 8 or 16 bytes

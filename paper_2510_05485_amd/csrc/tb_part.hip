@@ -906,8 +906,8 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, bool whole_call, hipStream_t s) {
   const bool with_count = whole_call && plan.count_in_dictionary;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_dictionary_kernel),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.dict_lds));
+  hipError_t e =
+      grant_dynamic_lds(reinterpret_cast<const void*>(part_dictionary_kernel), plan.dict_lds);
   if (e != hipSuccess) return e;
   // one launch for the orders with 8-byte packed keys, then one per order with 16-byte keys in
   // ascending order (each is keyed by the ids of the order below it)
@@ -962,8 +962,7 @@ hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const P
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(part_count_kernel),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, int(plan.count_lds));
+  e = grant_dynamic_lds(reinterpret_cast<const void*>(part_count_kernel), plan.count_lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(part_count_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),
                      plan.count_lds, s, a);

@@ -45,8 +45,9 @@ def path_supported(w, path, max_n=4):
     cfg = tb.make_config(max_n=max_n, vocab_size=w.vocab, path="auto")
     lay = tb.binding.tb_layout_t()
     import ctypes
-    tb.load_library().tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2],
-                                                  ctypes.byref(cfg), ctypes.byref(lay))
+    rc = tb.load_library().tensorbleu_workspace_layout(
+        w.B, w.R, w.cand.shape[1], w.refs.shape[2], ctypes.byref(cfg), ctypes.byref(lay))
+    assert rc in (0, 3), rc       # ok, or the forced path does not support the shape
     return bool(lay.fused_ok if path == "fused" else lay.global_ok)
 
 
