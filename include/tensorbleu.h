@@ -44,7 +44,9 @@ typedef enum {
   TB_ERR_INVALID_ARG = 1, /* NULL required pointer, B < 0, R < 1, max_n outside 1..8, bad stride */
   TB_ERR_WORKSPACE = 2,   /* workspace NULL, misaligned (256 B) or smaller than workspace_bytes */
   TB_ERR_UNSUPPORTED = 3, /* shape outside what the kernels handle (see tensorbleu_workspace_layout) */
-  TB_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed */
+  TB_ERR_HIP = 4,         /* a HIP runtime call or kernel launch failed */
+  TB_ERR_STATIC_SCRATCH = 5 /* tensorbleu_sentence_static: the problem needs more scratch memory
+                             than the library's built-in buffer holds */
 } tb_status_t;
 
 /* Smoothing of the modified precisions p_n (paper Section 3.4 names 'floor', 'add-k', 'exp'
@@ -180,6 +182,27 @@ int tensorbleu_corpus(const void* cand, int64_t cand_stride, const int32_t* cand
                       int32_t B, int32_t R, const tb_config_t* cfg, void* out_bleu,
                       const tb_stats_t* stats, void* workspace, size_t workspace_bytes,
                       void* hip_stream);
+
+/* tensorbleu_sentence for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs and error behaviour as tensorbleu_sentence, minus the workspace: the
+ * intermediates (integer statistics the caller did not ask for; on the GLOBAL path also keys,
+ * ids and tables) live in a buffer of tensorbleu_static_scratch_bytes() = 4 MiB that is part of
+ * the library's device code, one copy per GPU, held until the process ends.  The call allocates
+ * nothing and frees nothing.  A problem whose workspace (tensorbleu_workspace_bytes for the same
+ * arguments) exceeds that size returns TB_ERR_STATIC_SCRATCH before any work is enqueued: the
+ * headline shape on the FUSED path needs 25 KB, B = 65 536 candidates at N = 4 about 3.3 MB.
+ * All calls on one GPU share that GPU's buffer, which keeps the last call's bytes (no kernel
+ * relies on its contents): calls that may overlap in time on one GPU - different streams, or
+ * several host threads - race and must be serialised by the caller; calls on one stream are
+ * ordered and safe. */
+int tensorbleu_sentence_static(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                               const void* refs, int64_t ref_stride, const int32_t* ref_len,
+                               int32_t B, int32_t R, const tb_config_t* cfg, void* out_bleu,
+                               const tb_stats_t* stats, void* hip_stream);
+
+/* Size of the built-in scratch buffer of tensorbleu_sentence_static (host function). */
+size_t tensorbleu_static_scratch_bytes(void);
 
 /* ROUGE-N on the same n-gram counting core (the paper's Section 6 names ROUGE as the first
  * metric the method extends to; the metric is Lin 2004).  For the single order n = cfg->max_n

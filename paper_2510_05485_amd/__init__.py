@@ -7,7 +7,8 @@ from .binding import (  # noqa: F401
     LIB_PATH, TB_DEV_LENGTH_RANGE, TB_DEV_TABLE_OVERFLOW, TB_DEV_TOKEN_RANGE, Stats, TensorBLEUError, allocate_workspace, load_library, make_config,
     tensorbleu_corpus, tensorbleu_count_clip, tensorbleu_dictionary, tensorbleu_finalize,
     tensorbleu_pack, tensorbleu_sentence, tensorbleu_status_string, tensorbleu_workspace_bytes,
-    tensorbleu_workspace_layout, tensorrouge_n,
+    tensorbleu_workspace_layout, tensorrouge_n, tensorbleu_sentence_static,
+    tensorbleu_static_scratch_bytes,
 )
 from .api import (  # noqa: F401
     BleuScorer, corpus_bleu, lengths_from_padding, pad_references, rouge_n, sentence_bleu,

@@ -26,6 +26,7 @@ EXPORTS = [
     "tensorbleu_workspace_bytes", "tensorbleu_workspace_layout", "tensorbleu_sentence",
     "tensorbleu_corpus", "tensorbleu_pack", "tensorbleu_dictionary", "tensorbleu_count_clip",
     "tensorbleu_finalize", "tensorbleu_status_string", "tensorrouge_n",
+    "tensorbleu_sentence_static", "tensorbleu_static_scratch_bytes",
 ]
 
 
@@ -83,6 +84,10 @@ def load_library() -> ctypes.CDLL:
     lib.tensorbleu_sentence.argtypes = full
     lib.tensorbleu_corpus.restype = ctypes.c_int
     lib.tensorbleu_corpus.argtypes = full
+    lib.tensorbleu_sentence_static.restype = ctypes.c_int
+    lib.tensorbleu_sentence_static.argtypes = [vp, i64, vp, vp, i64, vp, i32, i32, cfgp, vp, stp, vp]
+    lib.tensorbleu_static_scratch_bytes.restype = sz
+    lib.tensorbleu_static_scratch_bytes.argtypes = []
     lib.tensorrouge_n.restype = ctypes.c_int
     lib.tensorrouge_n.argtypes = [vp, i64, vp, vp, i64, vp, i32, i32, cfgp, vp, vp, vp, stp, vp, sz, vp]
     lib.tensorbleu_pack.restype = ctypes.c_int
@@ -261,6 +266,26 @@ def tensorbleu_sentence(cand, cand_len, refs, ref_len, cfg: tb_config_t,
     out = _score_out(out, cfg, (cand.shape[0],), cand.device)
     return _full("tensorbleu_sentence", cand, cand_len, refs, ref_len, cfg, out, stats,
                  workspace, stream)
+
+
+def tensorbleu_static_scratch_bytes() -> int:
+    return int(load_library().tensorbleu_static_scratch_bytes())
+
+
+def tensorbleu_sentence_static(cand, cand_len, refs, ref_len, cfg: tb_config_t,
+                               out: torch.Tensor, stats: Optional[Stats] = None,
+                               stream=None) -> torch.Tensor:
+    """tensorbleu_sentence without a workspace: the library's built-in scratch buffer is used and
+    nothing is allocated (`out` must be brought by the caller for the same reason)."""
+    out = _score_out(out, cfg, (cand.shape[0],), cand.device)
+    b = _batch(cand, cand_len, refs, ref_len, cfg)
+    st = stats.as_struct() if stats is not None else None
+    rc = load_library().tensorbleu_sentence_static(
+        b.cand.data_ptr(), b.cand_stride, b.cand_len.data_ptr(), b.refs.data_ptr(), b.ref_stride,
+        b.ref_len.data_ptr(), b.B, b.R, ctypes.byref(cfg), out.data_ptr(),
+        ctypes.byref(st) if st is not None else None, _stream_ptr(stream))
+    _check(rc, "tensorbleu_sentence_static")
+    return out
 
 
 def tensorbleu_corpus(cand, cand_len, refs, ref_len, cfg: tb_config_t,

@@ -6,9 +6,16 @@
 
 #include "tb_kernels.h"
 
+// Scratch memory of tensorbleu_sentence_static: a device array that is part of the loaded code
+// object, so that entry point never allocates.  Every GPU the library runs on holds its own copy
+// at its own address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the address that call returns, never the name.
+constexpr size_t kStaticScratchBytes = size_t(4) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace tb {
 
-// The only process-wide state of the library: which kernels already had their dynamic-LDS limit
+// Process-wide state of the library (besides the static scratch buffer's address): which kernels already had their dynamic-LDS limit
 // raised on which device (a cache of an idempotent runtime setting, invisible to callers).
 hipError_t grant_dynamic_lds(const void* kernel, size_t bytes) {
   struct Grant {
@@ -54,6 +61,32 @@ hipError_t grant_dynamic_lds(const void* kernel, size_t bytes) {
 namespace {
 
 using namespace tb;
+
+// Device address of `scratch` on the current device: looked up once per device (with that device
+// current) and kept.
+hipError_t static_scratch_address(void** out) {
+  constexpr int kMaxDevices = 64;
+  static void* address[kMaxDevices];
+  static std::atomic<bool> known[kMaxDevices];
+  static std::mutex mu;
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!known[device].load(std::memory_order_acquire)) {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!known[device].load(std::memory_order_relaxed)) {
+      void* ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return hipErrorInvalidSymbol;
+      address[device] = ptr;
+      known[device].store(true, std::memory_order_release);
+    }
+  }
+  *out = address[device];
+  return hipSuccess;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
@@ -386,6 +419,24 @@ int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t
                                 c.stream));
 }
 
+size_t tensorbleu_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int tensorbleu_sentence_static(const void* cand, int64_t cand_stride, const int32_t* cand_len,
+                               const void* refs, int64_t ref_stride, const int32_t* ref_len,
+                               int32_t B, int32_t R, const tb_config_t* cfg, void* out_bleu,
+                               const tb_stats_t* stats, void* hip_stream) {
+  // size check first: a problem beyond the built-in buffer is refused before anything else
+  Plans p{};
+  int rc = make_plans(B, R, cand_stride, ref_stride, cfg, &p);
+  if (rc != TB_OK) return rc;
+  if (p.layout.bytes > kStaticScratchBytes) return TB_ERR_STATIC_SCRATCH;
+  if (B == 0) return TB_OK;
+  void* scratch_ptr = nullptr;
+  if (static_scratch_address(&scratch_ptr) != hipSuccess) return TB_ERR_HIP;
+  return run_all(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, out_bleu,
+                 stats, scratch_ptr, kStaticScratchBytes, hip_stream, false);
+}
+
 const char* tensorbleu_status_string(int status) {
   switch (status) {
     case TB_OK: return "ok";
@@ -393,6 +444,8 @@ const char* tensorbleu_status_string(int status) {
     case TB_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case TB_ERR_UNSUPPORTED: return "shape not supported by the selected path";
     case TB_ERR_HIP: return "HIP runtime error";
+    case TB_ERR_STATIC_SCRATCH:
+      return "problem needs more scratch memory than the built-in static buffer holds";
     default: return "unknown status";
   }
 }
