@@ -133,6 +133,8 @@ typedef struct tb_layout {
                               dictionary (ids are below id_stride; dense 0..distinct-1 unless
                               global_partitions > 0) */
   size_t  clipped_off, total_off, closest_off, distinct_off; /* int32 [B,N],[B,N],[B],[B,N] */
+  size_t  cand_distinct_off; /* int32 [B,N]: distinct n-grams of the candidate alone (GLOBAL path,
+                              written by the dictionary pass when global_candidate_first is set) */
   size_t  corpus_off;      /* int64 [2N+2] */
   size_t  bytes;           /* total workspace size for this path */
   int32_t fused_ok;        /* 1 if the FUSED path supports this shape */
@@ -146,6 +148,11 @@ typedef struct tb_layout {
                               and 8-byte key) */
   int64_t id_stride;       /* id range per group on the GLOBAL path: group_cap, or more when
                               global_partitions > 0 */
+  int32_t global_candidate_first; /* 1: the dictionary pass numbers the candidate's n-grams first:
+                              ids below cand_distinct[g][n] are exactly the n-grams that occur
+                              in candidate g (the count/clip pass then keeps counters for those
+                              only).  Set for groups within one LDS table whose (prefix id, last
+                              token) keys fit 31 bits: ceil(log2(group_cap)) + bits <= 31 */
   int32_t global_partitions; /* P > 0: groups beyond the single-table LDS kernels (12 288 slots)
                               but within 2 097 152 are handled by P workgroups per (group, order),
                               each keeping one hash partition of the dictionary in LDS; ids are

@@ -50,10 +50,12 @@ class tb_layout_t(ctypes.Structure):
                 ("keys_off", ctypes.c_size_t * 8), ("inv_off", ctypes.c_size_t * 8),
                 ("clipped_off", ctypes.c_size_t), ("total_off", ctypes.c_size_t),
                 ("closest_off", ctypes.c_size_t), ("distinct_off", ctypes.c_size_t),
+                ("cand_distinct_off", ctypes.c_size_t),
                 ("corpus_off", ctypes.c_size_t), ("bytes", ctypes.c_size_t),
                 ("fused_ok", ctypes.c_int32), ("global_ok", ctypes.c_int32),
                 ("global_tables_in_hbm", ctypes.c_int32), ("tables_off", ctypes.c_size_t),
-                ("id_stride", ctypes.c_int64), ("global_partitions", ctypes.c_int32)]
+                ("id_stride", ctypes.c_int64), ("global_candidate_first", ctypes.c_int32),
+                ("global_partitions", ctypes.c_int32)]
 
 
 class TensorBLEUError(RuntimeError):

@@ -115,6 +115,8 @@ struct Plans {
   FusedPlan fused;
   BigPlan big;
   PartPlan part;
+  HierPlan hier;
+  bool use_hier;  // GLOBAL path on the hierarchical-key kernels (a subset of the LDS shapes)
   bool use_part;  // GLOBAL path with P workgroups per (group, order), tables split over their LDS
   bool use_big;   // GLOBAL path with tables in the workspace (group too large for that, too)
 };
@@ -137,6 +139,7 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   const bool lds_ok = global_n &&
                       plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
                       plan_count(L.group_cap, cand_stride, ref_stride, R, &p->count);
+  p->use_hier = lds_ok && plan_hier(L.group_cap, cand_stride, ref_stride, R, N, L.bits, &p->hier);
   p->use_part = global_n && !lds_ok &&
                 plan_part(L.group_cap, cand_stride, ref_stride, R, N, L.key_bytes, &p->part);
   p->use_big = global_n && !lds_ok && !p->use_part && plan_big(L.group_cap, N, &p->big);
@@ -146,6 +149,7 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   L.global_ok = ids_fit && (lds_ok || p->use_part || p->use_big);
   L.global_tables_in_hbm = p->use_big ? 1 : 0;
   L.global_partitions = p->use_part ? (1 << p->part.log2_parts) : 0;
+  L.global_candidate_first = p->use_hier ? 1 : 0;
   L.fused_ok = plan_fused(cand_stride, ref_stride, R, N, L.bits, &p->fused);
   int path = cfg->force_path;
   if (path == TB_PATH_AUTO) path = L.fused_ok ? TB_PATH_FUSED : TB_PATH_GLOBAL;
@@ -159,6 +163,7 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   L.total_off = off;    off = align_up(off + bn * 4);
   L.closest_off = off;  off = align_up(off + size_t(B) * 4);
   L.distinct_off = off; off = align_up(off + bn * 4);
+  L.cand_distinct_off = off; off = align_up(off + bn * 4);
   L.corpus_off = off;   off = align_up(off + 18 * 8);
   if (path == TB_PATH_GLOBAL) {
     const size_t slots = size_t(B) * size_t(L.group_cap);
@@ -168,7 +173,7 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
     }
     for (int n = 0; n < N; ++n) {
       L.inv_off[n] = off;
-      off = align_up(off + slots * 4);
+      off = align_up(off + slots * 4 + 16);  // 16 spare bytes: ids are also read four at a time
     }
     if (p->use_big) {
       L.tables_off = off;
@@ -188,6 +193,7 @@ struct Call {
   Problem pb;
   GlobalWs ws;
   StatPtrs st;
+  int32_t* cand_distinct;  // [B, N] in the workspace: dictionary pass -> count/clip pass
   ScoreParams sp;
   hipStream_t stream;
   bool want_corpus_stats;
@@ -247,6 +253,7 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                                                  : reinterpret_cast<int32_t*>(w + L.distinct_off);
   st.corpus = (stats && stats->corpus_stats) ? stats->corpus_stats
                                              : reinterpret_cast<int64_t*>(w + L.corpus_off);
+  c->cand_distinct = reinterpret_cast<int32_t*>(w + L.cand_distinct_off);
   c->want_corpus_stats = stats && stats->corpus_stats;
   ScoreParams& sp = c->sp;
   sp.N = cfg->max_n;
@@ -269,12 +276,22 @@ bool counts_in_dictionary(const Call& c) {
   return c.plans.use_part && c.plans.part.count_in_dictionary;
 }
 hipError_t run_dictionary(const Call& c, bool whole_call) {
+  if (c.plans.use_hier)
+    return launch_hier_dictionary(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.stream);
   if (c.plans.use_part)
     return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st, whole_call, c.stream);
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }
-hipError_t run_count_clip(const Call& c) {
+// out_bleu_or_null: whole per-sentence call; the hierarchical kernel then also forms the scores
+// when one workgroup holds all orders of a group (scores_in_count says whether it does)
+bool scores_in_count(const Call& c) {
+  return c.plans.use_hier && hier_count_scores(c.pb, c.plans.hier);
+}
+hipError_t run_count_clip(const Call& c, void* out_bleu_or_null = nullptr) {
+  if (c.plans.use_hier)
+    return launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.sp,
+                                  out_bleu_or_null, c.stream);
   if (c.plans.use_part) return launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream);
   return c.plans.use_big ? launch_big_count_clip(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream);
@@ -303,9 +320,13 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   }
   if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
   if ((rc = hip_rc(run_dictionary(c, true))) != TB_OK) return rc;
-  if (!counts_in_dictionary(c) && (rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
-  return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
-                                out_bleu, c.stream));
+  const bool tail_in_count = !corpus && scores_in_count(c);
+  if (!counts_in_dictionary(c) &&
+      (rc = hip_rc(run_count_clip(c, tail_in_count ? out_bleu : nullptr))) != TB_OK)
+    return rc;
+  if (tail_in_count && !c.want_corpus_stats) return TB_OK;
+  return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus && !tail_in_count,
+                                corpus || c.want_corpus_stats, corpus, out_bleu, c.stream));
 }
 
 }  // namespace

@@ -291,6 +291,18 @@ void fused_kernel(FusedArgs a) {
 
 #pragma unroll 1
   for (int n = 1; n <= N; ++n) {
+#ifndef TB_NO_PRIO
+    // Two workgroups share a compute unit, and its arbiter serves the older wavefronts first:
+    // left alone, the workgroup dispatched first finishes early and the other one then runs
+    // alone on a half-empty unit.  A workgroup that is behind (a lower order) therefore gets
+    // the higher priority, which keeps the two within an order of each other.
+    switch (n) {
+      case 1: __builtin_amdgcn_s_setprio(3); break;
+      case 2: __builtin_amdgcn_s_setprio(2); break;
+      case 3: __builtin_amdgcn_s_setprio(1); break;
+      default: __builtin_amdgcn_s_setprio(0); break;
+    }
+#endif
     if (n >= 2) __syncthreads();  // every slot of the previous order has been emptied
 
     // ---- A: candidate n-grams claim or find their entry

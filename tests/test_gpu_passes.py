@@ -61,6 +61,9 @@ def test_pack_dictionary_count_passes(seed, B, R, V, L):
     lay, wsb, stats, out = stage_all(w)
     cap = lay.group_cap
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+    assert lay.global_candidate_first == (0 if V > 2 ** 20 else 1)
+    cand_distinct = wsb[lay.cand_distinct_off: lay.cand_distinct_off + B * 4 * 4].view(
+        np.int32).reshape(B, 4)
     for n in range(1, 5):
         keys = read_keys(wsb, lay, n, B * cap)
         inv = wsb[lay.inv_off[n - 1]: lay.inv_off[n - 1] + B * cap * 4].view(np.uint32)
@@ -78,6 +81,13 @@ def test_pack_dictionary_count_passes(seed, B, R, V, L):
             ids = sorted(seen.values())
             assert ids == list(range(len(ids)))                        # dense and injective
             assert len(ids) == ref.group_distinct[g, n - 1]
+            if lay.global_candidate_first:
+                # ids below cand_distinct[g][n] are exactly the n-grams the candidate contains
+                cd = int(cand_distinct[g, n - 1])
+                assert cd == ref.cand_distinct[g, n - 1]
+                in_cand = {tuple(int(t) for t in w.cand[g, p:p + n])
+                           for p in range(max(w.cand_len[g] - n + 1, 0))}
+                assert all((gram in in_cand) == (local < cd) for gram, local in seen.items())
     np.testing.assert_array_equal(stats.group_distinct.cpu().numpy(), ref.group_distinct)
     np.testing.assert_array_equal(stats.clipped.cpu().numpy(), ref.clipped)
     np.testing.assert_array_equal(stats.total.cpu().numpy(), ref.total)
