@@ -283,15 +283,9 @@ hipError_t run_dictionary(const Call& c, bool whole_call) {
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }
-// out_bleu_or_null: whole per-sentence call; the hierarchical kernel then also forms the scores
-// when one workgroup holds all orders of a group (scores_in_count says whether it does)
-bool scores_in_count(const Call& c) {
-  return c.plans.use_hier && hier_count_scores(c.pb, c.plans.hier);
-}
-hipError_t run_count_clip(const Call& c, void* out_bleu_or_null = nullptr) {
+hipError_t run_count_clip(const Call& c) {
   if (c.plans.use_hier)
-    return launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.sp,
-                                  out_bleu_or_null, c.stream);
+    return launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.stream);
   if (c.plans.use_part) return launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream);
   return c.plans.use_big ? launch_big_count_clip(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream);
@@ -320,13 +314,9 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   }
   if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
   if ((rc = hip_rc(run_dictionary(c, true))) != TB_OK) return rc;
-  const bool tail_in_count = !corpus && scores_in_count(c);
-  if (!counts_in_dictionary(c) &&
-      (rc = hip_rc(run_count_clip(c, tail_in_count ? out_bleu : nullptr))) != TB_OK)
-    return rc;
-  if (tail_in_count && !c.want_corpus_stats) return TB_OK;
-  return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus && !tail_in_count,
-                                corpus || c.want_corpus_stats, corpus, out_bleu, c.stream));
+  if (!counts_in_dictionary(c) && (rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
+  return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
+                                out_bleu, c.stream));
 }
 
 }  // namespace

@@ -20,15 +20,13 @@
 // of KB of LDS).  One workgroup per group streams the ids of all its orders with every load in
 // flight from the start, bumps a field per occurrence (references skip ids at or above
 // cand_distinct), and sweeps the few thousand entries once: maximum over the reference fields,
-// minimum with the candidate field, sum.  Three barriers for the whole group.  In a whole call
-// the same workgroup goes on to the brevity penalty, smoothing and geometric mean (Section 3.4).
+// minimum with the candidate field, sum.  Three barriers per workgroup.
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
 
 #include "tb_group_index.h"
 #include "tb_kernels.h"
-#include "tb_score.h"
 
 // Phase time stamps for tuning builds only (-DTB_STAMPS): thread 0 of every workgroup records the
 // 100 MHz wall clock at phase boundaries; tb_debug_stamps copies them to the host.
@@ -87,27 +85,21 @@ __device__ __forceinline__ void find_sequence(int k0, int lane, int incl, int R,
   *end = e;
 }
 
-// Claim-or-find in the open-addressing table (double hashing; the table is never full and a
-// key is below 2^31, so it never equals the empty marker).  Single-exit probe loop.
+// Claim-or-find in the open-addressing table (double hashing; a key is below 2^31, so it never
+// equals the empty marker).  Single-exit probe loop.
 __device__ __forceinline__ uint32_t hier_insert(uint32_t* table, uint32_t key, uint32_t mask,
                                                 int shift, bool* won) {
   const uint32_t h = key * 0x9E3779B1u;
   const uint32_t step = (h >> 3) | 1u;
   uint32_t s = h >> shift;
   uint32_t old = atomicCAS(&table[s], kEmpty, key);
-#ifdef TB_NO_GUARD
+  // No round limit is needed: the odd step visits every slot of the power-of-two table, the
+  // table has more slots than the group has n-grams (so an empty slot or the key itself is met
+  // within table_slots probes), and only this workgroup writes the table after clearing it.
   while (int(old != kEmpty) & int(old != key)) {
     s = (s + step) & mask;
     old = atomicCAS(&table[s], kEmpty, key);
   }
-#else
-  uint32_t rounds = 0;  // the same in every lane still probing
-  while (int(old != kEmpty) & int(old != key) & int(rounds < mask)) {
-    s = (s + step) & mask;
-    old = atomicCAS(&table[s], kEmpty, key);
-    rounds = uint32_t(__builtin_amdgcn_readfirstlane(int(rounds))) + 1u;
-  }
-#endif
   *won = old == kEmpty;
   return s;
 }
@@ -314,9 +306,7 @@ struct HierCountArgs {
   Problem pb;
   GlobalWs ws;
   StatPtrs st;
-  ScoreParams sp;
   const int32_t* cand_distinct;  // [B, N] written by the dictionary pass
-  void* out;       // per-sentence scores, or null (staged pass / corpus call / split > 1)
   int words;       // 32-bit words of 16-bit fields per entry: ceil((R + 1) / 2)
   int order_words; // LDS words per order: cand_stride * words
   int split;       // workgroups per group; workgroup r takes the orders r + 1, r + 1 + split, ...
@@ -330,7 +320,7 @@ struct __attribute__((packed, aligned(4))) IdQuad {
 
 // ROWS: 16-byte requests per thread and order; a wavefront's request covers 256 consecutive
 // slots (lane l: slots 4l .. 4l + 3 of the block), rows are 4 * threads slots apart.
-// OPW: orders per workgroup (1, 2, 4 or 8; orders beyond N idle).
+// OPW: orders per workgroup (1 or 2; orders beyond N idle).
 // The scalar work per block (its first sequence, the bounds, the branches) is shared by 256
 // n-grams; a block inside one sequence runs four predicated atomics with a scalar field word and
 // addend, a block that straddles sequences finds each slot's sequence per lane.
@@ -511,25 +501,6 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
       a.st.clipped[int64_t(g) * N + n - 1] = cn;
       a.st.total[int64_t(g) * N + n - 1] = tn;
     }
-    if (a.out) {  // whole call, all orders here (split == 1): lane o holds order o + 1
-      const int used = refs_used(pb, g, lane == 0);  // reports a clamped reference count
-      const int my_len = (lane >= 1 && lane <= used)
-          ? clamped_len(pb.ref_len[int64_t(g) * R + lane - 1], pb.ref_stride, nullptr) : 0;
-      const int c = clamped_len(pb.cand_len[g], pb.cand_stride, nullptr);
-      int best = lane_value(my_len, 1), bd = abs(best - c);
-      for (int j = 2; j <= used; ++j) {
-        const int l = lane_value(my_len, j), d = abs(l - c);
-        if (d < bd || (d == bd && l < best)) {
-          best = l;
-          bd = d;
-        }
-      }
-      const float score = bleu_from_stats_wave(cn, tn, c, best, a.sp);
-      if (lane == 0) {
-        a.st.closest[g] = best;
-        store_score(a.out, g, score, a.sp.out_bf16);
-      }
-    }
   }
 }
 
@@ -554,7 +525,6 @@ hipError_t launch_count_shape(const HierCountArgs& a, int threads, hipStream_t s
                     size_t(OPW) * a.order_words * 4, s);
 }
 
-// rows: 1, 2, 3, 4, 6, 8, 12 with one order per workgroup; fewer with more orders (registers)
 hipError_t launch_count_rows(const HierCountArgs& a, int threads, int rows, int opw,
                              hipStream_t s) {
   switch (opw * 100 + rows) {
@@ -563,18 +533,11 @@ hipError_t launch_count_rows(const HierCountArgs& a, int threads, int rows, int 
     case 103: return launch_count_shape<3, 1>(a, threads, s);
     case 104: return launch_count_shape<4, 1>(a, threads, s);
     case 106: return launch_count_shape<6, 1>(a, threads, s);
-    case 108: return launch_count_shape<8, 1>(a, threads, s);
-    case 112: return launch_count_shape<12, 1>(a, threads, s);
     case 201: return launch_count_shape<1, 2>(a, threads, s);
     case 202: return launch_count_shape<2, 2>(a, threads, s);
     case 203: return launch_count_shape<3, 2>(a, threads, s);
     case 204: return launch_count_shape<4, 2>(a, threads, s);
     case 206: return launch_count_shape<6, 2>(a, threads, s);
-    case 401: return launch_count_shape<1, 4>(a, threads, s);
-    case 402: return launch_count_shape<2, 4>(a, threads, s);
-    case 403: return launch_count_shape<3, 4>(a, threads, s);
-    case 801: return launch_count_shape<1, 8>(a, threads, s);
-    case 802: return launch_count_shape<2, 8>(a, threads, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -587,15 +550,16 @@ struct CountShape {
 
 int rows_for(int64_t group_cap, int threads) {
   const int need = int((group_cap + 4 * threads - 1) / (4 * threads));
-  for (int r : {1, 2, 3, 4, 6, 8, 12})
+  for (int r : {1, 2, 3, 4, 6})
     if (r >= need) return r;
   return 0;
 }
 
 CountShape count_shape(const Problem& pb, const HierPlan& plan) {
-  CountShape c{plan.count_threads, plan.count_rows, plan.orders_per_workgroup};
-  // more workgroups per group when the batch alone does not fill the GPU
-  while (c.opw > 1 && int64_t(pb.B) * ((pb.N + c.opw - 1) / c.opw) < 384) c.opw /= 2;
+  CountShape c{plan.count_threads, plan.count_rows, 1};
+  // two orders per workgroup when single orders would make more workgroups than the GPU digests
+  // well (measured: 16 384 workgroups of 128 threads lose to 8192 with two orders each)
+  if (int64_t(pb.B) * pb.N > 8192 && plan.count_pairs_fit) c.opw = 2;
 #ifdef TB_STAMPS
   if (const char* e = getenv("TB_COUNT_SHAPE")) {  // tuning builds: "threads,opw"
     int t = 0, o = 0;
@@ -630,21 +594,16 @@ bool plan_hier(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
   plan->words = (R + 2) / 2;
   const size_t per_order = size_t(cand_stride) * plan->words * 4;
   if (per_order > kHierLdsPerWorkgroup) return false;
-  // orders whose counters one workgroup holds at once: a power of two, at most N rounded up
-  int opw = 1;
-  while (opw < N && size_t(2 * opw) * per_order <= kHierLdsPerWorkgroup) opw *= 2;
-  plan->orders_per_workgroup = opw;
-  // count/clip: 16-byte requests, ROWS per thread and order; the workgroup size that leaves the
-  // fewest idle lanes among those with at most three rows (the larger one on ties)
-  int64_t best_pad = -1;
-  for (int nt = 1024; nt >= 256; nt /= 2) {
+  plan->count_pairs_fit = 2 * per_order <= kHierLdsPerWorkgroup / 2;
+  // count/clip: 16-byte id requests, ROWS per thread and order; measured best with small
+  // workgroups that take four to six requests per thread
+  plan->count_threads = 1024;
+  for (int nt = 128; nt <= 1024; nt *= 2) {
     const int rows = rows_for(group_cap, nt);
-    if (rows < 1 || rows > 3) continue;
-    const int64_t pad = int64_t(rows) * 4 * nt;
-    if (best_pad < 0 || pad < best_pad) {
-      best_pad = pad;
+    if (rows >= 1) {
       plan->count_threads = nt;
       plan->count_rows = rows;
+      break;
     }
   }
   return true;
@@ -659,37 +618,56 @@ hipError_t launch_hier_dictionary(const Problem& pb, const GlobalWs& ws, const H
   a.cand_distinct = cand_distinct;
   a.table_slots = plan.table_slots;
   a.table_shift = 32 - ceil_log2_int(plan.table_slots);
-  switch (plan.items) {
-    case 2: return launch_dict_items<2>(a, plan, s);
-    case 4: return launch_dict_items<4>(a, plan, s);
-    case 6: return launch_dict_items<6>(a, plan, s);
-    case 8: return launch_dict_items<8>(a, plan, s);
-    case 12: return launch_dict_items<12>(a, plan, s);
+  HierPlan shape = plan;
+  auto items_for = [&](int t) {
+    const int need = int((pb.group_cap + t - 1) / t);
+    return need <= 2 ? 2 : need <= 4 ? 4 : need <= 6 ? 6 : need <= 8 ? 8 : need <= 12 ? 12 : 0;
+  };
+  // A batch of many rounds of workgroups runs best on small workgroups with up to eight
+  // positions per thread (the per-wavefront work of every phase is shared by more n-grams);
+  // otherwise the plan's wider workgroups finish a group sooner.
+  if (pb.B >= 2048) {
+    for (int t = 256; t < plan.threads; t *= 2) {
+      const int items = items_for(t);
+      if (items >= 2 && items <= 8 && plan.table_slots % (4 * t) == 0) {
+        shape.threads = t;
+        shape.items = items;
+        break;
+      }
+    }
+  }
+#ifdef TB_STAMPS
+  if (const char* e = getenv("TB_DICT_THREADS")) {  // tuning builds
+    const int t = atoi(e);
+    if ((t == 256 || t == 512 || t == 1024) && items_for(t) && plan.table_slots % (4 * t) == 0) {
+      shape.threads = t;
+      shape.items = items_for(t);
+    }
+  }
+#endif
+  switch (shape.items) {
+    case 2: return launch_dict_items<2>(a, shape, s);
+    case 4: return launch_dict_items<4>(a, shape, s);
+    case 6: return launch_dict_items<6>(a, shape, s);
+    case 8: return launch_dict_items<8>(a, shape, s);
+    case 12: return launch_dict_items<12>(a, shape, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, const int32_t* cand_distinct,
-                                  const ScoreParams& sp, void* out_bleu_or_null, hipStream_t s) {
+                                  hipStream_t s) {
   HierCountArgs a;
   a.pb = pb;
   a.ws = ws;
   a.st = st;
-  a.sp = sp;
   a.cand_distinct = cand_distinct;
   a.words = plan.words;
   a.order_words = int(pb.cand_stride) * plan.words;
   const CountShape shape = count_shape(pb, plan);
   a.split = (pb.N + shape.opw - 1) / shape.opw;
-  a.out = a.split == 1 ? out_bleu_or_null : nullptr;
   return launch_count_rows(a, shape.threads, shape.rows, shape.opw, s);
-}
-
-// whether launch_hier_count_clip, given an output pointer, writes the scores itself
-bool hier_count_scores(const Problem& pb, const HierPlan& plan) {
-  const CountShape shape = count_shape(pb, plan);
-  return (pb.N + shape.opw - 1) / shape.opw == 1;
 }
 
 }  // namespace tb

@@ -68,20 +68,17 @@ struct HierPlan {
   int table_slots;           // power of two > group_cap, 4-byte entries
   size_t dict_lds;
   int words;                 // count/clip: 32-bit words of 16-bit fields per entry
-  int orders_per_workgroup;  // count/clip: orders whose counters one workgroup holds at once
   int count_threads, count_rows;  // count/clip: workgroup size; 16-byte id requests per thread
+  int count_pairs_fit;       // count/clip: the counters of two orders fit one workgroup's LDS
 };
 bool plan_hier(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
                HierPlan* plan);
 // cand_distinct [B, N]: written by the dictionary pass, read by the count/clip pass
 hipError_t launch_hier_dictionary(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, int32_t* cand_distinct, hipStream_t s);
-// out_bleu_or_null: per-sentence scores (and st.closest) are formed by the same kernel when
-// hier_count_scores() says so; otherwise the pointer is ignored
 hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, const int32_t* cand_distinct,
-                                  const ScoreParams& sp, void* out_bleu_or_null, hipStream_t s);
-bool hier_count_scores(const Problem& pb, const HierPlan& plan);
+                                  hipStream_t s);
 
 // Groups beyond the LDS plans: table and counters live in the workspace.
 struct BigPlan {
