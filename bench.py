@@ -6,7 +6,8 @@ synthetic batch already resident in HBM.  The default workload is the headline c
 (B=512 candidates of 1024 tokens, 4 references each, vocabulary 50257).  One JSON line is
 printed: `value` = sentences/s of the whole call, `roofline` = the dominant kernel's algorithmic
 bytes per launch over its HIP-event duration against the 8 TB/s HBM peak (plus its measured HBM
-traffic and instruction-issue time from the committed profiler summaries), `passes` = every
+traffic and instruction counts, parsed from the committed rocprofv3 summaries under profiles/),
+`passes` = every
 kernel of the path that ran, `global_path` = the staged pipeline's passes timed one by one,
 `achievable_hbm_GBps` = plain fill / read / copy kernels in the same run, `cpu_baseline` = the CPU
 oracle on a bounded sample of the same workload.
@@ -41,11 +42,38 @@ def algorithmic_bytes(w, lay, N, token_bytes=4):
     }
 
 
+_SLEEP_CYCLES_PER_MS = None
+
+
+def _block_stream(ms, torch):
+    """Keep the GPU busy for about `ms` milliseconds (torch's spin kernel on the current stream),
+    so that the host can enqueue the timed launches ahead of the GPU."""
+    global _SLEEP_CYCLES_PER_MS
+    if _SLEEP_CYCLES_PER_MS is None:
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        torch.cuda._sleep(2_000_000)
+        b.record()
+        torch.cuda.synchronize()
+        _SLEEP_CYCLES_PER_MS = 2_000_000 / max(a.elapsed_time(b), 1e-3)
+    torch.cuda._sleep(int(ms * _SLEEP_CYCLES_PER_MS))
+
+
 def time_region(fn, iters, torch):
-    """Average milliseconds of `fn` over `iters` back-to-back enqueues, timed with HIP events
-    recorded on the stream the kernels are launched on (torch's current stream)."""
+    """Average milliseconds of GPU time of `fn` over `iters` back-to-back launches, timed with HIP
+    events recorded on the stream the kernels are launched on (torch's current stream).  A call
+    through Python costs 8-12 us of host time, more than some of the kernels take; so a spin
+    kernel first holds the stream while the host enqueues start event, launches and stop event:
+    the events then bracket GPU execution, not the host's enqueue rate."""
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(8):
+        fn()
+    host_ms = (time.perf_counter() - t0) / 8
+    torch.cuda.synchronize()
+    _block_stream(host_ms * iters * 2.0 + 0.5, torch)
     start.record()
     for _ in range(iters):
         fn()
@@ -106,7 +134,8 @@ def cpu_baseline(w, run, gpu=None, budget_s=10.0):
     single = w.subset(min(sample.B, max(8, int(rate / threads))))      # about a second
     dt1, _ = timed(single, 1)
     what = "the whole workload" if sample.B == w.B else f"first {sample.B} sentence groups"
-    out = {"value": sample.B / best, "unit": "sentences/s", "cores": threads, "kind": "oracle",
+    out = {"value": sample.B / best, "unit": "sentences/s", "cores": threads,
+           "cores_available": cores, "kind": "oracle",
            "sample": f"{what}, best of 3, {threads} std::threads over sentences",
            "value_1_thread": single.B / dt1,
            "sample_1_thread": f"first {single.B} sentence groups, one run"}
@@ -174,25 +203,65 @@ def other_configs(skip, steps, torch, tb, syn, np, dev):
     return rows
 
 
-# HBM traffic per launch (fetch + write bytes) of the dominant kernel, from the rocprofv3 --pmc
-# runs summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters'
-# reading for a plain copy of known size).  Keyed by (workload name, kernel); None = not measured.
-MEASURED_TRAFFIC = {
-    ("cfg3_B512_L1024_R4", "fused"): 10.89e6,
-    ("cfg3_B512_L1024_R4", "pack"): 94.89e6,
-    ("cfg3_B512_L1024_R4", "dictionary"): 125.85e6,
-    ("cfg3_B512_L1024_R4", "count_clip"): 44.52e6,
-}
-
-# Wave-level instructions per launch (SQ_INSTS_VALU, SQ_INSTS_SALU) from the same --pmc runs.  A
-# compute unit issues about one of them per cycle, so their sum over 256 CUs at 2.4 GHz is the
-# time the instruction stream alone needs: the figure that actually bounds these kernels.
-MEASURED_INSTRUCTIONS = {
-    ("cfg3_B512_L1024_R4", "fused"): (9.58e6, 7.76e6),
-    ("cfg3_B512_L1024_R4", "dictionary"): (10.00e6, 10.08e6),
-    ("cfg3_B512_L1024_R4", "count_clip"): (4.47e6, 3.87e6),
+# Which kernels implement which pass (names as they appear in the rocprofv3 summaries).
+PASS_KERNELS = {
+    "fused": ("fused_kernel",),
+    "pack": ("pack_kernel",),
+    "dictionary": ("hier_dictionary_kernel", "dictionary_narrow_kernel", "dictionary_wide_kernel",
+                   "part_dictionary_kernel", "big_dictionary_kernel"),
+    "count_clip": ("hier_count_kernel", "count_fields_kernel", "count_clip_kernel",
+                   "part_count_kernel", "big_count_kernel"),
+    "finalize": ("sentence_score_kernel",),
 }
 NUM_CUS, CLOCK_GHZ = 256, 2.4
+# Issue rates measured with micro-benchmarks on this GPU (wavefront instructions per CU-cycle at
+# full occupancy): vector ALU alone, scalar ALU alone (one scalar unit per CU), both kinds mixed.
+ISSUE_PEAK = {"valu": 1.5, "salu": 1.0, "mixed": 1.7}
+
+
+def profile_counters(workload, pass_name):
+    """Counters of the kernel that implements `pass_name`, read from the committed rocprofv3
+    summary profiles/pmc_<workload>.md (sections '## `kernel`' with '* COUNTER: value' lines;
+    values are means per launch).  Returns (kernel name, {counter: value}) or (None, {}) when no
+    summary exists for the workload or the kernel."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.md")
+    if not os.path.exists(path):
+        return None, {}
+    best = (None, {})
+    kernel, counters = None, {}
+    for line in open(path).read().splitlines() + ["## `end`"]:
+        if line.startswith("## `"):
+            if kernel and any(k in kernel for k in PASS_KERNELS[pass_name]) and \
+                    counters.get("SQ_WAVES", 0) >= best[1].get("SQ_WAVES", -1):
+                best = (kernel, counters)          # several instantiations: the largest launch
+            kernel, counters = line[4:].rstrip("`"), {}
+        elif line.startswith("* ") and ":" in line and kernel:
+            name, value = line[2:].split(":", 1)
+            if "traffic" in name:                  # "... = 10.89 MB"
+                try:
+                    counters["hbm_traffic_bytes"] = float(value.split("=")[-1].split()[0]) * 1e6
+                except ValueError:
+                    pass
+            else:
+                try:
+                    counters[name.strip()] = float(value.replace(",", ""))
+                except ValueError:
+                    pass
+    return best
+
+
+def issue_model(counters, kernel_us):
+    """Time the kernel's instruction stream needs at the measured issue peaks, against its
+    measured duration."""
+    valu, salu = counters.get("SQ_INSTS_VALU"), counters.get("SQ_INSTS_SALU")
+    if valu is None or salu is None:
+        return None
+    cycles = max(valu / ISSUE_PEAK["valu"], salu / ISSUE_PEAK["salu"],
+                 (valu + salu) / ISSUE_PEAK["mixed"]) / NUM_CUS
+    issue_us = cycles / (CLOCK_GHZ * 1e3)
+    return {"valu_wave_instr": valu, "salu_wave_instr": salu,
+            "issue_peaks_per_cu_cycle": ISSUE_PEAK, "issue_us_at_peak": round(issue_us, 2),
+            "frac_of_kernel_time": round(issue_us / kernel_us, 3)}
 
 
 def main():
@@ -322,19 +391,30 @@ def main():
     else:
         passes = time_stages([("fused", step)], alg)
     dom = max(passes, key=lambda p: p["us"])
-    traffic = a.traffic_bytes
-    if traffic is None:
-        traffic = MEASURED_TRAFFIC.get((w.name, dom["kernel"]))
+    prof_kernel, counters = profile_counters(w.name, dom["kernel"])
+    traffic = a.traffic_bytes if a.traffic_bytes is not None else counters.get("hbm_traffic_bytes")
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["GBps"],
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_hbm"],
-                "traffic": traffic}
-    instr = MEASURED_INSTRUCTIONS.get((w.name, dom["kernel"]))
-    if instr is not None:
-        issue_us = sum(instr) / NUM_CUS / (CLOCK_GHZ * 1e3)
-        roofline["instruction_issue"] = {
-            "valu_wave_instr": instr[0], "salu_wave_instr": instr[1],
-            "issue_us_at_1_per_cu_cycle": round(issue_us, 2),
-            "frac_of_kernel_time": round(issue_us / dom["us"], 3)}
+                "traffic": traffic,
+                "traffic_source": (f"profiles/pmc_{w.name}.md ({prof_kernel})" if traffic and
+                                   a.traffic_bytes is None else
+                                   "command line" if traffic else
+                                   "no rocprofv3 summary committed for this workload")}
+    model = issue_model(counters, dom["us"])
+    if model is not None:
+        roofline["instruction_issue"] = model
+
+    # the paper's protocol beside it (its Section 4.2): mean wall-clock time of 5 single calls,
+    # each synchronised on its own (launch and synchronisation latency included)
+    runs = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        runs.append((time.perf_counter() - t0) * 1e3)
+    paper_protocol = {"ms_mean_of_5_synchronised_calls": round(sum(runs) / 5, 5),
+                      "sentences_per_s": round(w.B / (sum(runs) / 5 * 1e-3), 1)}
 
     result = {
         "metric": "per-sentence BLEU sentences/sec at B=512, L=1024; % HBM roofline",
@@ -348,7 +428,7 @@ def main():
                    "vocab": w.vocab, "max_n": N, "smoothing": run.smoothing, "path": path,
                    "tokens": w.tokens},
         "ms_per_step_events": round(ev_ms, 5), "ms_per_step_wall": round(wall_ms, 5),
-        "roofline": roofline, "passes": passes,
+        "roofline": roofline, "passes": passes, "paper_protocol": paper_protocol,
     }
     if global_section is not None and path != "global":
         result["global_path"] = global_section

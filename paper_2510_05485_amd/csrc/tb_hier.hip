@@ -111,7 +111,7 @@ __device__ __forceinline__ uint32_t hier_insert(uint32_t* table, uint32_t key, u
 // (The scalar-register cap keeps two 1024-thread workgroups on a compute unit: eight wavefronts
 // per SIMD need at most 80 scalar registers each on this hardware.)
 template <int ITEMS>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(80)))
+__global__ __launch_bounds__(1024, (ITEMS <= 6 ? 8 : 4)) __attribute__((amdgpu_num_sgpr(80)))
 void hier_dictionary_kernel(HierDictArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_delta[8 * kWave];  // [n-1][s]: order-1 slot minus order-n slot inside sequence s
