@@ -435,7 +435,7 @@ def main():
     if a.rouge:
         # the ROUGE-N extension on the same batch (same kernel family, order a.rouge)
         rws = tb.allocate_workspace(w.B, w.R, cs, rs, tb.make_config(
-            max_n=a.rouge, vocab_size=w.vocab, path="fused"), dev)
+            max_n=a.rouge, vocab_size=w.vocab, path="auto"), dev)
         rfn = lambda: tb.tensorrouge_n(cand, cl, refs, rl, n=a.rouge, vocab_size=w.vocab,
                                        workspace=rws)
         for _ in range(a.warmup):

@@ -136,6 +136,7 @@ typedef struct tb_layout {
   size_t  cand_distinct_off; /* int32 [B,N]: distinct n-grams of the candidate alone (GLOBAL path,
                               written by the dictionary pass when global_candidate_first is set) */
   size_t  corpus_off;      /* int64 [2N+2] */
+  size_t  overlap_off;     /* int32 [B, R]: ROUGE-N overlap counts (GLOBAL path) */
   size_t  bytes;           /* total workspace size for this path */
   int32_t fused_ok;        /* 1 if the FUSED path supports this shape */
   int32_t global_ok;       /* 1 if the GLOBAL path supports this shape */
@@ -223,9 +224,13 @@ size_t tensorbleu_static_scratch_bytes(void);
  * n-grams), to which F is proportional.  overlap[B, R] int32 and best_ref[B] int32 (index of that
  * reference) are optional device outputs (NULL to skip); entries of references beyond
  * cfg->ref_count[i] are 0.  cfg->weights and cfg->smoothing are ignored; vocab_size, token_bytes
- * and ref_count mean what they mean for BLEU.  Runs on the FUSED path only: shapes it does not
- * support return TB_ERR_UNSUPPORTED.  Workspace: tensorbleu_workspace_bytes with force_path =
- * TB_PATH_FUSED (or AUTO when AUTO resolves to FUSED).  stats: only device_status is used. */
+ * and ref_count mean what they mean for BLEU.  Paths as for BLEU (cfg->force_path; AUTO takes
+ * FUSED where the shape fits it, else GLOBAL: pack and dictionary for the orders 1..n, then the
+ * count pass for order n with per-reference sums).  On GLOBAL, LDS-resident groups with plain
+ * packed-key tables (global_candidate_first == 0 and global_partitions == 0) and groups on
+ * workspace tables (global_tables_in_hbm) return TB_ERR_UNSUPPORTED.  Workspace:
+ * tensorbleu_workspace_bytes for the same arguments (cfg->max_n = n).  stats: only
+ * device_status is used. */
 int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                   const void* refs, int64_t ref_stride, const int32_t* ref_len, int32_t B,
                   int32_t R, const tb_config_t* cfg, void* out_prf, int32_t* overlap,

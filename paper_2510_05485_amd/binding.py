@@ -51,7 +51,8 @@ class tb_layout_t(ctypes.Structure):
                 ("clipped_off", ctypes.c_size_t), ("total_off", ctypes.c_size_t),
                 ("closest_off", ctypes.c_size_t), ("distinct_off", ctypes.c_size_t),
                 ("cand_distinct_off", ctypes.c_size_t),
-                ("corpus_off", ctypes.c_size_t), ("bytes", ctypes.c_size_t),
+                ("corpus_off", ctypes.c_size_t), ("overlap_off", ctypes.c_size_t),
+                ("bytes", ctypes.c_size_t),
                 ("fused_ok", ctypes.c_int32), ("global_ok", ctypes.c_int32),
                 ("global_tables_in_hbm", ctypes.c_int32), ("tables_off", ctypes.c_size_t),
                 ("id_stride", ctypes.c_int64), ("global_candidate_first", ctypes.c_int32),
@@ -303,11 +304,11 @@ def tensorrouge_n(cand, cand_len, refs, ref_len, n: int = 2, beta: float = 1.0, 
                   vocab_size: int, ref_count: Optional[torch.Tensor] = None,
                   want_overlap: bool = False, want_best: bool = False,
                   workspace: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
-                  stream=None, score_dtype: torch.dtype = torch.float32):
+                  stream=None, score_dtype: torch.dtype = torch.float32, path: str = "auto"):
     """ROUGE-N of every candidate against its references: float32 (or bfloat16) [B, 3] (precision,
     recall, F of the best reference), plus overlap int32 [B, R] and best-reference index int32 [B]
     on request (returned as a tuple then)."""
-    cfg = make_config(max_n=n, smooth_param=beta, vocab_size=vocab_size, path="fused",
+    cfg = make_config(max_n=n, smooth_param=beta, vocab_size=vocab_size, path=path,
                       ref_count=ref_count, score_dtype=score_dtype)
     b = _batch(cand, cand_len, refs, ref_len, cfg)
     if workspace is None:

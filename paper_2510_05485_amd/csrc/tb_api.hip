@@ -166,6 +166,8 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   L.cand_distinct_off = off; off = align_up(off + bn * 4);
   L.corpus_off = off;   off = align_up(off + 18 * 8);
   if (path == TB_PATH_GLOBAL) {
+    L.overlap_off = off;  // int32 [B, R]: ROUGE-N overlap counts (count pass -> score kernel)
+    off = align_up(off + size_t(B) * size_t(R) * 4);
     const size_t slots = size_t(B) * size_t(L.group_cap);
     for (int n = 0; n < N; ++n) {
       L.keys_off[n] = off;
@@ -363,7 +365,7 @@ int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len
                   size_t workspace_bytes, void* hip_stream) {
   Call c{};
   int rc = prepare(cand, cand_stride, cand_len, refs, ref_stride, ref_len, B, R, cfg, stats,
-                   workspace, workspace_bytes, hip_stream, true, TB_PATH_FUSED, &c);
+                   workspace, workspace_bytes, hip_stream, true, TB_PATH_AUTO, &c);
   if (rc != TB_OK || B == 0) return rc;
   if (!out_prf) return TB_ERR_INVALID_ARG;
   const float beta = cfg->smooth_param > 0.0f ? cfg->smooth_param : 1.0f;
@@ -375,12 +377,24 @@ int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len
   // the integer BLEU statistics of the run are scratch here: never the caller's arrays
   unsigned char* w = static_cast<unsigned char*>(workspace);
   const tb_layout_t& L = c.plans.layout;
-  StatPtrs st = c.st;
-  st.clipped = reinterpret_cast<int32_t*>(w + L.clipped_off);
-  st.total = reinterpret_cast<int32_t*>(w + L.total_off);
-  st.closest = reinterpret_cast<int32_t*>(w + L.closest_off);
-  st.distinct = reinterpret_cast<int32_t*>(w + L.distinct_off);
-  return hip_rc(launch_fused(c.pb, c.plans.fused, st, c.sp, nullptr, c.stream, &ro));
+  c.st.clipped = reinterpret_cast<int32_t*>(w + L.clipped_off);
+  c.st.total = reinterpret_cast<int32_t*>(w + L.total_off);
+  c.st.closest = reinterpret_cast<int32_t*>(w + L.closest_off);
+  c.st.distinct = reinterpret_cast<int32_t*>(w + L.distinct_off);
+  if (L.path == TB_PATH_FUSED)
+    return hip_rc(launch_fused(c.pb, c.plans.fused, c.st, c.sp, nullptr, c.stream, &ro));
+  // GLOBAL: pack and dictionary as for BLEU (the keys of order n build on the ids of the orders
+  // below), then the count pass for order n alone, which also sums the per-reference overlaps
+  if (!c.plans.use_hier && !c.plans.use_part) return TB_ERR_UNSUPPORTED;  // BLEU-only kernels
+  int32_t* ov = reinterpret_cast<int32_t*>(w + L.overlap_off);
+  if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
+  if ((rc = hip_rc(run_dictionary(c, false))) != TB_OK) return rc;
+  rc = hip_rc(c.plans.use_hier
+                  ? launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct,
+                                           c.stream, ov)
+                  : launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream, ov));
+  if (rc != TB_OK) return rc;
+  return hip_rc(launch_rouge_finalize(c.pb, c.sp, ov, ro, c.stream));
 }
 
 int tensorbleu_pack(const void* cand, int64_t cand_stride, const int32_t* cand_len,

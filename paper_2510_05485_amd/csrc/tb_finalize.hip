@@ -90,6 +90,68 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
   }
 }
 
+// ROUGE-N from the overlap counts of the GLOBAL path, one lane per candidate: precision, recall
+// and F against every reference in use; the best reference is the first one with the largest
+// overlap / (candidate n-grams + beta^2 * reference n-grams), to which F is proportional (the
+// same single-precision quotient as the fused kernel forms: both paths choose alike).
+struct RougeFinalArgs {
+  Problem pb;
+  ScoreParams sp;
+  const int32_t* overlap;   // [B, R] from the count pass
+  void* prf;                // [B, 3]
+  int32_t* overlap_out;     // [B, R] caller's array, or null (then `overlap` is the caller's)
+  int32_t* best;            // [B] or null
+  float beta2;
+};
+
+__global__ __launch_bounds__(256) void rouge_score_kernel(RougeFinalArgs a) {
+  const Problem& pb = a.pb;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= pb.B) return;
+  const int N = pb.N, R = pb.R;
+  const int used = refs_used(pb, i, true);
+  const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
+  const float ct = float(max(c - N + 1, 0));
+  int best_j = 0;
+  float best_key = -1.0f, best_rt = 0.0f;
+  int best_ov = 0;
+  for (int j = 0; j < R; ++j) {
+    const int ov = j < used ? a.overlap[int64_t(i) * R + j] : 0;
+    if (a.overlap_out) a.overlap_out[int64_t(i) * R + j] = ov;
+    if (j >= used) continue;
+    const int len = clamped_len(pb.ref_len[int64_t(i) * R + j], pb.ref_stride, pb.status);
+    const float rt = float(max(len - N + 1, 0));
+    const float key = ov > 0 ? float(ov) / __fmaf_rn(a.beta2, rt, ct) : 0.0f;
+    if (key > best_key) {
+      best_key = key;
+      best_j = j;
+      best_rt = rt;
+      best_ov = ov;
+    }
+  }
+  const float p = ct > 0.0f ? float(best_ov) / ct : 0.0f;
+  const float r = best_rt > 0.0f ? float(best_ov) / best_rt : 0.0f;
+  const float f = (p + r > 0.0f) ? (1.0f + a.beta2) * p * r / (r + a.beta2 * p) : 0.0f;
+  store_score(a.prf, int64_t(i) * 3 + 0, p, a.sp.out_bf16);
+  store_score(a.prf, int64_t(i) * 3 + 1, r, a.sp.out_bf16);
+  store_score(a.prf, int64_t(i) * 3 + 2, f, a.sp.out_bf16);
+  if (a.best) a.best[i] = best_j;
+}
+
+hipError_t launch_rouge_finalize(const Problem& pb, const ScoreParams& sp, const int32_t* overlap,
+                                 const RougeOut& out, hipStream_t s) {
+  RougeFinalArgs a;
+  a.pb = pb;
+  a.sp = sp;
+  a.overlap = overlap;
+  a.prf = out.prf;
+  a.overlap_out = (out.overlap && out.overlap != overlap) ? out.overlap : nullptr;
+  a.best = out.best;
+  a.beta2 = out.beta2;
+  hipLaunchKernelGGL(rouge_score_kernel, dim3((pb.B + 255) / 256), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
                            bool sentence_scores, bool corpus_sums, bool corpus_score,
                            void* out_bleu, hipStream_t s) {

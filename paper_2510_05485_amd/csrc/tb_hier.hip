@@ -310,6 +310,9 @@ struct HierCountArgs {
   int words;       // 32-bit words of 16-bit fields per entry: ceil((R + 1) / 2)
   int order_words; // LDS words per order: cand_stride * words
   int split;       // workgroups per group; workgroup r takes the orders r + 1, r + 1 + split, ...
+  // ROUGE-N (rouge_overlap != null): one workgroup per group counts order N only and, in its
+  // sweep, sums min(candidate count, reference j's count) per reference into rouge_overlap[B, R]
+  int32_t* rouge_overlap;
 };
 
 // Four consecutive offset ids, loaded with one 16-byte request.  A group's first slot is only
@@ -328,12 +331,14 @@ template <int ROWS, int OPW>
 __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_clipped[8];
+  __shared__ int s_overlap[kWave];  // ROUGE-N: overlap with each reference
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const bool rouge = a.rouge_overlap != nullptr;  // then split == 1, OPW == 1, order N only
   const int g = blockIdx.x / a.split;
-  const int first_order = blockIdx.x % a.split + 1;
   const int R = pb.R, N = pb.N;
+  const int first_order = rouge ? N : int(blockIdx.x % a.split) + 1;
   const uint32_t W = uint32_t(a.words);
   const int cap = int(pb.group_cap);
   uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
@@ -356,6 +361,7 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
     const int quads = (OPW * a.order_words + 3) / 4;
     for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
     if (tid < 8) s_clipped[tid] = 0;
+    if (tid < kWave) s_overlap[tid] = 0;
   }
   // Ids of every order of this workgroup, all requested before any is used, and only as far as
   // the order's n-gram count reaches (blocks beyond re-read its last ids, a cache hit; the id
@@ -467,6 +473,14 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
           for (uint32_t q = 1; q < W; ++q) m = max(m, max(e[q] & 0xFFFFu, e[q] >> 16));
         }
         sum += min(w0 & 0xFFFFu, m);
+        if (rouge) {  // uniform; field j + 1 is reference j
+          const uint32_t cc = w0 & 0xFFFFu;
+          for (int j = 0; j < R; ++j) {
+            const uint32_t w = e[(j + 1) >> 1];
+            const uint32_t both = min(cc, ((j + 1) & 1) ? (w >> 16) : (w & 0xFFFFu));
+            if (both) atomicAdd(&s_overlap[j], int(both));
+          }
+        }
       }
     };
     switch (W) {  // uniform
@@ -501,6 +515,7 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
       a.st.clipped[int64_t(g) * N + n - 1] = cn;
       a.st.total[int64_t(g) * N + n - 1] = tn;
     }
+    if (rouge && lane < R) a.rouge_overlap[int64_t(g) * R + lane] = s_overlap[lane];
   }
 }
 
@@ -657,7 +672,7 @@ hipError_t launch_hier_dictionary(const Problem& pb, const GlobalWs& ws, const H
 
 hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, const int32_t* cand_distinct,
-                                  hipStream_t s) {
+                                  hipStream_t s, int32_t* rouge_overlap) {
   HierCountArgs a;
   a.pb = pb;
   a.ws = ws;
@@ -666,6 +681,11 @@ hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const H
   a.words = plan.words;
   a.order_words = int(pb.cand_stride) * plan.words;
   const CountShape shape = count_shape(pb, plan);
+  a.rouge_overlap = rouge_overlap;
+  if (rouge_overlap) {  // order N only
+    a.split = 1;
+    return launch_count_rows(a, shape.threads, shape.rows, 1, s);
+  }
   a.split = (pb.N + shape.opw - 1) / shape.opw;
   return launch_count_rows(a, shape.threads, shape.rows, shape.opw, s);
 }

@@ -76,9 +76,11 @@ bool plan_hier(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 // cand_distinct [B, N]: written by the dictionary pass, read by the count/clip pass
 hipError_t launch_hier_dictionary(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, int32_t* cand_distinct, hipStream_t s);
+// rouge_overlap != null: ROUGE-N instead -- only order N is counted, and overlap[B, R] receives
+// per reference the sum over n-grams of min(candidate count, the reference's count)
 hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, const int32_t* cand_distinct,
-                                  hipStream_t s);
+                                  hipStream_t s, int32_t* rouge_overlap = nullptr);
 
 // Groups beyond the LDS plans: table and counters live in the workspace.
 struct BigPlan {
@@ -107,8 +109,10 @@ size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan&
 // then not to be launched
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, bool whole_call, hipStream_t s);
+// rouge_overlap != null: ROUGE-N instead, as for launch_hier_count_clip
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, hipStream_t s);
+                                  const StatPtrs& st, hipStream_t s,
+                                  int32_t* rouge_overlap = nullptr);
 
 bool plan_big(int64_t group_cap, int N, BigPlan* plan);
 hipError_t launch_big_dictionary(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
@@ -133,6 +137,10 @@ hipError_t launch_count_clip(const Problem& pb, const GlobalWs& ws, const CountP
 hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
                            bool sentence_scores, bool corpus_sums, bool corpus_score,
                            void* out_bleu, hipStream_t s);
+// ROUGE-N scores from overlap counts (GLOBAL path): precision, recall, F of the best reference.
+struct RougeOut;
+hipError_t launch_rouge_finalize(const Problem& pb, const ScoreParams& sp, const int32_t* overlap,
+                                 const RougeOut& out, hipStream_t s);
 // ROUGE-N outputs of the fused kernel (order n = pb.N): see tensorrouge_n.
 struct RougeOut {
   void* prf;         // [B, 3] fp32 or bfloat16 (ScoreParams::out_bf16)

@@ -58,6 +58,8 @@ struct PartArgs {
   int words;               // count/clip: 32-bit counter words per id
   int fields_per_word;     // 2: 16-bit counters (sequences of at most 65 535 tokens); 1: 32-bit
   int64_t id_stride;       // ids of group g lie in [g * id_stride, (g + 1) * id_stride)
+  int32_t* rouge_overlap;  // count kernel, ROUGE-N: [B, R] sums of min(candidate count, reference
+                           // j's count), zeroed by the launcher and added to per partition; or null
 };
 
 __device__ __forceinline__ uint32_t part_hash(uint64_t key) {
@@ -423,7 +425,10 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
                                                     const uint32_t* member_ids,
                                                     const uint32_t (&first_round)[kPartUnroll],
                                                     const uint32_t* member_slot = nullptr,
-                                                    uint32_t last_slot = 0, int seq_end = 0) {
+                                                    uint32_t last_slot = 0, int seq_end = 0,
+                                                    int* overlap = nullptr) {
+  // overlap (LDS, R ints, or null): ROUGE-N -- the sweep also adds, per reference j, the sum over
+  // the ids of min(candidate count, reference j's count)
   const int nt = blockDim.x, tid = threadIdx.x;
   {
     uint4* c4 = reinterpret_cast<uint4*>(cnt);
@@ -499,10 +504,23 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
         m = max(m, max(w & 0xFFFFu, w >> 16));
       }
       part += int(min(w0 & 0xFFFFu, m));
+      if (overlap) {  // uniform; field j + 1 is reference j
+        for (int j = 0; j < R; ++j) {
+          const uint32_t w = e[(j + 1) >> 1];
+          const uint32_t both = min(w0 & 0xFFFFu, ((j + 1) & 1) ? (w >> 16) : (w & 0xFFFFu));
+          if (both) atomicAdd(&overlap[j], int(both));
+        }
+      }
     } else {  // word 0: candidate, word 1 + j: reference j
       uint32_t m = 0;
       for (int q = 1; q < W; ++q) m = max(m, e[q]);
       part += int(min(w0, m));
+      if (overlap) {
+        for (int j = 0; j < R; ++j) {
+          const uint32_t both = min(w0, e[1 + j]);
+          if (both) atomicAdd(&overlap[j], int(both));
+        }
+      }
     }
   }
   return part;
@@ -518,7 +536,8 @@ constexpr int kPassWords = 6;
 __device__ __forceinline__ int count_clip_partition_in_passes(uint32_t* cnt, int U,
                                                               int fields_per_word, int R,
                                                               int refs_per_pass, int members,
-                                                              const uint32_t* member_ids) {
+                                                              const uint32_t* member_ids,
+                                                              int* overlap = nullptr) {
   const int nt = blockDim.x, tid = threadIdx.x;
   constexpr int W = kPassWords;
   const int first_word = fields_per_word == 2 ? 1 : 2;  // of the pass's reference fields
@@ -554,6 +573,15 @@ __device__ __forceinline__ int count_clip_partition_in_passes(uint32_t* cnt, int
     __syncthreads();
     for (int u = tid; u < U; u += nt) {
       uint32_t* e = &cnt[uint32_t(u) * uint32_t(W)];
+      if (overlap) {  // ROUGE-N: the pass's references against the candidate's count
+        const uint32_t cc = fields_per_word == 2 ? (e[0] & 0xFFFFu) : e[0];
+        for (int r = 0; r < refs_per_pass && pass_first + r < R; ++r) {
+          const uint32_t w = fields_per_word == 2 ? e[first_word + (r >> 1)] : e[first_word + r];
+          const uint32_t c = fields_per_word == 2 ? ((r & 1) ? (w >> 16) : (w & 0xFFFFu)) : w;
+          const uint32_t both = min(cc, c);
+          if (both) atomicAdd(&overlap[pass_first + r], int(both));
+        }
+      }
       uint32_t m = 0;
       for (int q = first_word; q < W; ++q) {
         const uint32_t w = e[q];
@@ -777,12 +805,15 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
 __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int red_scratch[17];
+  __shared__ int s_overlap[kWave];  // ROUGE-N: this partition's overlap with each reference
   const Problem& pb = a.pb;
   const int tid = threadIdx.x;
-  const Role me = role_of_block(a, nullptr, a.pb.N);
+  const Role me = role_of_block(a, a.orders, a.num_orders);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
   const int W = a.words;
+  int* overlap = a.rouge_overlap ? s_overlap : nullptr;  // (at most 62 references here)
+  if (tid < kWave) s_overlap[tid] = 0;  // (the counting routines start with a barrier)
   uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
   const int U = min(
       max(a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p], 0),
@@ -804,10 +835,12 @@ __global__ __launch_bounds__(kPartThreads) void part_count_kernel(PartArgs a) {
   const int part =
       a.refs_per_pass
           ? count_clip_partition_in_passes(cnt, U, a.fields_per_word, pb.R, a.refs_per_pass,
-                                           members, member_ids)
+                                           members, member_ids, overlap)
           : count_clip_partition<false>(cnt, U, W, a.fields_per_word, pb.R, members, member_ids,
-                                        none);
-  const int clipped = block_sum(part, red_scratch);
+                                        none, nullptr, 0, 0, overlap);
+  const int clipped = block_sum(part, red_scratch);  // (two barriers: s_overlap is complete)
+  if (overlap && tid < pb.R && s_overlap[tid])
+    atomicAdd(&a.rouge_overlap[int64_t(g) * pb.R + tid], s_overlap[tid]);
   if (tid == 0) {
     if (clipped) atomicAdd(&a.st.clipped[int64_t(g) * pb.N + n - 1], clipped);
     if (p == 0) {
@@ -848,6 +881,7 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   a.member_id = reinterpret_cast<uint32_t*>(after_slots);
   a.member_key = reinterpret_cast<uint64_t*>(after_slots + slots4);
   a.chunk_hist = reinterpret_cast<int32_t*>(after_slots + 3 * slots4);
+  a.rouge_overlap = nullptr;
   a.xcd_aware = 1;
   a.with_count = 0;
   a.ids_wanted = ~0;
@@ -955,13 +989,19 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
 }
 
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, hipStream_t s) {
+                                  const StatPtrs& st, hipStream_t s, int32_t* rouge_overlap) {
   PartArgs a = make_args(pb, ws, plan, st);
-  a.xcd_aware = part_xcd_aware(pb, pb.N) ? 1 : 0;
-  const int64_t blocks = part_grid(pb, plan, pb.N);
+  // every order, or for ROUGE-N the highest one only
+  a.num_orders = rouge_overlap ? 1 : pb.N;
+  for (int k = 0; k < 8; ++k) a.orders[k] = rouge_overlap ? pb.N : k + 1;
+  a.rouge_overlap = rouge_overlap;
+  a.xcd_aware = part_xcd_aware(pb, a.num_orders) ? 1 : 0;
+  const int64_t blocks = part_grid(pb, plan, a.num_orders);
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipError_t e = zero_ints(st.clipped, int64_t(pb.B) * pb.N, s);
   if (e != hipSuccess) return e;
+  if (rouge_overlap && (e = zero_ints(rouge_overlap, int64_t(pb.B) * pb.R, s)) != hipSuccess)
+    return e;
   e = grant_dynamic_lds(reinterpret_cast<const void*>(part_count_kernel), plan.count_lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(part_count_kernel, dim3(uint32_t(blocks)), dim3(kPartThreads),

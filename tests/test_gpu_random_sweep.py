@@ -79,13 +79,22 @@ def test_random_sweep(sweep_seed):
                 err = float(np.abs(out.astype(np.float64) - ref.bleu).max())
             assert err <= 1e-5, (tag, err)
             worst = max(worst, err)
-        if lay.fused_ok:
-            n = int(rng.integers(1, 7))
-            beta = float(rng.choice([0.5, 1.0, 2.0]))
+        n = int(rng.integers(1, 7))
+        beta = float(rng.choice([0.5, 1.0, 2.0]))
+        rcfg = tb.make_config(max_n=n, vocab_size=V, path=path)
+        try:
+            rlay = tb.tensorbleu_workspace_layout(B, R, cand.shape[1], refs.shape[2], rcfg)
+        except tb.TensorBLEUError:
+            rlay = None
+        # ROUGE-N runs on the fused kernel and on the GLOBAL path's hierarchical-key and
+        # partitioned kernels
+        if rlay is not None and (rlay.path == 1 or rlay.global_candidate_first or
+                                 rlay.global_partitions):
             rr = oracle.rouge_n(w.cand, w.cand_len, w.refs, w.ref_len, n=n, beta=beta,
                                 ref_count=rc)
             o, ov, best = tb.tensorrouge_n(cand, cl, refs, rl, n=n, beta=beta, vocab_size=V,
-                                           ref_count=drc, want_overlap=True, want_best=True)
+                                           ref_count=drc, want_overlap=True, want_best=True,
+                                           path=path)
             check_rouge(rr, ov.cpu().numpy(), best.cpu().numpy(), o.cpu().numpy(), 1e-5,
                         ref_count=rc)
     assert worst <= 1e-5

@@ -19,7 +19,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def check(w, n, beta=1.0, ref_count=None, int64=False):
+def check(w, n, beta=1.0, ref_count=None, int64=False, path="auto"):
     ref = oracle.rouge_n(w.cand, w.cand_len, w.refs, w.ref_len, n=n, beta=beta,
                          ref_count=ref_count)
     cand, refs = dev(w.cand), dev(w.refs)
@@ -29,7 +29,7 @@ def check(w, n, beta=1.0, ref_count=None, int64=False):
     out, overlap, best = tb.tensorrouge_n(
         cand, dev(w.cand_len), refs, dev(w.ref_len), n=n, beta=beta, vocab_size=w.vocab,
         ref_count=dev(ref_count) if ref_count is not None else None, want_overlap=True,
-        want_best=True, stats=stats)
+        want_best=True, stats=stats, path=path)
     torch.cuda.synchronize()
     assert stats.device_status.item() == 0
     check_rouge(ref, overlap.cpu().numpy(), best.cpu().numpy(), out.cpu().numpy(), TOL,
@@ -58,11 +58,42 @@ def test_rouge_n_beta_reference_counts_and_int64():
     check(w, 3, int64=True)
 
 
+@pytest.mark.parametrize("path", ["auto", "global"])
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
-def test_rouge_n_full_size_configs(k):
+def test_rouge_n_full_size_configs(k, path):
     w = syn.make(k)
     for n in (1, 2, 4):
+        check(w, n, path=path)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5])
+@pytest.mark.parametrize("seed,B,R,V,L", [
+    (511, 21, 3, 7, 70),          # several references, empty rows included
+    (512, 9, 2, 50257, 300),
+    (513, 5, 1, 262144, 1500),    # 18-bit ids: 16-byte packed keys from order 4 on
+    (514, 4, 40, 300, 100),       # forty references
+])
+def test_rouge_n_global_path_random_ragged_batches(n, seed, B, R, V, L):
+    w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L)
+    check(w, n, path="global")
+    if R > 1:
+        check(w, n, beta=2.0, ref_count=syn.ref_counts(seed, w.B, w.R), path="global")
+
+
+@pytest.mark.parametrize("seed,B,R,V,L,parts", [
+    (521, 3, 1, 50257, 5000, 0),      # beyond the fused plans, one LDS table per group
+    (522, 2, 2, 300, 5467, 1),        # 16 401 slots per group: partitions per (group, order)
+    (523, 2, 1, 50257, 40000, 1),     # long generation, partitioned
+    (524, 2, 14, 300, 1500, 1),       # partitioned, references counted in passes
+])
+def test_rouge_n_beyond_the_fused_plans(seed, B, R, V, L, parts):
+    w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=L * 9 // 10)
+    cfg = tb.make_config(max_n=2, vocab_size=V)
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.fused_ok == 0 and (lay.global_partitions > 0) == bool(parts)
+    for n in (1, 2, 4):
         check(w, n)
+    check(w, 2, beta=0.5, ref_count=syn.ref_counts(seed, w.B, w.R) if R > 1 else None)
 
 
 def test_rouge_n_closed_forms_and_unsupported_shapes():
@@ -80,4 +111,9 @@ def test_rouge_n_closed_forms_and_unsupported_shapes():
     big = syn.random_small(507, B=2, R=2, vocab=50, max_len=9000)     # beyond the fused plans
     with pytest.raises(tb.TensorBLEUError):
         tb.tensorrouge_n(dev(big.cand), dev(big.cand_len), dev(big.refs), dev(big.ref_len), n=2,
-                         vocab_size=big.vocab)
+                         vocab_size=big.vocab, path="fused")
+    # 31-bit ids on the GLOBAL path: the packed-key kernels score BLEU only
+    wide = syn.random_small(508, B=2, R=1, vocab=2 ** 31 - 1, max_len=60)
+    with pytest.raises(tb.TensorBLEUError):
+        tb.tensorrouge_n(dev(wide.cand), dev(wide.cand_len), dev(wide.refs), dev(wide.ref_len),
+                         n=2, vocab_size=wide.vocab, path="global")
