@@ -17,7 +17,8 @@
  *     synchronised by the caller.
  *   - Layout: candidate i is the row `cand + i*cand_stride`, valid for `cand_len[i]` tokens;
  *     reference j of candidate i is the row `refs + (i*R + j)*ref_stride`, valid for
- *     `ref_len[i*R + j]` tokens.  Token ids are int32, or int64 when cfg->token_bytes == 8 (the
+ *     `ref_len[i*R + j]` tokens (or, with cfg->ref_offsets, row ref_offsets[i] + j of a packed
+ *     list of reference rows).  Token ids are int32, or int64 when cfg->token_bytes == 8 (the
  *     usual dtype of tokenizer output; read directly, no conversion pass).  Strides are in
  *     elements and bound the lengths; lengths are always int32; cells
  *     at or beyond a row's length are never interpreted (token id 0 inside the length is an
@@ -95,6 +96,19 @@ typedef struct tb_config {
                            n-grams, no part in the closest reference length).  Values outside
                            [1, R] are clamped and reported through TB_DEV_LENGTH_RANGE.  The
                            staged GLOBAL entry points must all see the same array. */
+  const int32_t* ref_offsets; /* optional DEVICE pointer [B + 1] (NULL: the fixed layout above):
+                           reference lists in CSR form, for batches whose candidates have very
+                           different numbers of references.  `refs` is then ref_rows packed rows
+                           of ref_stride elements and `ref_len` has one entry per row; candidate i
+                           owns the rows ref_offsets[i] .. ref_offsets[i + 1] - 1, its references
+                           in order.  The R argument of the call is the largest number of
+                           references any candidate has (it sizes workspace and plans; the
+                           ROUGE-N overlap output stays [B, R]).  A candidate without rows has no
+                           reference: its statistics and score are 0 and its closest reference
+                           length is 0.  Spans that leave [0, ref_rows] or hold more than R rows
+                           are clamped and reported through TB_DEV_LENGTH_RANGE, as is an empty
+                           span.  Not together with ref_count (TB_ERR_INVALID_ARG). */
+  int64_t ref_rows;     /* with ref_offsets: the number of reference rows in `refs` / `ref_len` */
 } tb_config_t;
 
 /* Optional integer outputs (each pointer may be NULL).  These are what the parity tests compare

@@ -65,6 +65,32 @@ def _p(a: np.ndarray, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct))
 
 
+def expand_reference_lists(refs: np.ndarray, ref_len: np.ndarray, ref_offsets: np.ndarray):
+    """Reference lists in CSR form -> the padded fixed-R form plus a per-candidate count.
+
+    refs [rows, Lr], ref_len [rows]; candidate i owns the rows ref_offsets[i] .. ref_offsets[i+1]-1
+    in order.  Returns refs [B, R, Lr], ref_len [B, R] (R = the largest list, at least 1), the
+    counts [B] and a mask [B] of candidates without any reference.  Such a candidate is given one
+    EMPTY reference: nothing can match it, so its statistics and score are 0 and its closest
+    reference length is 0 -- the reading taken for a candidate that has nothing to be compared
+    with.  Pure rearrangement of the inputs; all arithmetic stays in the routines that follow."""
+    refs = np.ascontiguousarray(refs, dtype=np.int32)
+    ref_len = np.ascontiguousarray(ref_len, dtype=np.int32)
+    off = np.asarray(ref_offsets, dtype=np.int64)
+    assert refs.ndim == 2 and ref_len.shape == (refs.shape[0],) and off.ndim == 1
+    assert off[0] >= 0 and (np.diff(off) >= 0).all() and off[-1] <= refs.shape[0]
+    B = off.size - 1
+    counts = np.diff(off).astype(np.int32)
+    R = max(int(counts.max()) if B else 1, 1)
+    out = np.zeros((B, R, refs.shape[1]), np.int32)
+    out_len = np.zeros((B, R), np.int32)
+    for i in range(B):
+        k = int(counts[i])
+        out[i, :k] = refs[off[i]:off[i] + k]
+        out_len[i, :k] = ref_len[off[i]:off[i] + k]
+    return out, out_len, np.maximum(counts, 1).astype(np.int32), counts == 0
+
+
 @dataclass
 class OracleResult:
     clipped: np.ndarray         # [B, N] int32
@@ -80,10 +106,16 @@ class OracleResult:
 def bleu(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.ndarray,
          max_n: int = 4, weights: Optional[Sequence[float]] = None, smoothing: str = "none",
          smooth_param: float = 0.0, threads: int = 1,
-         ref_count: Optional[np.ndarray] = None) -> OracleResult:
+         ref_count: Optional[np.ndarray] = None,
+         ref_offsets: Optional[np.ndarray] = None) -> OracleResult:
     """Per-sentence and corpus BLEU of a padded batch (see bleu_oracle.cpp for the definition).
 
-    ref_count [B] (optional): candidate i has only its first ref_count[i] references."""
+    ref_count [B] (optional): candidate i has only its first ref_count[i] references.
+    ref_offsets [B + 1] (optional): reference lists in CSR form, refs [rows, Lr], ref_len [rows]
+    (see expand_reference_lists)."""
+    if ref_offsets is not None:
+        assert ref_count is None
+        refs, ref_len, ref_count, _ = expand_reference_lists(refs, ref_len, ref_offsets)
     lib = _load()
     cand = np.ascontiguousarray(cand, dtype=np.int32)
     refs = np.ascontiguousarray(refs, dtype=np.int32)
@@ -164,7 +196,8 @@ class RougeResult:
 
 
 def rouge_n(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: np.ndarray,
-            n: int = 2, beta: float = 1.0, ref_count: Optional[np.ndarray] = None) -> RougeResult:
+            n: int = 2, beta: float = 1.0, ref_count: Optional[np.ndarray] = None,
+            ref_offsets: Optional[np.ndarray] = None) -> RougeResult:
     """ROUGE-N of every candidate against its references (Lin 2004; the paper's Section 6 names
     ROUGE as the first metric its counting method extends to).
 
@@ -175,6 +208,9 @@ def rouge_n(cand: np.ndarray, cand_len: np.ndarray, refs: np.ndarray, ref_len: n
     rational arithmetic (beta is taken as the exact value of the given double), so it does not
     depend on any rounding; the reported numbers are those fractions rounded to float64."""
     from fractions import Fraction
+    if ref_offsets is not None:     # CSR reference lists (see expand_reference_lists)
+        assert ref_count is None
+        refs, ref_len, ref_count, _ = expand_reference_lists(refs, ref_len, ref_offsets)
     lib = _load()
     cand = np.ascontiguousarray(cand, dtype=np.int32)
     refs = np.ascontiguousarray(refs, dtype=np.int32)

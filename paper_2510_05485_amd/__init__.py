@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     tensorbleu_static_scratch_bytes,
 )
 from .api import (  # noqa: F401
-    BleuScorer, corpus_bleu, lengths_from_padding, pad_references, rouge_n, sentence_bleu,
+    BleuScorer, corpus_bleu, lengths_from_padding, pack_reference_lists, pad_references, rouge_n,
+    sentence_bleu,
 )

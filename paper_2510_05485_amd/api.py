@@ -32,6 +32,12 @@ class BleuScorer:
 
     score_dtype=torch.bfloat16 stores the scores as bfloat16 (the fp32 score rounded to nearest
     even) for consumers that keep rewards in that type.
+
+    Conditions that only the kernels can see (a token id outside [0, vocab_size), a clamped
+    length or reference count, an overflowing table partition) are OR-ed into
+    `scorer.device_status` (int32 [1] on the GPU) by every call and make the scores of the rows
+    concerned unspecified; `scorer.check()` synchronises, raises if any bit is set and clears
+    them.  Poll it where a silent wrong reward would hurt (a mis-set vocab_size is enough).
     """
 
     def __init__(self, B: int, R: int, cand_stride: int, ref_stride: int, *, vocab_size: int,
@@ -46,7 +52,21 @@ class BleuScorer:
         self.workspace = _b.allocate_workspace(B, R, cand_stride, ref_stride, self.cfg, device)
         self.out = torch.empty(B, dtype=score_dtype, device=device)
         self.corpus_out = torch.zeros(1, dtype=score_dtype, device=device)
-        self.stats = _b.Stats.allocate(B, max_n, device) if want_stats else None
+        self.stats = (_b.Stats.allocate(B, max_n, device) if want_stats else
+                      _b.Stats(device_status=torch.zeros(1, dtype=torch.int32, device=device)))
+        self.device_status = self.stats.device_status
+
+    def check(self) -> None:
+        """Synchronise, raise TensorBLEUError if a kernel reported a condition since the last
+        check, and clear the status word."""
+        bits = int(self.device_status.item())
+        if bits:
+            self.device_status.zero_()
+            names = [n for n, b in (("token id out of range", _b.TB_DEV_TOKEN_RANGE),
+                                    ("length or reference count clamped", _b.TB_DEV_LENGTH_RANGE),
+                                    ("table partition overflow", _b.TB_DEV_TABLE_OVERFLOW))
+                     if bits & b]
+            raise _b.TensorBLEUError("device status " + str(bits) + ": " + ", ".join(names))
 
     def _check(self, cand, refs):
         B, R, cs, rs = self.shape
@@ -107,6 +127,27 @@ def rouge_n(cand, cand_len, refs, ref_len, *, n: int = 2, beta: float = 1.0, voc
     rc = None if ref_count is None else _len32(ref_count).contiguous()
     return _b.tensorrouge_n(cand, _len32(cand_len), refs, _len32(ref_len), n=n, beta=beta,
                             vocab_size=vocab_size, ref_count=rc, score_dtype=score_dtype)
+
+
+def pack_reference_lists(references, device="cuda:0", dtype=torch.int32):
+    """Lay out a ragged list of references in CSR form (tb_config_t.ref_offsets): no padding rows.
+
+    `references[i]` is the list of reference token sequences of candidate i.  Returns (rows
+    [total, L], row_len [total] int32, ref_offsets [B + 1] int32, max_refs) with the tensors on
+    `device`; pass them as make_config(ref_offsets=..., max_refs=...) and as `refs` / `ref_len`.
+    Host-side convenience: builds the arrays on the CPU and copies them once."""
+    flat = [seq for group in references for seq in group]
+    L = max(1, max((len(s) for s in flat), default=1))
+    rows = torch.zeros(max(len(flat), 1), L, dtype=dtype)
+    row_len = torch.zeros(max(len(flat), 1), dtype=torch.int32)
+    for r, seq in enumerate(flat):
+        t = torch.as_tensor(seq, dtype=dtype)
+        rows[r, :t.numel()] = t
+        row_len[r] = t.numel()
+    offsets = torch.zeros(len(references) + 1, dtype=torch.int32)
+    offsets[1:] = torch.cumsum(torch.tensor([len(g) for g in references], dtype=torch.int32), 0)
+    return (rows[:len(flat)].to(device), row_len[:len(flat)].to(device), offsets.to(device),
+            max((len(g) for g in references), default=1))
 
 
 def lengths_from_padding(tokens: torch.Tensor, pad_id: int) -> torch.Tensor:

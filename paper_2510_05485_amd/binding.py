@@ -35,7 +35,8 @@ class tb_config_t(ctypes.Structure):
                 ("smoothing", ctypes.c_int32), ("smooth_param", ctypes.c_float),
                 ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32),
                 ("token_bytes", ctypes.c_int32), ("score_bytes", ctypes.c_int32),
-                ("ref_count", ctypes.c_void_p)]
+                ("ref_count", ctypes.c_void_p), ("ref_offsets", ctypes.c_void_p),
+                ("ref_rows", ctypes.c_int64)]
 
 
 class tb_stats_t(ctypes.Structure):
@@ -120,9 +121,13 @@ def _check(rc: int, what: str) -> None:
 def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
                 smoothing: str = "none", smooth_param: float = 0.0, vocab_size: int = 1 << 16,
                 path: str = "auto", ref_count: Optional[torch.Tensor] = None,
-                score_dtype: torch.dtype = torch.float32) -> tb_config_t:
+                score_dtype: torch.dtype = torch.float32,
+                ref_offsets: Optional[torch.Tensor] = None, max_refs: int = 0) -> tb_config_t:
     """ref_count: optional int32 device tensor [B]; candidate i is scored against its first
     ref_count[i] references only.  The config keeps the tensor alive.
+    ref_offsets: optional int32 device tensor [B + 1]: reference lists in CSR form (`refs` is then
+    [rows, Lr] and `ref_len` [rows]; candidate i owns rows ref_offsets[i] .. ref_offsets[i+1]-1);
+    max_refs is the largest number of references of any candidate.
     score_dtype: torch.float32, or torch.bfloat16 for scores stored as bfloat16."""
     if score_dtype not in (torch.float32, torch.bfloat16):
         raise TensorBLEUError(f"score_dtype must be float32 or bfloat16 (got {score_dtype})")
@@ -145,6 +150,17 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
             raise TensorBLEUError("ref_count must be a contiguous int32 tensor of shape [B]")
         cfg.ref_count = ref_count.data_ptr()
         cfg._ref_count_tensor = ref_count      # keeps the device memory alive with the config
+    cfg.ref_offsets = None
+    cfg.ref_rows = 0
+    cfg._max_refs = 0
+    if ref_offsets is not None:
+        if ref_offsets.dtype != torch.int32 or not ref_offsets.is_contiguous() or \
+                ref_offsets.dim() != 1 or max_refs < 1 or ref_count is not None:
+            raise TensorBLEUError("ref_offsets must be a contiguous int32 tensor of shape [B + 1], "
+                                  "given with max_refs >= 1 and without ref_count")
+        cfg.ref_offsets = ref_offsets.data_ptr()
+        cfg._ref_offsets_tensor = ref_offsets
+        cfg._max_refs = int(max_refs)
     return cfg
 
 
@@ -200,6 +216,17 @@ def _batch(cand, cand_len, refs, ref_len, cfg: Optional[tb_config_t] = None) -> 
                               f"(got {cand.dtype}, {refs.dtype})")
     if cfg is not None:
         cfg.token_bytes = 8 if cand.dtype == torch.int64 else 4
+    if cfg is not None and cfg.ref_offsets:           # CSR reference lists
+        if cand.dim() != 2 or refs.dim() != 2 or tuple(ref_len.shape) != (refs.shape[0],):
+            raise TensorBLEUError("with ref_offsets: expected cand [B, Lc], refs [rows, Lr] and "
+                                  "ref_len [rows]")
+        B = int(cand.shape[0])
+        if tuple(cand_len.shape) != (B,) or cfg._ref_offsets_tensor.numel() != B + 1:
+            raise TensorBLEUError("expected cand_len [B] and ref_offsets [B + 1]")
+        cfg.ref_rows = int(refs.shape[0])
+        return _Batch(cand.contiguous(), cand_len.contiguous(), refs.contiguous(),
+                      ref_len.contiguous(), B, cfg._max_refs, int(cand.shape[1]),
+                      int(refs.shape[1]))
     if cand.dim() != 2 or refs.dim() != 3 or refs.shape[0] != cand.shape[0]:
         raise TensorBLEUError("expected cand [B, Lc] and refs [B, R, Lr]")
     B, R = int(cand.shape[0]), int(refs.shape[1])
@@ -304,12 +331,14 @@ def tensorrouge_n(cand, cand_len, refs, ref_len, n: int = 2, beta: float = 1.0, 
                   vocab_size: int, ref_count: Optional[torch.Tensor] = None,
                   want_overlap: bool = False, want_best: bool = False,
                   workspace: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
-                  stream=None, score_dtype: torch.dtype = torch.float32, path: str = "auto"):
+                  stream=None, score_dtype: torch.dtype = torch.float32, path: str = "auto",
+                  ref_offsets: Optional[torch.Tensor] = None, max_refs: int = 0):
     """ROUGE-N of every candidate against its references: float32 (or bfloat16) [B, 3] (precision,
     recall, F of the best reference), plus overlap int32 [B, R] and best-reference index int32 [B]
     on request (returned as a tuple then)."""
     cfg = make_config(max_n=n, smooth_param=beta, vocab_size=vocab_size, path=path,
-                      ref_count=ref_count, score_dtype=score_dtype)
+                      ref_count=ref_count, score_dtype=score_dtype, ref_offsets=ref_offsets,
+                      max_refs=max_refs)
     b = _batch(cand, cand_len, refs, ref_len, cfg)
     if workspace is None:
         workspace = allocate_workspace(b.B, b.R, b.cand_stride, b.ref_stride, cfg, b.cand.device)
@@ -343,7 +372,8 @@ def tensorbleu_pack(cand, cand_len, refs, ref_len, cfg, workspace, stats=None, s
 
 
 def _stage(entry, cand_len, ref_len, cand_stride, ref_stride, cfg, workspace, stats, stream):
-    B, R = int(ref_len.shape[0]), int(ref_len.shape[1])
+    B = int(cand_len.shape[0])
+    R = cfg._max_refs if cfg.ref_offsets else int(ref_len.shape[1])
     st = stats.as_struct() if stats is not None else None
     rc = getattr(load_library(), entry)(
         cand_len.data_ptr(), ref_len.data_ptr(), cand_stride, ref_stride, B, R, ctypes.byref(cfg),
@@ -366,7 +396,8 @@ def tensorbleu_count_clip(cand_len, ref_len, cand_stride, ref_stride, cfg, works
 
 def tensorbleu_finalize(cand_len, ref_len, cand_stride, ref_stride, cfg, corpus, out, workspace,
                         stats=None, stream=None):
-    B, R = int(ref_len.shape[0]), int(ref_len.shape[1])
+    B = int(cand_len.shape[0])
+    R = cfg._max_refs if cfg.ref_offsets else int(ref_len.shape[1])
     st = stats.as_struct() if stats is not None else None
     rc = load_library().tensorbleu_finalize(
         cand_len.data_ptr(), ref_len.data_ptr(), B, R, cand_stride, ref_stride, ctypes.byref(cfg),

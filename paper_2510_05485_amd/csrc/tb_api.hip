@@ -105,6 +105,7 @@ bool config_ok(const tb_config_t* cfg) {
   if (cfg->force_path < TB_PATH_AUTO || cfg->force_path > TB_PATH_GLOBAL) return false;
   if (cfg->token_bytes != 0 && cfg->token_bytes != 4 && cfg->token_bytes != 8) return false;
   if (cfg->score_bytes != 0 && cfg->score_bytes != 4 && cfg->score_bytes != 2) return false;
+  if (cfg->ref_offsets && (cfg->ref_count || cfg->ref_rows < 0)) return false;
   return true;
 }
 
@@ -227,6 +228,8 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   pb.refs = refs;
   pb.ref_len = ref_len;
   pb.ref_count = cfg->ref_count;
+  pb.ref_offsets = cfg->ref_offsets;
+  pb.ref_rows = cfg->ref_offsets ? cfg->ref_rows : 0;
   pb.cand_stride = cand_stride;
   pb.ref_stride = ref_stride;
   pb.group_cap = L.group_cap;

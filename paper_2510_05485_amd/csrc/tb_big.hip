@@ -23,8 +23,9 @@ struct BigArgs {
 
 __device__ __forceinline__ int big_seq_len(const Problem& pb, int g, int j) {
   if (j == 0) return clamped_len(pb.cand_len[g], pb.cand_stride, nullptr);
-  if (j > refs_used(pb, g)) return 0;  // reference not in use
-  return clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
+  const RefRows rr = ref_rows(pb, g);
+  if (j > rr.used) return 0;  // reference not in use
+  return clamped_len(pb.ref_len[rr.row0 + j - 1], pb.ref_stride, nullptr);
 }
 // First compact slot of sequence j for order n (j = R + 1: the group's n-gram count).
 __device__ __forceinline__ int64_t big_seq_start(const Problem& pb, int g, int n, int j) {

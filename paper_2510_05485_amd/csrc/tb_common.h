@@ -131,6 +131,10 @@ struct Problem {
   int32_t vocab;
   int32_t tok64;      // token ids are int64
   const int32_t* ref_count;  // per-candidate number of references in use, or null (= R)
+  const int32_t* ref_offsets;  // CSR reference lists: candidate g owns the reference rows
+                               // ref_offsets[g] .. ref_offsets[g + 1] - 1 (at most R); or null:
+                               // the fixed layout, rows g * R .. g * R + R - 1
+  int64_t ref_rows;   // CSR: number of reference rows (rows beyond are never touched)
   int32_t* status;    // may be null
 };
 
@@ -144,13 +148,43 @@ __device__ __forceinline__ int32_t load_token(const void* base, int64_t idx, int
   return static_cast<const int32_t*>(base)[idx];
 }
 
-// References candidate g is scored against: all R, or the caller's count clamped into [1, R]
-// (`flag`: report a clamped count; set by one thread per group only).
+// Where candidate g's references are: rows row0 .. row0 + used - 1 of `refs` and `ref_len`.
+// Fixed layout: row0 = g * R, used = R or the caller's count clamped into [1, R].  CSR: the span
+// the offsets give, clamped into the reference rows that exist and to at most R rows (a candidate
+// may then have no reference at all: used = 0).  `flag`: report a clamped count (set by one thread
+// per group only).
+struct RefRows {
+  int64_t row0;
+  int used;
+};
+__device__ __forceinline__ RefRows ref_rows(const Problem& pb, int g, bool flag = false) {
+  RefRows r;
+  if (pb.ref_offsets) {
+    const int64_t b = pb.ref_offsets[g], e = pb.ref_offsets[g + 1];
+    const int64_t row0 = min(max(b, int64_t(0)), max(pb.ref_rows, int64_t(0)));
+    const int64_t used = min(min(max(e - row0, int64_t(0)), int64_t(pb.R)), pb.ref_rows - row0);
+    if (flag && (row0 != b || used != e - b || used < 1) && pb.status)
+      atomicOr(pb.status, TB_DEV_LENGTH_RANGE);
+    r.row0 = row0;
+    r.used = int(max(used, int64_t(0)));
+    return r;
+  }
+  r.row0 = int64_t(g) * pb.R;
+  r.used = pb.R;
+  if (pb.ref_count) {
+    const int c = pb.ref_count[g];
+    if (flag && (c < 1 || c > pb.R) && pb.status) atomicOr(pb.status, TB_DEV_LENGTH_RANGE);
+    r.used = min(max(c, 1), pb.R);
+  }
+  return r;
+}
 __device__ __forceinline__ int refs_used(const Problem& pb, int g, bool flag = false) {
-  if (!pb.ref_count) return pb.R;
-  const int c = pb.ref_count[g];
-  if (flag && (c < 1 || c > pb.R) && pb.status) atomicOr(pb.status, TB_DEV_LENGTH_RANGE);
-  return min(max(c, 1), pb.R);
+  return ref_rows(pb, g, flag).used;
+}
+// Rows of `ref_len` that may be read for candidate g without knowing `used`: all R in the fixed
+// layout (they exist), only the candidate's own with CSR.
+__device__ __forceinline__ int ref_rows_readable(const Problem& pb, const RefRows& r) {
+  return pb.ref_offsets ? r.used : pb.R;
 }
 
 // Length of a row as the kernels use it: clamped into [0, stride].

@@ -18,8 +18,8 @@ __global__ __launch_bounds__(256) void sentence_score_kernel(FinalArgs a) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= pb.B) return;
   const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
-  const int r = closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, refs_used(pb, i, true),
-                                pb.ref_stride, pb.status);
+  const RefRows rr = ref_rows(pb, i, true);
+  const int r = closest_ref_len(c, pb.ref_len + rr.row0, rr.used, pb.ref_stride, pb.status);
   a.st.closest[i] = r;
   int cl[8], to[8];
 #pragma unroll
@@ -50,9 +50,8 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
   for (int k = 0; k < 18; ++k) acc[k] = 0;
   for (int i = threadIdx.x; i < pb.B; i += blockDim.x) {
     const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
-    const int r =
-        closest_ref_len(c, pb.ref_len + int64_t(i) * pb.R, refs_used(pb, i, true), pb.ref_stride,
-                        pb.status);
+    const RefRows rr = ref_rows(pb, i, true);
+    const int r = closest_ref_len(c, pb.ref_len + rr.row0, rr.used, pb.ref_stride, pb.status);
     a.st.closest[i] = r;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
@@ -109,7 +108,8 @@ __global__ __launch_bounds__(256) void rouge_score_kernel(RougeFinalArgs a) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= pb.B) return;
   const int N = pb.N, R = pb.R;
-  const int used = refs_used(pb, i, true);
+  const RefRows rr = ref_rows(pb, i, true);
+  const int used = rr.used;
   const int c = clamped_len(pb.cand_len[i], pb.cand_stride, pb.status);
   const float ct = float(max(c - N + 1, 0));
   int best_j = 0;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void rouge_score_kernel(RougeFinalArgs a) {
     const int ov = j < used ? a.overlap[int64_t(i) * R + j] : 0;
     if (a.overlap_out) a.overlap_out[int64_t(i) * R + j] = ov;
     if (j >= used) continue;
-    const int len = clamped_len(pb.ref_len[int64_t(i) * R + j], pb.ref_stride, pb.status);
+    const int len = clamped_len(pb.ref_len[rr.row0 + j], pb.ref_stride, pb.status);
     const float rt = float(max(len - N + 1, 0));
     const float key = ov > 0 ? float(ov) / __fmaf_rn(a.beta2, rt, ct) : 0.0f;
     if (key > best_key) {

@@ -207,12 +207,13 @@ void fused_kernel(FusedArgs a) {
   // lane j of every wavefront: length of sequence j and the inclusive prefix of lengths
   // (a reference beyond the candidate's reference count has length 0 and no say in the closest
   // reference length)
-  const int used = refs_used(pb, g, tid == 0);
+  const RefRows rr = ref_rows(pb, g, tid == 0);
+  const int used = rr.used;
   int my_len = 0;
   if (lane <= used) {
     my_len = (lane == 0)
         ? clamped_len(pb.cand_len[g], pb.cand_stride, wave == 0 ? pb.status : nullptr)
-        : clamped_len(pb.ref_len[int64_t(g) * R + lane - 1], pb.ref_stride,
+        : clamped_len(pb.ref_len[rr.row0 + lane - 1], pb.ref_stride,
                       wave == 0 ? pb.status : nullptr);
   }
   const int incl = wave_inclusive_scan(my_len);
@@ -248,7 +249,7 @@ void fused_kernel(FusedArgs a) {
       }
     }
     const int64_t cand_row = int64_t(g) * pb.cand_stride;
-    const int64_t ref_rows = int64_t(g) * R * pb.ref_stride;
+    const int64_t ref_rows = rr.row0 * pb.ref_stride;
     int32_t t[SITEMS];
 #pragma unroll
     for (int i = 0; i < SITEMS; ++i) {

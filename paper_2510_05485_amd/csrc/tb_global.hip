@@ -63,9 +63,10 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(PackArgs a) {
     j = 1 + rem / a.ref_chunks;
     chunk = rem % a.ref_chunks;
     rows = pb.refs;
-    row = (int64_t(g) * pb.R + j - 1) * pb.ref_stride;
-    len = clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, pb.status);
-    if (j > refs_used(pb, g)) len = 0;  // reference not in use
+    const RefRows rr = ref_rows(pb, g);
+    row = (rr.row0 + j - 1) * pb.ref_stride;
+    len = j <= rr.used ? clamped_len(pb.ref_len[rr.row0 + j - 1], pb.ref_stride, pb.status)
+                       : 0;  // reference not in use
   }
   const int p0 = chunk * kPackTile;
   if (p0 >= len) return;  // uniform over the workgroup

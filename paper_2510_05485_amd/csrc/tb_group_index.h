@@ -10,8 +10,9 @@ namespace tb {
 // A reference beyond the candidate's reference count has no n-grams: length 0.
 __device__ __forceinline__ int seq_len(const Problem& pb, int g, int j) {
   if (j == 0) return clamped_len(pb.cand_len[g], pb.cand_stride, nullptr);
-  if (j > refs_used(pb, g)) return 0;
-  return clamped_len(pb.ref_len[int64_t(g) * pb.R + j - 1], pb.ref_stride, nullptr);
+  const RefRows rr = ref_rows(pb, g);
+  if (j > rr.used) return 0;
+  return clamped_len(pb.ref_len[rr.row0 + j - 1], pb.ref_stride, nullptr);
 }
 
 // Where each sequence of group g starts inside the group's compact slot range for order n.
@@ -44,8 +45,7 @@ class GroupIndex {
       // fields would otherwise be turned into one vector load from a selected address)
       const int cs = __builtin_amdgcn_readfirstlane(int(min(pb_.cand_stride, int64_t(1) << 30)));
       const int rs = __builtin_amdgcn_readfirstlane(int(min(pb_.ref_stride, int64_t(1) << 30)));
-      const int used = min(max(used_, 1), pb_.R);  // references in use
-      const int len = lane <= used ? clamped_len(raw_, lane == 0 ? cs : rs, nullptr) : 0;
+      const int len = lane <= used_ ? clamped_len(raw_, lane == 0 ? cs : rs, nullptr) : 0;
       incl_ = wave_inclusive_scan(max(len - n + 1, 0));
     }
   }
@@ -65,11 +65,12 @@ class GroupIndex {
   __device__ __forceinline__ void load_raw() {
     const int lane = threadIdx.x & (kWave - 1);
     raw_ = 0;
+    const RefRows rr = ref_rows(pb_, g_);
     if (lane == 0)
       raw_ = pb_.cand_len[g_];
-    else if (lane <= pb_.R)
-      raw_ = pb_.ref_len[int64_t(g_) * pb_.R + lane - 1];
-    if (pb_.ref_count) used_ = pb_.ref_count[g_];
+    else if (lane <= ref_rows_readable(pb_, rr))
+      raw_ = pb_.ref_len[rr.row0 + lane - 1];
+    used_ = rr.used;
   }
   const Problem& pb_;
   int g_, n_;

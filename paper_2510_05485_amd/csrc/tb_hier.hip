@@ -134,11 +134,12 @@ void hier_dictionary_kernel(HierDictArgs a) {
   // lane j: stored length of sequence j (requested first, clamped once the key requests below
   // are out: a wavefront's loads return in order, so the lengths arrive first)
   int raw_len = 0;
+  const RefRows rr = ref_rows(pb, g);
+  const int used = rr.used;
   if (lane == 0)
     raw_len = pb.cand_len[g];
-  else if (lane <= R)
-    raw_len = pb.ref_len[int64_t(g) * R + lane - 1];
-  const int used = refs_used(pb, g);
+  else if (lane <= ref_rows_readable(pb, rr))
+    raw_len = pb.ref_len[rr.row0 + lane - 1];
   // Low dwords of the order-1 keys, requested before the lengths are known: at order 1 the slot
   // of a position is the position itself (slots past the group's tokens hold stale bytes that
   // are never used).

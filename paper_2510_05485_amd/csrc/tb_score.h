@@ -6,9 +6,11 @@
 
 namespace tb {
 
-// Reference length closest to c; the shorter one on ties.  R >= 1.
+// Reference length closest to c; the shorter one on ties.  No reference at all (possible with
+// CSR reference lists only): 0.
 __device__ __forceinline__ int closest_ref_len(int c, const int32_t* ref_len, int R,
                                                int64_t ref_stride, int32_t* status) {
+  if (R < 1) return 0;
   int best = clamped_len(ref_len[0], ref_stride, status);
   int bd = abs(best - c);
   for (int j = 1; j < R; ++j) {

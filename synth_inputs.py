@@ -307,3 +307,19 @@ def ref_counts(seed: int, B: int, R: int) -> np.ndarray:
     """Per-candidate number of references in use, uniform in 1..R (for ragged reference counts)."""
     u = uniforms(seed, 0, 15, B)
     return (np.minimum(np.floor(u * R), R - 1) + 1).astype(np.int32)
+
+
+def pack_reference_lists(refs: np.ndarray, ref_len: np.ndarray, counts: np.ndarray):
+    """Fixed-R references [B, R, Lr] with per-candidate counts -> reference lists in CSR form:
+    rows [sum(counts), Lr], their lengths [rows], offsets [B + 1] (candidate i owns the rows
+    offsets[i] .. offsets[i + 1] - 1, its first counts[i] references in order).  Layout only."""
+    B = refs.shape[0]
+    offsets = np.zeros(B + 1, np.int32)
+    offsets[1:] = np.cumsum(counts)
+    rows = np.zeros((int(offsets[-1]), refs.shape[2]), np.int32)
+    lens = np.zeros(int(offsets[-1]), np.int32)
+    for i in range(B):
+        k = int(counts[i])
+        rows[offsets[i]:offsets[i] + k] = refs[i, :k]
+        lens[offsets[i]:offsets[i] + k] = ref_len[i, :k]
+    return rows, lens, offsets

@@ -181,6 +181,37 @@ def test_pad_references_with_ragged_reference_lists():
         assert abs(float(out[i]) - ref.bleu[0]) <= 1e-5
 
 
+def test_pack_reference_lists_and_scorer_status_check():
+    rng = np.random.default_rng(6)
+    B, V = 10, 30
+    cands = [rng.integers(0, V, rng.integers(5, 30)).tolist() for _ in range(B)]
+    refs = [[rng.integers(0, V, rng.integers(3, 35)).tolist() for _ in range(rng.integers(1, 7))]
+            for _ in range(B)]
+    rows, row_len, offsets, max_refs = tb.pack_reference_lists(refs)
+    assert rows.shape[0] == sum(len(g) for g in refs) and max_refs == max(len(g) for g in refs)
+    L = max(len(c) for c in cands)
+    cand = np.zeros((B, L), np.int32)
+    for i, c in enumerate(cands):
+        cand[i, :len(c)] = c
+    cand_len = np.array([len(c) for c in cands], np.int32)
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    cfg = tb.make_config(vocab_size=V, smoothing="exp", ref_offsets=offsets, max_refs=max_refs)
+    out = tb.tensorbleu_sentence(to(cand), to(cand_len), rows, row_len, cfg).cpu().numpy()
+    ref = oracle.bleu(cand, cand_len, rows.cpu().numpy(), row_len.cpu().numpy(), smoothing="exp",
+                      ref_offsets=offsets.cpu().numpy())
+    assert np.abs(out.astype(np.float64) - ref.bleu).max() <= 1e-5
+    # the scorer's status word: clean after a good call, raised (and cleared) after a bad one
+    w = syn.random_small(88, B=6, R=1, vocab=50, max_len=40, min_len=10)
+    scorer = tb.BleuScorer(w.B, 1, w.cand.shape[1], w.refs.shape[2], vocab_size=50)
+    scorer(to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len))
+    scorer.check()
+    narrow = tb.BleuScorer(w.B, 1, w.cand.shape[1], w.refs.shape[2], vocab_size=8)
+    narrow(to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len))
+    with pytest.raises(tb.TensorBLEUError, match="token id out of range"):
+        narrow.check()
+    narrow.check()                                     # cleared by the failed check
+
+
 def test_plain_c_caller_of_the_abi():
     """The C ABI is usable without PyTorch: a C99 program (built beforehand by build.py) links the
     library, runs both paths on three closed-form cases and compares them itself."""

@@ -564,3 +564,38 @@ def test_more_than_four_orders_closed_forms_and_brute_force(N):
         refs = [w.refs[i, j, :w.ref_len[i, j]].tolist() for j in range(w.R)]
         clipped, total = brute_force_stats(w.cand[i, :w.cand_len[i]].tolist(), refs, N)
         assert res.clipped[i].tolist() == clipped and res.total[i].tolist() == total
+
+
+# ------------------------------------------------------------------- reference lists (CSR)
+
+def test_reference_lists_equal_each_candidate_scored_alone_with_its_own_references():
+    """A batch with reference lists of different lengths is, by definition, every candidate
+    scored against its own list: the CSR form must equal B separate single-candidate calls."""
+    w = syn.random_small(91, B=14, R=5, vocab=9, max_len=26, min_len=3)
+    counts = syn.ref_counts(91, w.B, w.R)
+    rows, lens, offsets = syn.pack_reference_lists(w.refs, w.ref_len, counts)
+    assert rows.shape[0] == counts.sum() and offsets[-1] == counts.sum()
+    res = oracle.bleu(w.cand, w.cand_len, rows, lens, smoothing="add-k", smooth_param=1.0,
+                      ref_offsets=offsets)
+    for i in range(w.B):
+        k = int(counts[i])
+        alone = oracle.bleu(w.cand[i:i + 1], w.cand_len[i:i + 1], w.refs[i:i + 1, :k],
+                            w.ref_len[i:i + 1, :k], smoothing="add-k", smooth_param=1.0)
+        assert res.clipped[i].tolist() == alone.clipped[0].tolist()
+        assert res.closest_ref_len[i] == alone.closest_ref_len[0]
+        assert res.bleu[i] == alone.bleu[0]
+        rouge = oracle.rouge_n(w.cand, w.cand_len, rows, lens, n=2, ref_offsets=offsets)
+        rouge_alone = oracle.rouge_n(w.cand[i:i + 1], w.cand_len[i:i + 1], w.refs[i:i + 1, :k],
+                                     w.ref_len[i:i + 1, :k], n=2)
+        assert rouge.overlap[i, :k].tolist() == rouge_alone.overlap[0].tolist()
+        assert rouge.best[i] == rouge_alone.best[0]
+
+
+def test_a_candidate_without_references_matches_nothing():
+    cand, cl, ref, rl = pad_batch([[1, 2, 3, 4, 5], [1, 2, 3, 4, 5]], [[[1, 2, 3, 4, 5]]] * 2)
+    rows, lens = ref[:1, 0], rl[:1, 0]
+    res = oracle.bleu(cand, cl, rows, lens, smoothing="floor", smooth_param=0.1,
+                      ref_offsets=np.array([0, 1, 1]))
+    assert res.bleu.tolist() == [1.0, 0.0]
+    assert res.clipped[1].tolist() == [0, 0, 0, 0] and res.total[1].tolist() == [5, 4, 3, 2]
+    assert res.closest_ref_len.tolist() == [5, 0]
