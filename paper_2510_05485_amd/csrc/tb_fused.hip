@@ -17,6 +17,18 @@
 #include "tb_kernels.h"
 #include "tb_score.h"
 
+// Phase time stamps for tuning builds only (-DTB_STAMPS), as in the hierarchical kernels.
+#ifdef TB_STAMPS
+__device__ unsigned long long tb_fused_stamps[8192 * 32];
+#define TB_FSTAMP(i) \
+  do { if (threadIdx.x == 0 && blockIdx.x < 8192) tb_fused_stamps[blockIdx.x * 32 + (i)] = wall_clock64(); } while (0)
+extern "C" int tb_debug_stamps_fused(unsigned long long* host, int count) {
+  return int(hipMemcpyFromSymbol(host, HIP_SYMBOL(tb_fused_stamps), size_t(count) * 8));
+}
+#else
+#define TB_FSTAMP(i) do {} while (0)
+#endif
+
 namespace tb {
 
 constexpr int kMaxFusedSeqs = kWave;  // candidate + references handled by one lane each
@@ -37,6 +49,7 @@ struct FusedArgs {
   int table_shift;      // 32 - log2(table_slots)
   int words;            // 32-bit counter words per id: ceil((R + 1) / 2)
   int list_per_wave;    // work-list entries reserved for each wavefront
+  int progress_priority;  // 1: wavefronts of a workgroup that is behind get the higher priority
   uint32_t off_ids, off_cnt, off_cstate, off_tok, off_list;
 };
 
@@ -46,7 +59,7 @@ static size_t fused_layout(int slots, int64_t cand_stride, int64_t cap, int list
   plan->off_ids = off;
   off += size_t(slots) * 2;
   plan->off_cnt = off;
-  off += size_t(cand_stride) * words * 4;
+  off += (size_t(cand_stride) * words * 4 + 15) & ~size_t(15);  // cleared in 16-byte stores
   plan->off_cstate = off;
   off += size_t(cand_stride) * 4;
   plan->off_tok = off;
@@ -203,6 +216,8 @@ void fused_kernel(FusedArgs a) {
   uint32_t* my_list = reinterpret_cast<uint32_t*>(smem + a.off_list) + wave * a.list_per_wave;
   const ProbeTable dict{table, uint32_t(T) - 1u, a.table_shift};
   const int bits = pb.bits;
+  TB_FSTAMP(0);
+  if (a.progress_priority) __builtin_amdgcn_s_setprio(3);  // staging: as the first order, below
 
   // lane j of every wavefront: length of sequence j and the inclusive prefix of lengths
   // (a reference beyond the candidate's reference count has length 0 and no say in the closest
@@ -225,27 +240,44 @@ void fused_kernel(FusedArgs a) {
   const int total_tokens = min(lane_value(incl, R), SITEMS * nt);
   const int cand_len = lane_value(my_len, 0);
 
-  for (int s = tid; s < T; s += nt) table[s] = kEmptySlot;
-  for (int s = tid; s < cand_len * int(W); s += nt) cnt[s] = 0;
-  for (int s = tid; s < cand_len; s += nt) cstate[s] = 0;
+  {
+    // 16-byte stores (table and counters start on 16-byte boundaries and the counters' area is
+    // a whole number of them)
+    uint4* t4 = reinterpret_cast<uint4*>(table);
+    for (int q = tid; q < T / 4; q += nt)
+      t4[q] = make_uint4(kEmptySlot, kEmptySlot, kEmptySlot, kEmptySlot);
+    uint4* c4 = reinterpret_cast<uint4*>(cnt);
+    for (int q = tid; q < (cand_len * int(W) + 3) / 4; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
+    for (int s = tid; s < cand_len; s += nt) cstate[s] = 0;
+  }
 
   // stage the tokens back to back: candidate, reference 0, reference 1, ...  All of a thread's
   // loads are issued before the first one is consumed (one round trip to memory, not one per
   // position).
   {
+    // sequence of each position and where it begins: the 64 positions of a wavefront usually
+    // lie in one sequence, which one ballot over the lanes holding the sequence ends finds
     int seq[SITEMS], begin[SITEMS];
-#pragma unroll
-    for (int i = 0; i < SITEMS; ++i) {
-      seq[i] = 0;
-      begin[i] = 0;
-    }
-    for (int m = 1; m <= R; ++m) {
-      const int bm = lane_value(incl, m - 1);
+    {
+      const int ends = (lane <= R) ? incl : 0x7FFFFFFF;
+      const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
 #pragma unroll
       for (int i = 0; i < SITEMS; ++i) {
-        const bool ge = tid + i * nt >= bm;
-        seq[i] = ge ? m : seq[i];
-        begin[i] = ge ? bm : begin[i];
+        const int k0 = wave_first + i * nt;
+        const int f0 = min(int(__popcll(__builtin_amdgcn_ballot_w64(ends <= k0))), R);
+        int sq = f0, bg = f0 > 0 ? __builtin_amdgcn_readlane(incl, max(f0 - 1, 0)) : 0;
+        if (k0 + kWave > __builtin_amdgcn_readlane(incl, f0)) {  // uniform: the block straddles
+          const int f1 =
+              min(int(__popcll(__builtin_amdgcn_ballot_w64(ends <= k0 + kWave - 1))), R);
+          for (int q = f0; q < f1; ++q) {
+            const int e = __builtin_amdgcn_readlane(incl, q);
+            const bool ge = k0 + lane >= e;
+            sq = ge ? q + 1 : sq;
+            bg = ge ? e : bg;
+          }
+        }
+        seq[i] = sq;
+        begin[i] = bg;
       }
     }
     const int64_t cand_row = int64_t(g) * pb.cand_stride;
@@ -289,21 +321,24 @@ void fused_kernel(FusedArgs a) {
     f_hi += (slice_begin + todo - 1 >= bm) ? 1 : 0;
   }
   __syncthreads();
+  TB_FSTAMP(1);
 
 #pragma unroll 1
   for (int n = 1; n <= N; ++n) {
-#ifndef TB_NO_PRIO
     // Two workgroups share a compute unit, and its arbiter serves the older wavefronts first:
     // left alone, the workgroup dispatched first finishes early and the other one then runs
     // alone on a half-empty unit.  A workgroup that is behind (a lower order) therefore gets
-    // the higher priority, which keeps the two within an order of each other.
-    switch (n) {
-      case 1: __builtin_amdgcn_s_setprio(3); break;
-      case 2: __builtin_amdgcn_s_setprio(2); break;
-      case 3: __builtin_amdgcn_s_setprio(1); break;
-      default: __builtin_amdgcn_s_setprio(0); break;
+    // the higher priority, which keeps the two within an order of each other.  (Only for
+    // batches of at most two rounds of workgroups: with more, fresh workgroups at the highest
+    // priority would hold up the nearly finished ones whose slots the next round waits for.)
+    if (a.progress_priority) {
+      switch (n) {
+        case 1: __builtin_amdgcn_s_setprio(3); break;
+        case 2: __builtin_amdgcn_s_setprio(2); break;
+        case 3: __builtin_amdgcn_s_setprio(1); break;
+        default: __builtin_amdgcn_s_setprio(0); break;
+      }
     }
-#endif
     if (n >= 2) __syncthreads();  // every slot of the previous order has been emptied
 
     // ---- A: candidate n-grams claim or find their entry
@@ -316,6 +351,7 @@ void fused_kernel(FusedArgs a) {
       cstate[k] = s | (won ? 0x80000000u : 0u);
     }
     __syncthreads();
+    TB_FSTAMP(2 + (n - 1) * 3);
 
     // ---- B: candidate counts (field 0 of the entry's id) ...
     for (int k = tid; k + n <= cand_len; k += nt) {
@@ -361,6 +397,7 @@ void fused_kernel(FusedArgs a) {
     }
     todo = kept;
     __syncthreads();
+    TB_FSTAMP(3 + (n - 1) * 3);
 
     // ---- C: the position that created an entry clips it (max over the reference fields, min
     // with the candidate field), zeroes its counters and empties its slot
@@ -390,8 +427,10 @@ void fused_kernel(FusedArgs a) {
     }
     part = wave_sum(part);
     if (lane == 0 && part != 0) atomicAdd(&s_part[n - 1], part);
+    TB_FSTAMP(4 + (n - 1) * 3);
   }
   __syncthreads();
+  TB_FSTAMP(2 + N * 3);
 
   // wavefront 0: lane n < N owns order n + 1 (statistics out, one logarithm each)
   if (wave == 0) {
@@ -498,6 +537,13 @@ hipError_t launch_fused(const Problem& pb, const FusedPlan& plan, const StatPtrs
   a.table_shift = 32 - lg;
   a.words = plan.words;
   a.list_per_wave = plan.list_per_wave;
+  {
+    // workgroups a compute unit holds at once (2048 threads, 160 KB of LDS), times 256 units
+    const int by_threads = 2048 / plan.threads;
+    const int by_lds = int(size_t(kLdsBudget) / (plan.lds_bytes + 512));
+    const int resident = 256 * (by_threads < by_lds ? by_threads : (by_lds < 1 ? 1 : by_lds));
+    a.progress_priority = pb.B <= 2 * resident ? 1 : 0;
+  }
   a.off_ids = uint32_t(plan.off_ids);
   a.off_cnt = uint32_t(plan.off_cnt);
   a.off_cstate = uint32_t(plan.off_cstate);
