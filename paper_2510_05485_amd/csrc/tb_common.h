@@ -148,6 +148,15 @@ __device__ __forceinline__ int32_t load_token(const void* base, int64_t idx, int
   return static_cast<const int32_t*>(base)[idx];
 }
 
+// A load from an INPUT array (memory no kernel of the running call writes) at an address that is
+// the same in every lane: read through the constant address space, so that it goes through the
+// scalar cache -- no vector-memory round trip with a wait for every other outstanding vector load
+// of the wavefront behind it.
+__device__ __forceinline__ int32_t uniform_load(const int32_t* p, int64_t i) {
+  typedef const int32_t __attribute__((address_space(4))) * constant_ptr;
+  return *(constant_ptr)(p + i);
+}
+
 // Where candidate g's references are: rows row0 .. row0 + used - 1 of `refs` and `ref_len`.
 // Fixed layout: row0 = g * R, used = R or the caller's count clamped into [1, R].  CSR: the span
 // the offsets give, clamped into the reference rows that exist and to at most R rows (a candidate
@@ -160,7 +169,7 @@ struct RefRows {
 __device__ __forceinline__ RefRows ref_rows(const Problem& pb, int g, bool flag = false) {
   RefRows r;
   if (pb.ref_offsets) {
-    const int64_t b = pb.ref_offsets[g], e = pb.ref_offsets[g + 1];
+    const int64_t b = uniform_load(pb.ref_offsets, g), e = uniform_load(pb.ref_offsets, g + 1);
     const int64_t row0 = min(max(b, int64_t(0)), max(pb.ref_rows, int64_t(0)));
     const int64_t used = min(min(max(e - row0, int64_t(0)), int64_t(pb.R)), pb.ref_rows - row0);
     if (flag && (row0 != b || used != e - b || used < 1) && pb.status)
@@ -172,7 +181,7 @@ __device__ __forceinline__ RefRows ref_rows(const Problem& pb, int g, bool flag 
   r.row0 = int64_t(g) * pb.R;
   r.used = pb.R;
   if (pb.ref_count) {
-    const int c = pb.ref_count[g];
+    const int c = uniform_load(pb.ref_count, g);
     if (flag && (c < 1 || c > pb.R) && pb.status) atomicOr(pb.status, TB_DEV_LENGTH_RANGE);
     r.used = min(max(c, 1), pb.R);
   }

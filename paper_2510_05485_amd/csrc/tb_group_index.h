@@ -64,12 +64,13 @@ class GroupIndex {
   // lane j <= R: the stored length of sequence j; other lanes: 0
   __device__ __forceinline__ void load_raw() {
     const int lane = threadIdx.x & (kWave - 1);
-    raw_ = 0;
     const RefRows rr = ref_rows(pb_, g_);
-    if (lane == 0)
-      raw_ = pb_.cand_len[g_];
-    else if (lane <= ref_rows_readable(pb_, rr))
-      raw_ = pb_.ref_len[rr.row0 + lane - 1];
+    // (two separate values and a select: an if / else over one variable would make the compiler
+    // wait for the vector load where the branches join)
+    const int raw_cand = uniform_load(pb_.cand_len, g_);
+    int raw_ref = 0;
+    if (lane >= 1 && lane <= ref_rows_readable(pb_, rr)) raw_ref = pb_.ref_len[rr.row0 + lane - 1];
+    raw_ = lane == 0 ? raw_cand : raw_ref;
     used_ = rr.used;
   }
   const Problem& pb_;

@@ -33,7 +33,8 @@
 #ifdef TB_STAMPS
 __device__ unsigned long long tb_stamps[8192 * 32];
 #define TB_STAMP(i) \
-  do { if (threadIdx.x == 0 && blockIdx.x < 8192) tb_stamps[blockIdx.x * 32 + (i)] = wall_clock64(); } while (0)
+  do { const unsigned wg_ = blockIdx.y * gridDim.x + blockIdx.x; \
+       if (threadIdx.x == 0 && wg_ < 8192) tb_stamps[wg_ * 32 + (i)] = wall_clock64(); } while (0)
 extern "C" int tb_debug_stamps(unsigned long long* host, int count) {
   return int(hipMemcpyFromSymbol(host, HIP_SYMBOL(tb_stamps), size_t(count) * 8));
 }
@@ -133,13 +134,13 @@ void hier_dictionary_kernel(HierDictArgs a) {
   TB_STAMP(0);
   // lane j: stored length of sequence j (requested first, clamped once the key requests below
   // are out: a wavefront's loads return in order, so the lengths arrive first)
-  int raw_len = 0;
   const RefRows rr = ref_rows(pb, g);
   const int used = rr.used;
-  if (lane == 0)
-    raw_len = pb.cand_len[g];
-  else if (lane <= ref_rows_readable(pb, rr))
-    raw_len = pb.ref_len[rr.row0 + lane - 1];
+  // (two separate values, selected after the key requests are out: an if / else over one
+  // variable makes the compiler wait for the vector load where the branches join)
+  const int raw_cand = uniform_load(pb.cand_len, g);
+  int raw_ref = 0;
+  if (lane >= 1 && lane <= ref_rows_readable(pb, rr)) raw_ref = pb.ref_len[rr.row0 + lane - 1];
   // Low dwords of the order-1 keys, requested before the lengths are known: at order 1 the slot
   // of a position is the position itself (slots past the group's tokens hold stale bytes that
   // are never used).
@@ -156,6 +157,7 @@ void hier_dictionary_kernel(HierDictArgs a) {
   // hold the group's token count
   const int cs = __builtin_amdgcn_readfirstlane(int(min(pb.cand_stride, int64_t(1) << 30)));
   const int rs = __builtin_amdgcn_readfirstlane(int(min(pb.ref_stride, int64_t(1) << 30)));
+  const int raw_len = lane == 0 ? raw_cand : raw_ref;
   const int my_len = (lane <= used) ? min(max(raw_len, 0), lane == 0 ? cs : rs) : 0;
   const int incl = wave_inclusive_scan(my_len);
   const int total = min(lane_value(incl, R), ITEMS * nt);
@@ -337,9 +339,9 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
   const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const bool rouge = a.rouge_overlap != nullptr;  // then split == 1, OPW == 1, order N only
-  const int g = blockIdx.x / a.split;
+  const int g = blockIdx.x;  // grid: (groups, workgroups per group)
   const int R = pb.R, N = pb.N;
-  const int first_order = rouge ? N : int(blockIdx.x % a.split) + 1;
+  const int first_order = rouge ? N : int(blockIdx.y) + 1;
   const uint32_t W = uint32_t(a.words);
   const int cap = int(pb.group_cap);
   uint32_t* cnt = reinterpret_cast<uint32_t*>(smem);
@@ -355,7 +357,8 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
   int uc[OPW];
 #pragma unroll
   for (int o = 0; o < OPW; ++o)
-    uc[o] = a.cand_distinct[int64_t(g) * N + min(first_order + o * a.split, N) - 1];
+    uc[o] = uniform_load(a.cand_distinct,
+                         int64_t(g) * N + min(first_order + o * a.split, N) - 1);
   // counters of all orders: cleared while the lengths are on their way
   {
     uint4* c4 = reinterpret_cast<uint4*>(cnt);
@@ -537,8 +540,13 @@ hipError_t launch_dict_items(const HierDictArgs& a, const HierPlan& plan, hipStr
 
 template <int ROWS, int OPW>
 hipError_t launch_count_shape(const HierCountArgs& a, int threads, hipStream_t s) {
-  return launch_lds(hier_count_kernel<ROWS, OPW>, a, int64_t(a.pb.B) * a.split, threads,
-                    size_t(OPW) * a.order_words * 4, s);
+  const size_t lds = size_t(OPW) * a.order_words * 4;
+  hipError_t e =
+      grant_dynamic_lds(reinterpret_cast<const void*>(hier_count_kernel<ROWS, OPW>), lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((hier_count_kernel<ROWS, OPW>), dim3(uint32_t(a.pb.B), uint32_t(a.split)),
+                     dim3(threads), lds, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_count_rows(const HierCountArgs& a, int threads, int rows, int opw,
