@@ -70,7 +70,10 @@ enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0,
                                    [1, R], was clamped */
        TB_DEV_TABLE_OVERFLOW = 4 /* GLOBAL path with partitioned tables (global_partitions > 0):
                                    more distinct n-grams hashed into one partition than it can
-                                   hold; cannot happen unless keys are built to collide */ };
+                                   hold; cannot happen unless keys are built to collide.  The
+                                   score of such a group is NaN (and so is a corpus score it
+                                   enters), so that it cannot pass for a reward; its integer
+                                   statistics are unspecified */ };
 
 typedef struct tb_config {
   int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1 names 1 to 4 as the usual range);

@@ -117,6 +117,7 @@ struct Plans {
   BigPlan big;
   PartPlan part;
   HierPlan hier;
+  size_t overflow_off;
   bool use_hier;  // GLOBAL path on the hierarchical-key kernels (a subset of the LDS shapes)
   bool use_part;  // GLOBAL path with P workgroups per (group, order), tables split over their LDS
   bool use_big;   // GLOBAL path with tables in the workspace (group too large for that, too)
@@ -166,6 +167,9 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   L.distinct_off = off; off = align_up(off + bn * 4);
   L.cand_distinct_off = off; off = align_up(off + bn * 4);
   L.corpus_off = off;   off = align_up(off + 18 * 8);
+  const size_t overflow_off = off;  // int32 [B]: groups whose partitioned dictionary overflowed
+  off = align_up(off + size_t(B) * 4);
+  p->overflow_off = overflow_off;
   if (path == TB_PATH_GLOBAL) {
     L.overlap_off = off;  // int32 [B, R]: ROUGE-N overlap counts (count pass -> score kernel)
     off = align_up(off + size_t(B) * size_t(R) * 4);
@@ -248,6 +252,8 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   }
   c->ws.tables = (L.path == TB_PATH_GLOBAL && (c->plans.use_big || c->plans.use_part))
                      ? w + L.tables_off : nullptr;
+  c->ws.overflow = (L.path == TB_PATH_GLOBAL && c->plans.use_part)
+                       ? reinterpret_cast<int32_t*>(w + c->plans.overflow_off) : nullptr;
   StatPtrs& st = c->st;
   st.clipped = (stats && stats->clipped) ? stats->clipped
                                          : reinterpret_cast<int32_t*>(w + L.clipped_off);
@@ -321,7 +327,7 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   if ((rc = hip_rc(run_dictionary(c, true))) != TB_OK) return rc;
   if (!counts_in_dictionary(c) && (rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
   return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
-                                out_bleu, c.stream));
+                                out_bleu, c.stream, c.ws.overflow));
 }
 
 }  // namespace
@@ -444,7 +450,7 @@ int tensorbleu_finalize(const int32_t* cand_len, const int32_t* ref_len, int32_t
   if (!out_bleu) return TB_ERR_INVALID_ARG;
   return hip_rc(launch_finalize(c.pb, c.st, c.sp, corpus == 0,
                                 corpus != 0 || c.want_corpus_stats, corpus != 0, out_bleu,
-                                c.stream));
+                                c.stream, c.ws.overflow));
 }
 
 size_t tensorbleu_static_scratch_bytes(void) { return kStaticScratchBytes; }

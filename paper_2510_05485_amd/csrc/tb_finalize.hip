@@ -10,6 +10,7 @@ struct FinalArgs {
   StatPtrs st;
   ScoreParams sp;
   void* out;  // fp32 or bfloat16 scores (sp.out_bf16)
+  const int32_t* overflow;  // [B] or null: groups whose dictionary overflowed score NaN
 };
 
 // One lane per sentence.
@@ -27,7 +28,10 @@ __global__ __launch_bounds__(256) void sentence_score_kernel(FinalArgs a) {
     cl[n] = (n < pb.N) ? a.st.clipped[int64_t(i) * pb.N + n] : 0;
     to[n] = (n < pb.N) ? a.st.total[int64_t(i) * pb.N + n] : 0;
   }
-  store_score(a.out, i, bleu_from_stats<int>(cl, to, c, r, a.sp), a.sp.out_bf16);
+  // a group whose statistics are not trustworthy must not pass for a reward
+  const bool spoilt = a.overflow && a.overflow[i] != 0;
+  store_score(a.out, i, spoilt ? __int_as_float(0x7FC00000) : bleu_from_stats<int>(cl, to, c, r, a.sp),
+              a.sp.out_bf16);
 }
 
 __device__ __forceinline__ long long wave_sum64(long long v) {
@@ -62,6 +66,7 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
     }
     acc[16] += c;
     acc[17] += r;
+    if (a.overflow && a.overflow[i] != 0) acc[0] = (long long)(1) << 62;  // poisons the sums
   }
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 #pragma unroll
@@ -83,8 +88,11 @@ __global__ __launch_bounds__(1024) void corpus_kernel(FinalArgs a, int write_sco
     }
     a.st.corpus[2 * pb.N] = tot[16];
     a.st.corpus[2 * pb.N + 1] = tot[17];
+    const bool spoilt = tot[0] >= ((long long)(1) << 61);  // some group's dictionary overflowed
     if (write_score)
-      store_score(a.out, 0, bleu_from_stats<long long>(tot, tot + 8, tot[16], tot[17], a.sp),
+      store_score(a.out, 0,
+                  spoilt ? __int_as_float(0x7FC00000)
+                         : bleu_from_stats<long long>(tot, tot + 8, tot[16], tot[17], a.sp),
                   a.sp.out_bf16);
   }
 }
@@ -154,12 +162,13 @@ hipError_t launch_rouge_finalize(const Problem& pb, const ScoreParams& sp, const
 
 hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
                            bool sentence_scores, bool corpus_sums, bool corpus_score,
-                           void* out_bleu, hipStream_t s) {
+                           void* out_bleu, hipStream_t s, const int32_t* overflow) {
   FinalArgs a;
   a.pb = pb;
   a.st = st;
   a.sp = sp;
   a.out = out_bleu;
+  a.overflow = overflow;
   if (sentence_scores) {
     const int blocks = (pb.B + 255) / 256;
     hipLaunchKernelGGL(sentence_score_kernel, dim3(blocks), dim3(256), 0, s, a);

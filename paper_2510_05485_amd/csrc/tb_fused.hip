@@ -115,8 +115,10 @@ bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
 // The candidate's dictionary of one order: an open-addressing table of 32-bit keys with double
 // hashing.  One 32-bit multiply hashes the key: the top bits of the product pick the slot, lower
 // bits the (odd) probe step, so a probe sequence reaches every slot of the power-of-two table.
-// A probe loop ends at the key or at an empty slot; the table is at most 3/4 full and the probe
-// count is capped at the table size.  The loops have a single exit (one condition, no break):
+// A probe loop ends at the key or at an empty slot and needs no round limit: the odd step visits
+// every slot of the power-of-two table, which is at most 3/4 full (only candidate n-grams are
+// inserted, at most cand_stride of them) and written by this workgroup alone after clearing it.
+// The loops have a single exit (one condition, no break):
 // that halves the instructions the compiler emits per probe round.  (Measured on this hardware:
 // plain divergent loops beat
 // variants that keep all lanes in lock step until the slowest is done, and probing slot pairs
@@ -136,11 +138,9 @@ struct ProbeTable {
       const uint32_t step = (h >> 3) | 1u;
       uint32_t s = h >> shift;
       uint32_t e = slots[s];
-      int rounds = 0;  // the same in every lane still probing: kept in a scalar register
-      while (int(e != key) & int(e != kEmptySlot) & int(uint32_t(rounds) < mask)) {
+      while (int(e != key) & int(e != kEmptySlot)) {
         s = (s + step) & mask;
         e = slots[s];
-        rounds = __builtin_amdgcn_readfirstlane(rounds) + 1;
       }
       found = (e == key) ? s : kNotFound;
     }
@@ -157,11 +157,9 @@ struct ProbeTable {
       const uint32_t step = (h >> 3) | 1u;
       uint32_t s = h >> shift;
       uint32_t old = atomicCAS(&slots[s], kEmptySlot, key);
-      int rounds = 0;
-      while (int(old != kEmptySlot) & int(old != key) & int(uint32_t(rounds) < mask)) {
+      while (int(old != kEmptySlot) & int(old != key)) {
         s = (s + step) & mask;
         old = atomicCAS(&slots[s], kEmptySlot, key);
-        rounds = __builtin_amdgcn_readfirstlane(rounds) + 1;
       }
       created = old == kEmptySlot;
       slot = s;

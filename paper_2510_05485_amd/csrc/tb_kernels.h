@@ -17,6 +17,9 @@ struct GlobalWs {
   int32_t wide[8];    // 1 when the order uses 16-byte keys
   void* tables;       // hash tables / counters in HBM (groups too large for LDS), or the
                       // per-partition dictionary sizes of the partitioned kernels, else null
+  int32_t* overflow;  // [B], partitioned kernels only (else null): non-zero where a partition of
+                      // the group received more distinct n-grams than it can number; the score
+                      // kernels turn such a group's score into NaN
 };
 
 // Integer statistics (either the caller's arrays or workspace scratch; never null).
@@ -134,9 +137,10 @@ hipError_t launch_count_clip(const Problem& pb, const GlobalWs& ws, const CountP
                              const StatPtrs& st, hipStream_t s);
 // sentence_scores: out_bleu[B] per-sentence scores; corpus_sums: fill st.corpus;
 // corpus_score: additionally write the corpus score to out_bleu[0] (not with sentence_scores).
+// overflow: GlobalWs::overflow or null
 hipError_t launch_finalize(const Problem& pb, const StatPtrs& st, const ScoreParams& sp,
                            bool sentence_scores, bool corpus_sums, bool corpus_score,
-                           void* out_bleu, hipStream_t s);
+                           void* out_bleu, hipStream_t s, const int32_t* overflow = nullptr);
 // ROUGE-N scores from overlap counts (GLOBAL path): precision, recall, F of the best reference.
 struct RougeOut;
 hipError_t launch_rouge_finalize(const Problem& pb, const ScoreParams& sp, const int32_t* overlap,

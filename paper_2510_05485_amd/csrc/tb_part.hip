@@ -712,7 +712,10 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   // counts here can count by table entry: no ids, no second look into the table.
   if (a.with_count && !((a.ids_wanted >> n) & 1)) {
     const int distinct = block_sum(created, scan_scratch);  // (its barriers end the insertions)
-    if ((lost || distinct > kPartIdCap) && pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
+    if (lost || distinct > kPartIdCap) {
+      if (pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
+      if (a.ws.overflow) a.ws.overflow[g] = 1;
+    }
     if (tid == 0)
       a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
     // (the members' words hold their table entries; their sequences follow from their slots)
@@ -748,7 +751,10 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   }
   __syncthreads();
   const int distinct = *next_id;
-  if ((lost || distinct > kPartIdCap) && pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
+  if (lost || distinct > kPartIdCap) {
+    if (pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
+    if (a.ws.overflow) a.ws.overflow[g] = 1;
+  }
 
   const uint32_t id_base =
       uint32_t(int64_t(g) * a.id_stride) + uint32_t(p) * uint32_t(kPartIdCap);
@@ -947,6 +953,7 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
   // ascending order (each is keyed by the ids of the order below it)
   PartArgs a = make_args(pb, ws, plan, st);
   a.with_count = with_count ? 1 : 0;
+  if (ws.overflow && (e = zero_ints(ws.overflow, pb.B, s)) != hipSuccess) return e;
   if (whole_call) {  // nobody reads the id array afterwards, except the derived keys
     a.ids_wanted = 0;
     for (int n = 1; n < pb.N; ++n)

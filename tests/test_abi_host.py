@@ -157,3 +157,48 @@ def test_lengths_from_padding():
     refs = x.view(2, 2, 5).to(torch.int64)
     got = tb.lengths_from_padding(refs, 0)
     assert got.dtype == torch.int32 and got.tolist() == [[3, 0], [5, 3]]
+
+
+def test_partition_hash_spreads_realistic_and_structured_keys():
+    """The partitioned kernels give a hash partition room for 6144 distinct n-grams.  The hash
+    (re-stated here from the kernels' definition: a multiplicative hash of the packed key, the
+    partition = the top bits of a second product) must keep every partition below that on keys as
+    the workloads produce them -- Zipf tokens, and the most regular keys there are: consecutive
+    ids -- with the number of partitions the plan chooses for the shape."""
+    import numpy as np
+    import synth_inputs as syn
+    M = np.uint64(0xFFFFFFFF)
+
+    def partitions(keys, log2_parts):
+        keys = keys.astype(np.uint64)
+        lo, hi = keys & M, keys >> np.uint64(32)
+        rot = ((hi << np.uint64(15)) | (hi >> np.uint64(17))) & M
+        h = ((lo ^ rot) * np.uint64(0x9E3779B1)) & M
+        return ((h * np.uint64(0x85EBCA6B) + np.uint64(0x27D4EB2F)) & M) >> np.uint64(32 - log2_parts)
+
+    def worst_load(seqs, bits, parts):
+        log2_parts = parts.bit_length() - 1
+        worst = 0
+        for n in (1, 2, 3):                     # orders whose packed keys fit 64 bits at 16-bit ids
+            keys = []
+            for s in seqs:
+                s = s.astype(np.uint64)
+                k = np.zeros(max(len(s) - n + 1, 0), np.uint64)
+                for j in range(n):
+                    k = (k << np.uint64(bits)) | s[j:len(s) - n + 1 + j]
+                keys.append(k)
+            distinct = np.unique(np.concatenate(keys))
+            worst = max(worst, int(np.bincount(partitions(distinct, log2_parts).astype(np.int64),
+                                               minlength=parts).max()))
+        return worst
+
+    cfg = tb.make_config(vocab_size=50257, path="global")
+    for L, name in ((8192, "zipf"), (8192, "consecutive"), (40000, "zipf"), (40000, "consecutive")):
+        lay = tb.tensorbleu_workspace_layout(1, 1, L, L, cfg)
+        assert lay.global_partitions > 0
+        if name == "zipf":
+            w = syn.long_form(B=1, L=L)
+            seqs = [w.cand[0, :w.cand_len[0]], w.refs[0, 0, :w.ref_len[0, 0]]]
+        else:
+            seqs = [np.arange(L) % 50257, (np.arange(L) + L) % 50257]
+        assert worst_load(seqs, 16, lay.global_partitions) <= 6144, (L, name)

@@ -147,7 +147,8 @@ def test_partitioned_dictionary_ids_are_a_bijection_within_the_group(seed, B, R,
 
 def test_partition_overflow_is_reported_not_hidden():
     """More distinct n-grams in one hash partition than it can hold (6144) is only possible with
-    tokens chosen to collide; the kernels then finish normally and set TB_DEV_TABLE_OVERFLOW."""
+    tokens chosen to collide; the kernels then finish normally, set TB_DEV_TABLE_OVERFLOW and
+    give the group the score NaN."""
     M = 1 << 32
     part = lambda t: ((((t * 0x9E3779B1) % M) * 0x85EBCA6B + 0x27D4EB2F) % M) >> 30   # P = 4
     colliding = [t for t in range(40000) if part(t) == 0][:7000]
@@ -165,7 +166,10 @@ def test_partition_overflow_is_reported_not_hidden():
     out = tb.tensorbleu_sentence(dev(cand), dev(cl), dev(refs), dev(rl), cfg, stats=st)
     torch.cuda.synchronize()
     assert st.device_status.item() & tb.TB_DEV_TABLE_OVERFLOW
-    assert np.isfinite(out.cpu().numpy()).all()
+    assert np.isnan(out.cpu().numpy()).all()      # not a number: cannot pass for a reward
+    cout = tb.tensorbleu_corpus(dev(cand), dev(cl), dev(refs), dev(rl), cfg)
+    torch.cuda.synchronize()
+    assert np.isnan(cout.cpu().numpy()).all()
     # the same shape with ordinary tokens is scored and not flagged
     w = syn.random_small(206, B=1, R=1, vocab=40000, max_len=L, min_len=7000)
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len)
