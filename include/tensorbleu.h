@@ -256,8 +256,11 @@ int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len
 
 /* ---- The GLOBAL path one pass at a time (same arguments and workspace as above; the workspace
  * must have been sized with force_path = TB_PATH_GLOBAL).  tensorbleu_sentence on the GLOBAL
- * path is exactly pack, dictionary, count_clip, finalize in this order.  Exposed so that each
- * pass can be checked and timed on its own. */
+ * path computes exactly what pack, dictionary, count_clip, finalize compute in this order.
+ * Exposed so that each pass can be checked and timed on its own.  (With partitioned tables,
+ * global_partitions > 0, the single call itself fuses neighbouring passes: its dictionary pass
+ * extracts the n-grams from the token rows, so no key array is written, and counts in place
+ * where the counters fit the table's memory.  The staged calls below keep the pass boundaries.) */
 
 /* Section 3.1 + 3.2 step 1: every valid n-gram, n = 1..N, packed big-endian into a key
  * (first token in the most significant bits) and written to its slot in keys_off[n-1]. */

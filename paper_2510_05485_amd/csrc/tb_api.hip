@@ -286,11 +286,14 @@ inline int hip_rc(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 bool counts_in_dictionary(const Call& c) {
   return c.plans.use_part && c.plans.part.count_in_dictionary;
 }
-hipError_t run_dictionary(const Call& c, bool whole_call) {
+// from_tokens: the caller handed over the token rows (c.pb.cand / c.pb.refs are set); the
+// partitioned kernels then extract the n-grams themselves and the pack kernel need not have run
+hipError_t run_dictionary(const Call& c, bool whole_call, bool from_tokens) {
   if (c.plans.use_hier)
     return launch_hier_dictionary(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.stream);
   if (c.plans.use_part)
-    return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st, whole_call, c.stream);
+    return launch_part_dictionary(c.pb, c.ws, c.plans.part, c.st, whole_call, from_tokens,
+                                  c.stream);
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }
@@ -323,8 +326,8 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
     }
     return TB_OK;
   }
-  if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
-  if ((rc = hip_rc(run_dictionary(c, true))) != TB_OK) return rc;
+  if (!c.plans.use_part && (rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
+  if ((rc = hip_rc(run_dictionary(c, true, true))) != TB_OK) return rc;
   if (!counts_in_dictionary(c) && (rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
   return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
                                 out_bleu, c.stream, c.ws.overflow));
@@ -396,8 +399,8 @@ int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len
   // below), then the count pass for order n alone, which also sums the per-reference overlaps
   if (!c.plans.use_hier && !c.plans.use_part) return TB_ERR_UNSUPPORTED;  // BLEU-only kernels
   int32_t* ov = reinterpret_cast<int32_t*>(w + L.overlap_off);
-  if ((rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
-  if ((rc = hip_rc(run_dictionary(c, false))) != TB_OK) return rc;
+  if (!c.plans.use_part && (rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
+  if ((rc = hip_rc(run_dictionary(c, false, true))) != TB_OK) return rc;
   rc = hip_rc(c.plans.use_hier
                   ? launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct,
                                            c.stream, ov)
@@ -425,7 +428,7 @@ int tensorbleu_dictionary(const int32_t* cand_len, const int32_t* ref_len, int64
   int rc = prepare(nullptr, cand_stride, cand_len, nullptr, ref_stride, ref_len, B, R, cfg, stats,
                    workspace, workspace_bytes, hip_stream, false, TB_PATH_GLOBAL, &c);
   if (rc != TB_OK || B == 0) return rc;
-  return hip_rc(run_dictionary(c, false));
+  return hip_rc(run_dictionary(c, false, false));
 }
 
 int tensorbleu_count_clip(const int32_t* cand_len, const int32_t* ref_len, int64_t cand_stride,

@@ -109,9 +109,11 @@ size_t part_workspace_bytes(int64_t B, int N, int64_t group_cap, const PartPlan&
 // whole_call: the count/clip pass follows at once and nobody else reads the id array, so ids are
 // stored only where a later order's keys are derived from them and, if
 // plan.count_in_dictionary, the dictionary kernel also does the count/clip pass's work, which is
-// then not to be launched
+// then not to be launched.  from_tokens: pb.cand / pb.refs are set and the keys are built from
+// them; otherwise they are read from ws.keys as the pack kernel left them
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, bool whole_call, hipStream_t s);
+                                  const StatPtrs& st, bool whole_call, bool from_tokens,
+                                  hipStream_t s);
 // rouge_overlap != null: ROUGE-N instead, as for launch_hier_count_clip
 hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
                                   const StatPtrs& st, hipStream_t s,

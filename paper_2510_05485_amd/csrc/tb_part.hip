@@ -55,6 +55,7 @@ struct PartArgs {
   int orders[8];           // dictionary: the orders of this launch, and how many
   int num_orders;
   int derived;             // dictionary: 1 if this launch's orders use (prefix id, last token) keys
+  int from_tokens;         // dictionary: keys are built from the token rows (whole calls)
   int words;               // count/clip: 32-bit counter words per id
   int fields_per_word;     // 2: 16-bit counters (sequences of at most 65 535 tokens); 1: 32-bit
   int64_t id_stride;       // ids of group g lie in [g * id_stride, (g + 1) * id_stride)
@@ -111,24 +112,37 @@ __global__ __launch_bounds__(256) void zero_ints_kernel(int32_t* p, int64_t coun
   if (i < count) p[i] = 0;
 }
 
-// The 8-byte key of slot k of one (group, order): the packed n-gram, or for an order with 16-byte
-// packed keys (id of the (n-1)-gram at the same position, last token).  Construct in
-// wave-uniform control flow (it scans the group's lengths).
+// The 8-byte key of slot k of one (group, order): the n tokens packed `bits` apiece, or for an
+// order whose packed n-grams would need 16 bytes (id of the (n-1)-gram at the same position, last
+// token).  A whole call builds the keys from the token rows themselves (the n-gram extraction of
+// Section 3.1 happens here, and the pack kernel does not run); the staged dictionary entry point
+// is not given the tokens and reads the pack kernel's arrays.  Construct and call in wave-uniform
+// control flow with all 64 lanes active; within a call the lanes' slots must not decrease with
+// the lane number (consecutive slots, possibly clamped to the last one).
 struct KeySource {
-  const uint64_t* narrow_keys;
+  const uint64_t* narrow_keys;  // the pack kernel's arrays (used unless from_tokens)
   const Key128* wide_keys;
+  int from_tokens;
+  const void* cand;  // token rows
+  const void* refs;
+  int64_t cand_first;  // element index of the candidate's first token
+  int64_t ref_first;   // element index of the first token of the group's reference 0
+  int64_t ref_stride;
   const uint32_t* prev_inv;
   uint32_t prev_base;
-  uint64_t token_mask;
-  int bits, R, derived;
+  uint32_t vocab;
+  int32_t* status;
+  int bits, R, derived, n, tok64;
   int end_lane;    // lane j: end of sequence j among the order's slots
   int shift_lane;  // lane j: how far sequence j's slots of order n - 1 lie behind those of order n
   int count;       // n-grams of this (group, order)
+  mutable int bad; // a token outside the vocabulary was met (checked on the order-1 keys)
 
-  __device__ __forceinline__ KeySource(const PartArgs& a, int g, int n) {
+  __device__ __forceinline__ KeySource(const PartArgs& a, int g, int order) {
     const Problem& pb = a.pb;
     GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
     derived = a.derived;
+    n = order;
     shift_lane = 0;
     if (derived) {
       gi.set_order(n - 1);
@@ -142,24 +156,124 @@ struct KeySource {
       if ((threadIdx.x & (kWave - 1)) == 0) shift_lane = 0;
     }
     count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+    from_tokens = a.from_tokens;
     narrow_keys = reinterpret_cast<const uint64_t*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
     wide_keys = reinterpret_cast<const Key128*>(a.ws.keys[n - 1]) + int64_t(g) * pb.group_cap;
+    cand = pb.cand;
+    refs = pb.refs;
+    cand_first = int64_t(g) * pb.cand_stride;
+    ref_stride = pb.ref_stride;
+    ref_first = ref_rows(pb, g).row0 * pb.ref_stride;
     prev_inv = a.ws.inv[max(n - 2, 0)] + int64_t(g) * pb.group_cap;
     prev_base = uint32_t(int64_t(g) * a.id_stride);
-    token_mask = (uint64_t(1) << pb.bits) - 1u;
+    vocab = uint32_t(pb.vocab);
+    status = pb.status;
     bits = pb.bits;
     R = pb.R;
+    tok64 = pb.tok64;
+    bad = 0;
   }
-  // k < count
-  __device__ __forceinline__ uint64_t operator()(int k) const {
-    if (!derived) return narrow_keys[k];
-    int shift = 0;  // of the sequence that slot k belongs to
-    for (int j = 0; j < R; ++j) {
-      const bool past = k >= __builtin_amdgcn_readlane(end_lane, j);
-      shift = past ? __builtin_amdgcn_readlane(shift_lane, j + 1) : shift;
+
+  // Calls f(T, W) with T = integral constant, the tokens a key is built from (1..8; 0: the key
+  // is read from the pack kernel's arrays), and W = whether token ids are 64-bit: the loads of
+  // get<T, W> then carry no branches, so a caller's batch of them is in flight together.
+  template <typename F>
+  __device__ __forceinline__ void dispatch(F&& f) const {
+    if (!from_tokens) {
+      f(std::integral_constant<int, 0>{}, std::false_type{});
+      return;
     }
-    const uint64_t prefix = prev_inv[k + shift] - prev_base;
-    return (prefix << bits) | (wide_keys[k].lo & token_mask);
+    const int t = derived ? 1 : n;
+    if (tok64) {
+      switch (t) {
+        case 1: f(std::integral_constant<int, 1>{}, std::true_type{}); break;
+        case 2: f(std::integral_constant<int, 2>{}, std::true_type{}); break;
+        case 3: f(std::integral_constant<int, 3>{}, std::true_type{}); break;
+        case 4: f(std::integral_constant<int, 4>{}, std::true_type{}); break;
+        case 5: f(std::integral_constant<int, 5>{}, std::true_type{}); break;
+        case 6: f(std::integral_constant<int, 6>{}, std::true_type{}); break;
+        case 7: f(std::integral_constant<int, 7>{}, std::true_type{}); break;
+        default: f(std::integral_constant<int, 8>{}, std::true_type{}); break;
+      }
+    } else {
+      switch (t) {
+        case 1: f(std::integral_constant<int, 1>{}, std::false_type{}); break;
+        case 2: f(std::integral_constant<int, 2>{}, std::false_type{}); break;
+        case 3: f(std::integral_constant<int, 3>{}, std::false_type{}); break;
+        case 4: f(std::integral_constant<int, 4>{}, std::false_type{}); break;
+        case 5: f(std::integral_constant<int, 5>{}, std::false_type{}); break;
+        case 6: f(std::integral_constant<int, 6>{}, std::false_type{}); break;
+        case 7: f(std::integral_constant<int, 7>{}, std::false_type{}); break;
+        default: f(std::integral_constant<int, 8>{}, std::false_type{}); break;
+      }
+    }
+  }
+
+  // 0 <= k < count.  T, W: as handed out by dispatch().
+  template <int T, bool W>
+  __device__ __forceinline__ uint64_t get(int k) const {
+    if (T == 0 && !derived) return narrow_keys[k];
+    // the sequence slot k belongs to: usually the same for the whole wavefront, found by one
+    // ballot over the sequence ends (row address and offsets then stay in scalar registers); a
+    // wavefront that straddles sequences walks the ends inside
+    const int lane = threadIdx.x & (kWave - 1);
+    const int k_lo = __builtin_amdgcn_readfirstlane(k);
+    const int k_hi = __builtin_amdgcn_readlane(k, kWave - 1);
+    const int ends = lane <= R ? end_lane : 0x7FFFFFFF;
+    const int f0 = min(int(__popcll(__builtin_amdgcn_ballot_w64(ends <= k_lo))), R);
+    constexpr int kLoads = T == 0 ? 1 : T;
+    uint32_t tok[kLoads];
+    int shift;
+    // tokens [from, from + T) of the n-gram (derived keys: its last token only)
+    const int from = derived ? n - 1 : 0;
+    if (k_hi < __builtin_amdgcn_readlane(end_lane, f0)) {  // uniform
+      const int start = f0 > 0 ? __builtin_amdgcn_readlane(end_lane, max(f0 - 1, 0)) : 0;
+      const void* base = f0 == 0 ? cand : refs;
+      const int64_t row = f0 == 0 ? cand_first : ref_first + int64_t(f0 - 1) * ref_stride;
+      shift = __builtin_amdgcn_readlane(shift_lane, f0);
+      if (T != 0) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i)
+          tok[i] = uint32_t(load_token(base, row + (from - start + i) + k, W));
+      }
+    } else {
+      const int f_hi = min(int(__popcll(__builtin_amdgcn_ballot_w64(ends <= k_hi))), R);
+      int seq = f0;
+      int start = f0 > 0 ? __builtin_amdgcn_readlane(end_lane, max(f0 - 1, 0)) : 0;
+      shift = __builtin_amdgcn_readlane(shift_lane, f0);
+      for (int q = f0; q < f_hi; ++q) {
+        const int e = __builtin_amdgcn_readlane(end_lane, q);
+        const bool ge = k >= e;
+        seq = ge ? q + 1 : seq;
+        start = ge ? e : start;
+        shift = ge ? __builtin_amdgcn_readlane(shift_lane, q + 1) : shift;
+      }
+      const void* base = seq == 0 ? cand : refs;
+      const int64_t first =
+          (seq == 0 ? cand_first : ref_first + int64_t(seq - 1) * ref_stride) + (k - start);
+      if (T != 0) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) tok[i] = uint32_t(load_token(base, first + from + i, W));
+      }
+    }
+    if (derived) {
+      const uint64_t last =
+          T == 0 ? (wide_keys[k].lo & ((uint64_t(1) << bits) - 1u)) : uint64_t(tok[0]);
+      const uint64_t prefix = prev_inv[k + shift] - prev_base;
+      return (prefix << bits) | last;
+    }
+    uint64_t key = 0;
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      if (T == 1) bad |= int(tok[i] >= vocab);
+      key = (key << bits) | tok[i];
+    }
+    return key;
+  }
+
+  // Once per thread, after its last get(): reports a token outside the vocabulary.
+  __device__ __forceinline__ void report() const {
+    if (bad && status) atomicOr(status, TB_DEV_TOKEN_RANGE);
   }
 };
 
@@ -192,8 +306,11 @@ __device__ __forceinline__ void scatter_range(const PartArgs& a, const KeySource
   for (int base = begin; base < end; base += kRound) {
     uint64_t key[kRoundUnroll];
     int where[kRoundUnroll];  // rank within the partition's run | partition << 16
+    key_of.dispatch([&](auto T, auto W) {
 #pragma unroll
-    for (int u = 0; u < kRoundUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, end - 1));
+      for (int u = 0; u < kRoundUnroll; ++u)
+        key[u] = key_of.template get<T(), W()>(min(base + u * nt + tid, end - 1));
+    });
 #pragma unroll
     for (int u = 0; u < kRoundUnroll; ++u) {
       const int q = partition_of_key(key[u], a.log2_parts);
@@ -253,11 +370,16 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
     a.st.clipped[int64_t(g) * pb.N + n - 1] = 0;
     a.st.distinct[int64_t(g) * pb.N + n - 1] = 0;
   }
+  // (order 1 is in the first launch of a call; the dictionary workgroups raise the flag later)
+  if (n == 1 && tid == 0 && a.ws.overflow) a.ws.overflow[g] = 0;
   __syncthreads();
   for (int base = 0; base < count; base += kPartUnroll * nt) {
     uint64_t key[kPartUnroll];
+    key_of.dispatch([&](auto T, auto W) {
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, count - 1));
+      for (int u = 0; u < kPartUnroll; ++u)
+        key[u] = key_of.template get<T(), W()>(min(base + u * nt + tid, count - 1));
+    });
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
       if (base + u * nt + tid < count) atomicAdd(&hist[partition_of_key(key[u], a.log2_parts)], 1);
@@ -276,8 +398,11 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
   // (a partition's share of a wave's stores is a run of neighbouring addresses already)
   for (int base = 0; base < count; base += kPartUnroll * nt) {
     uint64_t key[kPartUnroll];
+    key_of.dispatch([&](auto T, auto W) {
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, count - 1));
+      for (int u = 0; u < kPartUnroll; ++u)
+        key[u] = key_of.template get<T(), W()>(min(base + u * nt + tid, count - 1));
+    });
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u) {
       const int k = base + u * nt + tid;
@@ -288,6 +413,7 @@ __global__ __launch_bounds__(kPartThreads) void part_scatter_kernel(PartArgs a) 
       }
     }
   }
+  key_of.report();
 }
 
 // The same for groups of at most 16 384 slots: every thread keeps its 16 keys in registers
@@ -309,10 +435,17 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_scatter_small_kernel(Par
     a.st.clipped[int64_t(g) * pb.N + n - 1] = 0;
     a.st.distinct[int64_t(g) * pb.N + n - 1] = 0;
   }
+  if (n == 1 && tid == 0 && a.ws.overflow) a.ws.overflow[g] = 0;
   __syncthreads();
   uint64_t key[kScatterRegItems];
 #pragma unroll
-  for (int i = 0; i < kScatterRegItems; ++i) key[i] = key_of(max(min(i * nt + tid, count - 1), 0));
+  for (int i = 0; i < kScatterRegItems; ++i) key[i] = 0;
+  if (count > 0)
+    key_of.dispatch([&](auto T, auto W) {
+#pragma unroll
+      for (int i = 0; i < kScatterRegItems; ++i)
+        key[i] = key_of.template get<T(), W()>(min(i * nt + tid, count - 1));
+    });
 #pragma unroll
   for (int i = 0; i < kScatterRegItems; ++i)
     if (i * nt + tid < count) atomicAdd(&hist[partition_of_key(key[i], a.log2_parts)], 1);
@@ -336,6 +469,7 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_scatter_small_kernel(Par
       member_keys[at] = key[i];
     }
   }
+  key_of.report();
 }
 
 // The same in two kernels with one workgroup per 16 384 slots, for batches of few, very long
@@ -356,8 +490,11 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_hist_kernel(PartArgs 
   __syncthreads();
   for (int base = begin; base < end; base += kPartUnroll * nt) {
     uint64_t key[kPartUnroll];
+    key_of.dispatch([&](auto T, auto W) {
 #pragma unroll
-    for (int u = 0; u < kPartUnroll; ++u) key[u] = key_of(min(base + u * nt + tid, end - 1));
+      for (int u = 0; u < kPartUnroll; ++u)
+        key[u] = key_of.template get<T(), W()>(min(base + u * nt + tid, end - 1));
+    });
 #pragma unroll
     for (int u = 0; u < kPartUnroll; ++u)
       if (base + u * nt + tid < end) atomicAdd(&hist[partition_of_key(key[u], a.log2_parts)], 1);
@@ -369,6 +506,8 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_hist_kernel(PartArgs 
     a.st.clipped[int64_t(g) * pb.N + n - 1] = 0;
     a.st.distinct[int64_t(g) * pb.N + n - 1] = 0;
   }
+  if (n == 1 && c == 0 && tid == 0 && a.ws.overflow) a.ws.overflow[g] = 0;
+  key_of.report();
 }
 
 __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartArgs a,
@@ -409,6 +548,7 @@ __global__ __launch_bounds__(kPartThreads) void part_chunk_scatter_kernel(PartAr
   __syncthreads();
 
   scatter_range(a, key_of, begin, end, cursor, lds, members, member_keys);
+  key_of.report();
 }
 
 // Counts a partition's members into one counter field per (id, sequence) -- `cnt`, LDS, U * W
@@ -899,6 +1039,7 @@ PartArgs make_args(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
   for (int k = 0; k < 8; ++k) a.orders[k] = 0;
   a.num_orders = 0;
   a.derived = 0;
+  a.from_tokens = 0;
   return a;
 }
 
@@ -944,7 +1085,8 @@ bool plan_part(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
 }
 
 hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const PartPlan& plan,
-                                  const StatPtrs& st, bool whole_call, hipStream_t s) {
+                                  const StatPtrs& st, bool whole_call, bool from_tokens,
+                                  hipStream_t s) {
   const bool with_count = whole_call && plan.count_in_dictionary;
   hipError_t e =
       grant_dynamic_lds(reinterpret_cast<const void*>(part_dictionary_kernel), plan.dict_lds);
@@ -953,7 +1095,7 @@ hipError_t launch_part_dictionary(const Problem& pb, const GlobalWs& ws, const P
   // ascending order (each is keyed by the ids of the order below it)
   PartArgs a = make_args(pb, ws, plan, st);
   a.with_count = with_count ? 1 : 0;
-  if (ws.overflow && (e = zero_ints(ws.overflow, pb.B, s)) != hipSuccess) return e;
+  a.from_tokens = from_tokens ? 1 : 0;
   if (whole_call) {  // nobody reads the id array afterwards, except the derived keys
     a.ids_wanted = 0;
     for (int n = 1; n < pb.N; ++n)

@@ -206,6 +206,26 @@ def test_device_status_reports_bad_tokens_and_lengths(path):
     assert st.device_status.item() & tb.binding.TB_DEV_LENGTH_RANGE
 
 
+@pytest.mark.parametrize("max_len,min_len", [(4000, 3400), (9000, 8500)])
+def test_device_status_on_partitioned_groups(max_len, min_len):
+    # groups beyond one LDS table: a whole call extracts the n-grams inside the partitioned
+    # kernels (the pack kernel does not run), which then also have to report bad tokens; the two
+    # sizes take the scatter kernel for groups of at most 16 384 slots and the general one
+    w = syn.random_small(131, B=2, R=3, vocab=300, max_len=max_len, min_len=min_len)
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.path == 2 and lay.global_partitions > 0
+    _, st = run_gpu(Device(w), syn.Run("none"), "auto")
+    assert st.device_status.item() == 0
+    w.refs[1, 2, int(w.ref_len[1, 2]) - 1] = 300   # == vocab_size, the last token inside a length
+    _, st = run_gpu(Device(w), syn.Run("none"), "auto")
+    assert st.device_status.item() & tb.binding.TB_DEV_TOKEN_RANGE
+    w.refs[1, 2, int(w.ref_len[1, 2]) - 1] = 299
+    w.refs[1, 2, int(w.ref_len[1, 2]):] = 300       # beyond the length: never looked at
+    _, st = run_gpu(Device(w), syn.Run("none"), "auto")
+    assert st.device_status.item() == 0
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_largest_supported_group(path):
     # cand_stride + R * ref_stride = 12288 n-gram slots: the limit of both LDS plans
