@@ -254,6 +254,8 @@ int prepare(const void* cand, int64_t cand_stride, const int32_t* cand_len,
                      ? w + L.tables_off : nullptr;
   c->ws.overflow = (L.path == TB_PATH_GLOBAL && c->plans.use_part)
                        ? reinterpret_cast<int32_t*>(w + c->plans.overflow_off) : nullptr;
+  c->ws.arrivals = (L.path == TB_PATH_GLOBAL && c->plans.use_hier)
+                       ? reinterpret_cast<int32_t*>(w + c->plans.overflow_off) : nullptr;
   StatPtrs& st = c->st;
   st.clipped = (stats && stats->clipped) ? stats->clipped
                                          : reinterpret_cast<int32_t*>(w + L.clipped_off);
@@ -297,9 +299,11 @@ hipError_t run_dictionary(const Call& c, bool whole_call, bool from_tokens) {
   return c.plans.use_big ? launch_big_dictionary(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_dictionary(c.pb, c.ws, c.plans.dict, c.st.distinct, c.stream);
 }
-hipError_t run_count_clip(const Call& c) {
+// tail: see launch_hier_count_clip (only for the hierarchical-key kernels)
+hipError_t run_count_clip(const Call& c, const ScoreTail* tail = nullptr) {
   if (c.plans.use_hier)
-    return launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.stream);
+    return launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct, c.stream,
+                                  nullptr, tail);
   if (c.plans.use_part) return launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream);
   return c.plans.use_big ? launch_big_count_clip(c.pb, c.ws, c.plans.big, c.st, c.stream)
                          : launch_count_clip(c.pb, c.ws, c.plans.count, c.st, c.stream);
@@ -328,6 +332,13 @@ int run_all(const void* cand, int64_t cand_stride, const int32_t* cand_len,
   }
   if (!c.plans.use_part && (rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
   if ((rc = hip_rc(run_dictionary(c, true, true))) != TB_OK) return rc;
+  if (c.plans.use_hier && !corpus && !c.want_corpus_stats) {
+    // per-sentence scores only: the count kernel's last workgroup per group scores the sentence
+    ScoreTail tail;
+    tail.sp = c.sp;
+    tail.out = out_bleu;
+    return hip_rc(run_count_clip(c, &tail));
+  }
   if (!counts_in_dictionary(c) && (rc = hip_rc(run_count_clip(c))) != TB_OK) return rc;
   return hip_rc(launch_finalize(c.pb, c.st, c.sp, !corpus, corpus || c.want_corpus_stats, corpus,
                                 out_bleu, c.stream, c.ws.overflow));

@@ -59,6 +59,15 @@ class GroupIndex {
   }
   // Lane j <= R: one past the last slot of sequence j.  Only when the group has < 64 sequences.
   __device__ __forceinline__ int end_in_lane() const { return incl_; }
+  // Lane j <= R: the clamped length of sequence j (0 for a reference not in use); and the number
+  // of references in use.  Only when the group has < 64 sequences.
+  __device__ __forceinline__ int length_in_lane() const {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int cs = __builtin_amdgcn_readfirstlane(int(min(pb_.cand_stride, int64_t(1) << 30)));
+    const int rs = __builtin_amdgcn_readfirstlane(int(min(pb_.ref_stride, int64_t(1) << 30)));
+    return lane <= used_ ? clamped_len(raw_, lane == 0 ? cs : rs, nullptr) : 0;
+  }
+  __device__ __forceinline__ int refs_in_use() const { return used_; }
 
  private:
   // lane j <= R: the stored length of sequence j; other lanes: 0

@@ -27,6 +27,7 @@
 
 #include "tb_group_index.h"
 #include "tb_kernels.h"
+#include "tb_score.h"
 
 // Phase time stamps for tuning builds only (-DTB_STAMPS): thread 0 of every workgroup records the
 // 100 MHz wall clock at phase boundaries; tb_debug_stamps copies them to the host.
@@ -132,6 +133,7 @@ void hier_dictionary_kernel(HierDictArgs a) {
   const uint32_t gbase = uint32_t(gslot);
 
   TB_STAMP(0);
+  if (tid == 0 && a.ws.arrivals) a.ws.arrivals[g] = 0;  // counted up by the count kernel
   // lane j: stored length of sequence j (requested first, clamped once the key requests below
   // are out: a wavefront's loads return in order, so the lengths arrive first)
   const RefRows rr = ref_rows(pb, g);
@@ -316,6 +318,10 @@ struct HierCountArgs {
   // ROUGE-N (rouge_overlap != null): one workgroup per group counts order N only and, in its
   // sweep, sums min(candidate count, reference j's count) per reference into rouge_overlap[B, R]
   int32_t* rouge_overlap;
+  // BLEU, whole calls (score_out != null): the last workgroup of a group to finish scores the
+  // sentence from the group's statistics (Section 3.4); ws.arrivals counts the finished ones
+  ScoreParams sp;
+  void* score_out;
 };
 
 // Four consecutive offset ids, loaded with one 16-byte request.  A group's first slot is only
@@ -515,11 +521,65 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
       tn = (lane == o) ? ccnt[o] : tn;
     }
     const int n = first_order + lane * a.split;
-    if (lane < OPW && n <= N) {
-      a.st.clipped[int64_t(g) * N + n - 1] = cn;
-      a.st.total[int64_t(g) * N + n - 1] = tn;
+    if (!a.score_out) {
+      if (lane < OPW && n <= N) {
+        a.st.clipped[int64_t(g) * N + n - 1] = cn;
+        a.st.total[int64_t(g) * N + n - 1] = tn;
+      }
+    } else if (lane < OPW && n <= N) {
+      // (stored with device-scope atomics: they are carried out where every compute unit of the
+      // device sees them, which a plain store is only after a write-back of the whole L2)
+      const int o1 = __hip_atomic_exchange(&a.st.clipped[int64_t(g) * N + n - 1], cn,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int o2 = __hip_atomic_exchange(&a.st.total[int64_t(g) * N + n - 1], tn,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // (the old values are asked for so that the atomics answer, which they do once done)
+      asm volatile("" ::"v"(o1), "v"(o2) : "memory");
     }
     if (rouge && lane < R) a.rouge_overlap[int64_t(g) * R + lane] = s_overlap[lane];
+
+    if (a.score_out) {
+      // An atomic returns once it has been carried out: after the wait every statistic of this
+      // workgroup is in place, and only then does the workgroup announce its arrival.  The
+      // workgroup whose arrival completes the group reads the others' statistics with
+      // device-scope loads.  (No fence: a release fence writes back the whole L2.)
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      int arrived = 0;
+      if (lane == 0)
+        arrived = __hip_atomic_fetch_add(&a.ws.arrivals[g], 1, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+      arrived = lane_value(arrived, 0);
+      if (arrived == int(gridDim.y) - 1) {  // uniform
+        const int my_len = gi.length_in_lane(), used = gi.refs_in_use();
+        const int c = lane_value(my_len, 0);
+        (void)ref_rows(pb, g, lane == 0);  // reports a reference count out of range
+        // closest reference length, the shorter one on ties (lane j: length of sequence j)
+        int best = 0;
+        if (used >= 1) {
+          best = lane_value(my_len, 1);
+          int bd = abs(best - c);
+          for (int j = 2; j <= used; ++j) {
+            const int l = lane_value(my_len, j), d = abs(l - c);
+            if (d < bd || (d == bd && l < best)) {
+              best = l;
+              bd = d;
+            }
+          }
+        }
+        // lane n < N: the statistics of order n + 1
+        const int64_t stat = int64_t(g) * N + min(lane, N - 1);
+        const int cn_read = __hip_atomic_load(&a.st.clipped[stat], __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+        const int tn_read = __hip_atomic_load(&a.st.total[stat], __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+        const int cn_all = lane < N ? cn_read : 0, tn_all = lane < N ? tn_read : 0;
+        const float score = bleu_from_stats_wave(cn_all, tn_all, c, best, a.sp);
+        if (lane == 0) {
+          a.st.closest[g] = best;
+          store_score(a.score_out, g, score, a.sp.out_bf16);
+        }
+      }
+    }
   }
 }
 
@@ -681,11 +741,19 @@ hipError_t launch_hier_dictionary(const Problem& pb, const GlobalWs& ws, const H
 
 hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, const int32_t* cand_distinct,
-                                  hipStream_t s, int32_t* rouge_overlap) {
+                                  hipStream_t s, int32_t* rouge_overlap, const ScoreTail* tail) {
   HierCountArgs a;
   a.pb = pb;
   a.ws = ws;
   a.st = st;
+  a.score_out = nullptr;
+  if (tail && !rouge_overlap) {
+    if (!ws.arrivals) return hipErrorInvalidValue;
+    a.sp = tail->sp;
+    a.score_out = tail->out;
+  } else {
+    a.sp = ScoreParams{};
+  }
   a.cand_distinct = cand_distinct;
   a.words = plan.words;
   a.order_words = int(pb.cand_stride) * plan.words;

@@ -20,6 +20,10 @@ struct GlobalWs {
   int32_t* overflow;  // [B], partitioned kernels only (else null): non-zero where a partition of
                       // the group received more distinct n-grams than it can number; the score
                       // kernels turn such a group's score into NaN
+  int32_t* arrivals;  // [B], hierarchical-key kernels only (else null; the same words as
+                      // `overflow`): how many of a group's count workgroups have finished; the
+                      // dictionary kernel zeroes it, and in a whole call the last count workgroup
+                      // to arrive scores the sentence
 };
 
 // Integer statistics (either the caller's arrays or workspace scratch; never null).
@@ -81,9 +85,17 @@ hipError_t launch_hier_dictionary(const Problem& pb, const GlobalWs& ws, const H
                                   const StatPtrs& st, int32_t* cand_distinct, hipStream_t s);
 // rouge_overlap != null: ROUGE-N instead -- only order N is counted, and overlap[B, R] receives
 // per reference the sum over n-grams of min(candidate count, the reference's count)
+// tail != null (BLEU only): the last workgroup of a group to finish also computes what the
+// sentence score kernel computes (closest reference length, Section 3.4's score into tail->out),
+// which then is not to be launched; needs ws.arrivals zeroed by the dictionary pass
+struct ScoreTail {
+  ScoreParams sp;
+  void* out;  // [B] fp32 or bfloat16 (sp.out_bf16)
+};
 hipError_t launch_hier_count_clip(const Problem& pb, const GlobalWs& ws, const HierPlan& plan,
                                   const StatPtrs& st, const int32_t* cand_distinct,
-                                  hipStream_t s, int32_t* rouge_overlap = nullptr);
+                                  hipStream_t s, int32_t* rouge_overlap = nullptr,
+                                  const ScoreTail* tail = nullptr);
 
 // Groups beyond the LDS plans: table and counters live in the workspace.
 struct BigPlan {

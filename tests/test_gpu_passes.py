@@ -110,6 +110,34 @@ def test_staged_calls_equal_the_single_call_on_config1():
     assert abs(cout[0] - ref.corpus_bleu) <= 1e-5
 
 
+@pytest.mark.parametrize("k", [2, 5])
+def test_single_global_call_scores_inside_the_count_kernel(k):
+    # A single per-sentence call on the hierarchical-key kernels launches no score kernel: of a
+    # group's count workgroups, the one that finishes last scores the sentence.  Whichever
+    # workgroup that is, the result has to be the staged passes' (which end with the score
+    # kernel), bit for bit and on every repetition; without corpus statistics, so that the
+    # single call takes that route.
+    w = syn.make(k)
+    run = [r for r in w.runs if not r.corpus][-1]
+    _, _, stats, out = stage_all(w, run)
+    cfg = tb.make_config(max_n=w.max_n, weights=w.weights, smoothing=run.smoothing,
+                         smooth_param=run.smooth_param, vocab_size=w.vocab, path="global")
+    cand, cl, refs, rl = dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len)
+    st2 = tb.Stats.allocate(w.B, w.max_n, DEV, corpus_stats=False)
+    ws = tb.allocate_workspace(w.B, w.R, cand.shape[1], refs.shape[2], cfg, DEV)
+    out2 = torch.empty(w.B, dtype=torch.float32, device=DEV)
+    expect, closest = torch.from_numpy(out).to(DEV), stats.closest_ref_len
+    for _ in range(100):
+        out2.fill_(-1.0)
+        st2.closest_ref_len.fill_(-1)
+        tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out2, stats=st2, workspace=ws)
+        assert torch.equal(out2, expect)
+        assert torch.equal(st2.closest_ref_len, closest)
+    np.testing.assert_array_equal(stats.clipped.cpu().numpy(), st2.clipped.cpu().numpy())
+    np.testing.assert_array_equal(stats.total.cpu().numpy(), st2.total.cpu().numpy())
+    assert st2.device_status.item() == 0
+
+
 @pytest.mark.parametrize("seed,B,R,L,P", [
     (205, 2, 2, 5000, 4),    # one scatter workgroup per (group, order)
     (206, 1, 1, 12000, 8),   # few long groups: the scatter is split over chunks of 16 384 slots
