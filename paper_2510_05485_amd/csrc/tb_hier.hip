@@ -336,7 +336,8 @@ struct __attribute__((packed, aligned(4))) IdQuad {
 // The scalar work per block (its first sequence, the bounds, the branches) is shared by 256
 // n-grams; a block inside one sequence runs four predicated atomics with a scalar field word and
 // addend, a block that straddles sequences finds each slot's sequence per lane.
-template <int ROWS, int OPW>
+// SCORE: the whole-call variant that also scores the sentence (a.score_out; see HierCountArgs).
+template <int ROWS, int OPW, bool SCORE>
 __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_clipped[8];
@@ -521,7 +522,7 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
       tn = (lane == o) ? ccnt[o] : tn;
     }
     const int n = first_order + lane * a.split;
-    if (!a.score_out) {
+    if (!SCORE) {
       if (lane < OPW && n <= N) {
         a.st.clipped[int64_t(g) * N + n - 1] = cn;
         a.st.total[int64_t(g) * N + n - 1] = tn;
@@ -538,7 +539,7 @@ __global__ __launch_bounds__(1024) void hier_count_kernel(HierCountArgs a) {
     }
     if (rouge && lane < R) a.rouge_overlap[int64_t(g) * R + lane] = s_overlap[lane];
 
-    if (a.score_out) {
+    if (SCORE) {
       // An atomic returns once it has been carried out: after the wait every statistic of this
       // workgroup is in place, and only then does the workgroup announce its arrival.  The
       // workgroup whose arrival completes the group reads the others' statistics with
@@ -598,15 +599,20 @@ hipError_t launch_dict_items(const HierDictArgs& a, const HierPlan& plan, hipStr
   return launch_lds(hier_dictionary_kernel<ITEMS>, a, a.pb.B, plan.threads, plan.dict_lds, s);
 }
 
+template <int ROWS, int OPW, bool SCORE>
+hipError_t launch_count_variant(const HierCountArgs& a, int threads, hipStream_t s) {
+  const size_t lds = size_t(OPW) * a.order_words * 4;
+  hipError_t e = grant_dynamic_lds(
+      reinterpret_cast<const void*>(hier_count_kernel<ROWS, OPW, SCORE>), lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((hier_count_kernel<ROWS, OPW, SCORE>),
+                     dim3(uint32_t(a.pb.B), uint32_t(a.split)), dim3(threads), lds, s, a);
+  return hipGetLastError();
+}
 template <int ROWS, int OPW>
 hipError_t launch_count_shape(const HierCountArgs& a, int threads, hipStream_t s) {
-  const size_t lds = size_t(OPW) * a.order_words * 4;
-  hipError_t e =
-      grant_dynamic_lds(reinterpret_cast<const void*>(hier_count_kernel<ROWS, OPW>), lds);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((hier_count_kernel<ROWS, OPW>), dim3(uint32_t(a.pb.B), uint32_t(a.split)),
-                     dim3(threads), lds, s, a);
-  return hipGetLastError();
+  return a.score_out ? launch_count_variant<ROWS, OPW, true>(a, threads, s)
+                     : launch_count_variant<ROWS, OPW, false>(a, threads, s);
 }
 
 hipError_t launch_count_rows(const HierCountArgs& a, int threads, int rows, int opw,
