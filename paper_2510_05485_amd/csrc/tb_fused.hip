@@ -76,9 +76,8 @@ bool plan_fused(int64_t cand_stride, int64_t ref_stride, int R, int N, int bits,
   const int64_t cap = cand_stride + int64_t(R) * ref_stride;
   // list entries pack position (14 bits), id (12 bits) and sequence index (6 bits)
   if (cap > 12 * 1024 || cand_stride > 4096 || ref_stride > 65535) return false;
-  int id_bits = 1;
-  while ((int64_t(1) << id_bits) < cand_stride) ++id_bits;
-  if (id_bits + bits > 31) return false;  // key = id * 2^bits + token must stay below 2^31
+  // key = id * 2^bits + token, id < cand_stride, must stay below the all-ones empty marker
+  if (bits > 31 || (uint64_t(cand_stride) << bits) > 0xFFFFFFFFull) return false;
   int t = 256;
   while (t < 1024 && cap > 4 * t) t *= 2;
   plan->threads = t;

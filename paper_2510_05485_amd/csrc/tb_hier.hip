@@ -87,8 +87,8 @@ __device__ __forceinline__ void find_sequence(int k0, int lane, int incl, int R,
   *end = e;
 }
 
-// Claim-or-find in the open-addressing table (double hashing; a key is below 2^31, so it never
-// equals the empty marker).  Single-exit probe loop.
+// Claim-or-find in the open-addressing table (double hashing; the plan keeps every key below the
+// all-ones empty marker).  Single-exit probe loop.
 __device__ __forceinline__ uint32_t hier_insert(uint32_t* table, uint32_t key, uint32_t mask,
                                                 int shift, bool* won) {
   const uint32_t h = key * 0x9E3779B1u;
@@ -669,8 +669,8 @@ bool plan_hier(int64_t group_cap, int64_t cand_stride, int64_t ref_stride, int R
                HierPlan* plan) {
   if (R + 1 > kHierMaxSeqs || group_cap < 4 || group_cap > 12 * 1024) return false;
   if (cand_stride > 65535 || ref_stride > 65535) return false;  // 16-bit counter fields
-  // key = id * 2^bits + token must stay below 2^31 (all-ones is the empty marker)
-  if (ceil_log2_int(group_cap) + bits > 31) return false;
+  // key = id * 2^bits + token, id < group_cap, must stay below the all-ones empty marker
+  if (bits > 31 || (uint64_t(group_cap) << bits) > 0xFFFFFFFFull) return false;
   int t = 256;
   while (t < 1024 && group_cap > 4 * t) t *= 2;
   plan->threads = t;

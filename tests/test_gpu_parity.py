@@ -227,6 +227,39 @@ def test_device_status_on_partitioned_groups(max_len, min_len):
 
 
 @pytest.mark.parametrize("path", PATHS)
+def test_32_bit_keys_that_use_the_top_bit(path):
+    # 18-bit token ids and 12 000 n-gram slots per group: keys (id of the prefix, last token) reach
+    # 12 000 * 2^18 > 2^31, so the hash tables hold keys with the top bit set (still below the
+    # all-ones empty marker); the GLOBAL path keeps its 32-bit-key kernels for this shape (the
+    # fused plan does not fit: 32-bit staged tokens).  Tokens are drawn from the top of the id
+    # range so that such keys do occur.
+    w = syn.random_small(141, B=3, R=2, vocab=262144, max_len=4000, min_len=3600)
+    rng = np.random.default_rng(141)
+    hi = rng.integers(262144 - 40, 262144, size=w.cand.shape, dtype=np.int64)
+    w.cand[:, 1::2] = hi[:, 1::2].astype(w.cand.dtype)
+    w.refs[:, :, 1::2] = w.cand[:, None, 1::2]      # (equal strides) shared with the references
+    cfg = tb.make_config(vocab_size=w.vocab, path="global")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.group_cap == 12000 and lay.global_candidate_first == 1 and lay.global_partitions == 0
+    check(w, syn.Run("exp"), path)
+
+
+def test_fused_keys_that_use_the_top_bit():
+    # the same on the fused kernel, whose keys are (candidate position that made the prefix's
+    # entry, last token): 20-bit token ids and a candidate of up to 4000 tokens reach 4000 * 2^20
+    w = syn.random_small(142, B=4, R=1, vocab=1 << 20, max_len=4000, min_len=3700)
+    rng = np.random.default_rng(142)
+    hi = rng.integers((1 << 20) - 40, 1 << 20, size=w.cand.shape, dtype=np.int64)
+    w.cand[:, 1::2] = hi[:, 1::2].astype(w.cand.dtype)
+    w.refs[:, :, 1::2] = w.cand[:, None, 1::2]
+    cfg = tb.make_config(vocab_size=w.vocab, path="auto")
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.fused_ok == 1 and lay.path == 1
+    check(w, syn.Run("exp"), "fused")
+    check(w, syn.Run("exp"), "global")
+
+
+@pytest.mark.parametrize("path", PATHS)
 def test_largest_supported_group(path):
     # cand_stride + R * ref_stride = 12288 n-gram slots: the limit of both LDS plans
     w = syn.random_small(140, B=3, R=2, vocab=5000, max_len=4096, min_len=3000)
