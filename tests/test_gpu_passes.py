@@ -110,6 +110,36 @@ def test_staged_calls_equal_the_single_call_on_config1():
     assert abs(cout[0] - ref.corpus_bleu) <= 1e-5
 
 
+@pytest.mark.parametrize("seed,B,R,L", [(231, 13, 2, 700), (232, 37, 1, 300), (233, 3, 4, 1500)])
+def test_score_inside_the_count_kernel_with_a_group_spread_over_xcds(seed, B, R, L):
+    # With a batch size that is no multiple of eight, the count workgroups of one group (one per
+    # order, B workgroup indices apart) run on different XCDs, each with its own L2: the
+    # statistics and the arrival counter then have to travel through device-scope operations.
+    w = syn.random_small(seed, B=B, R=R, vocab=5000, max_len=L, min_len=L // 2)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+    cfg = tb.make_config(smoothing="exp", vocab_size=w.vocab, path="global")
+    cand, cl, refs, rl = dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len)
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, cand.shape[1], refs.shape[2], cfg)
+    assert lay.global_candidate_first == 1      # the hierarchical-key kernels
+    st = tb.Stats.allocate(w.B, 4, DEV, corpus_stats=False)
+    ws = tb.allocate_workspace(w.B, w.R, cand.shape[1], refs.shape[2], cfg, DEV)
+    out = torch.empty(w.B, dtype=torch.float32, device=DEV)
+    first = None
+    for _ in range(300):
+        out.fill_(-1.0)
+        st.closest_ref_len.fill_(-1)
+        st.clipped.fill_(12345)     # a scoring workgroup that read stale statistics would show
+        st.total.fill_(1)
+        tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out, stats=st, workspace=ws)
+        if first is None:
+            first = out.clone()
+            np.testing.assert_array_equal(st.clipped.cpu().numpy(), ref.clipped)
+            np.testing.assert_array_equal(st.closest_ref_len.cpu().numpy(), ref.closest_ref_len)
+            assert np.abs(first.cpu().numpy().astype(np.float64) - ref.bleu).max() <= 1e-5
+        assert torch.equal(out, first)
+    assert st.device_status.item() == 0
+
+
 @pytest.mark.parametrize("k", [2, 5])
 def test_single_global_call_scores_inside_the_count_kernel(k):
     # A single per-sentence call on the hierarchical-key kernels launches no score kernel: of a
@@ -130,6 +160,8 @@ def test_single_global_call_scores_inside_the_count_kernel(k):
     for _ in range(100):
         out2.fill_(-1.0)
         st2.closest_ref_len.fill_(-1)
+        st2.clipped.fill_(12345)    # a scoring workgroup that read stale statistics would show
+        st2.total.fill_(1)
         tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out2, stats=st2, workspace=ws)
         assert torch.equal(out2, expect)
         assert torch.equal(st2.closest_ref_len, closest)
