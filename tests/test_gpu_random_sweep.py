@@ -65,7 +65,9 @@ def test_random_sweep(sweep_seed):
         except tb.TensorBLEUError:
             continue                                        # shape outside the forced path
         for corpus in (False, True):
-            st = tb.Stats.allocate(B, N, DEV)
+            # (per-sentence calls without corpus sums take the shortest route through the
+            # kernels, e.g. the score formed inside the count kernel: both kinds are swept)
+            st = tb.Stats.allocate(B, N, DEV, corpus_stats=corpus or case % 2 == 0)
             fn = tb.tensorbleu_corpus if corpus else tb.tensorbleu_sentence
             out = fn(cand, cl, refs, rl, cfg, stats=st).cpu().numpy()
             assert st.device_status.item() == 0, tag
