@@ -231,3 +231,32 @@ def test_plain_c_caller_of_the_abi():
     for got, want in rows:
         assert abs(got - want) <= 1e-5
     assert rows[1][1] == pytest.approx(np.exp(-0.5), abs=1e-6)
+
+
+def test_two_streams_with_their_own_workspaces_run_side_by_side():
+    """The stream argument: calls on two streams (default priority), each with its own scorer
+    (workspace, outputs), enqueued alternately without waiting, give what the same calls give one
+    at a time.  One scorer runs the fused kernel, the other the GLOBAL passes."""
+    wa = syn.random_small(421, B=64, R=2, vocab=5000, max_len=400, min_len=100)
+    wb = syn.random_small(422, B=40, R=3, vocab=300, max_len=700, min_len=50)
+    mk = lambda w, path: tb.BleuScorer(w.B, w.R, w.cand.shape[1], w.refs.shape[2],
+                                       vocab_size=w.vocab, smoothing="exp", path=path, device=DEV)
+    sa, sb = mk(wa, "fused"), mk(wb, "global")
+    ins = lambda w: (dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len))
+    ia, ib = ins(wa), ins(wb)
+    serial_a, serial_b = sa(*ia).clone(), sb(*ib).clone()
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(20):
+        with torch.cuda.stream(s1):
+            oa = sa(*ia)
+        with torch.cuda.stream(s2):
+            ob = sb(*ib)
+        s1.synchronize(); s2.synchronize()
+        outs.append((oa.clone(), ob.clone()))
+    for oa, ob in outs:
+        assert torch.equal(oa, serial_a) and torch.equal(ob, serial_b)
+    sa.check(); sb.check()
+    ref = oracle.bleu(wb.cand, wb.cand_len, wb.refs, wb.ref_len, smoothing="exp")
+    assert np.abs(serial_b.cpu().numpy() - ref.bleu).max() <= 1e-5
