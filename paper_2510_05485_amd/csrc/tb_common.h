@@ -148,10 +148,11 @@ __device__ __forceinline__ int32_t load_token(const void* base, int64_t idx, int
   return static_cast<const int32_t*>(base)[idx];
 }
 
-// A load from an INPUT array (memory no kernel of the running call writes) at an address that is
-// the same in every lane: read through the constant address space, so that it goes through the
-// scalar cache -- no vector-memory round trip with a wait for every other outstanding vector load
-// of the wavefront behind it.
+// A load at an address that is the same in every lane, from memory that no workgroup of the
+// RUNNING KERNEL writes (an input array, or what an earlier launch of the call left): read
+// through the constant address space, so that it goes through the scalar cache -- no
+// vector-memory round trip with a wait for every other outstanding vector load of the wavefront
+// behind it.  (The scalar cache is invalidated when a kernel starts, not while it runs.)
 __device__ __forceinline__ int32_t uniform_load(const int32_t* p, int64_t i) {
   typedef const int32_t __attribute__((address_space(4))) * constant_ptr;
   return *(constant_ptr)(p + i);

@@ -24,6 +24,18 @@
 #include "tb_group_index.h"
 #include "tb_kernels.h"
 
+// Phase time stamps for tuning builds only (-DTB_STAMPS), as in the hierarchical kernels.
+#ifdef TB_STAMPS
+__device__ unsigned long long tb_part_stamps[8192 * 16];
+#define TB_PSTAMP(i) \
+  do { if (threadIdx.x == 0 && blockIdx.x < 8192) tb_part_stamps[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+extern "C" int tb_debug_stamps_part(unsigned long long* host, int count) {
+  return int(hipMemcpyFromSymbol(host, HIP_SYMBOL(tb_part_stamps), size_t(count) * 8));
+}
+#else
+#define TB_PSTAMP(i) do {} while (0)
+#endif
+
 namespace tb {
 
 namespace {
@@ -576,6 +588,7 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
     for (int q = tid; q < quads; q += nt) c4[q] = make_uint4(0u, 0u, 0u, 0u);
   }
   __syncthreads();
+  TB_PSTAMP(4);
   // A crowded partition (see the dictionary kernel) holds thousands of occurrences of one
   // n-gram: there the lanes of a wavefront that hold the same (id, sequence) as its first lane
   // add up in one atomic instead of queueing at one LDS address.
@@ -602,7 +615,7 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
           for (int j = 0; j < R; ++j)
             f += (int(k[kSeqFromSlot ? u : 0]) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
         } else {
-          f = min(int(id[u] >> 16), R);
+          f = min(int((id[u] >> 16) & 0x7FFFu), R);  // (bit 31 may hold a dictionary flag)
         }
         const uint32_t word = (id[u] & 0xFFFFu) | (uint32_t(f) << 16);
         id[u] &= 0xFFFFu;
@@ -632,7 +645,9 @@ __device__ __forceinline__ int count_clip_partition(uint32_t* cnt, int U, int W,
     tally(std::true_type{});
   else
     tally(std::false_type{});
+  TB_PSTAMP(5);
   __syncthreads();
+  TB_PSTAMP(6);
   int part = 0;
   for (int u = tid; u < U; u += nt) {
     const uint32_t* e = &cnt[__umul24(uint32_t(u), uint32_t(W))];
@@ -755,6 +770,7 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   int* next_id = &scan_scratch[17];
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+  TB_PSTAMP(0);
   const Role me = role_of_block(a, a.orders, a.num_orders);
   if (me.g < 0) return;  // uniform over the workgroup
   const int g = me.g, n = me.n, p = me.p;
@@ -765,13 +781,17 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   static_assert((1 << 13) == kPartSlots, "table_shift");
   unsigned long long* table = reinterpret_cast<unsigned long long*>(smem);
   uint32_t* ginv = a.ws.inv[n - 1] + int64_t(g) * pb.group_cap;
+  // where the partition's members are: written by the scatter kernel, a launch earlier, and the
+  // same for the whole workgroup -- read through the scalar cache, next to the lengths' loads
+  const int64_t start_at = (int64_t(g) * pb.N + n - 1) * (parts + 1) + p;
+  const int start_p = uniform_load(a.part_start, start_at);
+  const int start_next = uniform_load(a.part_start, start_at + 1);
   GroupIndex gi(pb, g, GroupIndex::WaveOnly{});
-  gi.set_order(n);
-  const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
-  const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
-  const int32_t* start = a.part_start + (int64_t(g) * pb.N + n - 1) * (parts + 1);
-  const int first = min(max(start[p], 0), count);
-  const int members = min(max(start[p + 1] - first, 0), count - first);
+  // (bounded by the arrays' extent, not by the lengths: the members' addresses then do not wait
+  // for the lengths, whose loads are in flight)
+  const int cap = int(min(pb.group_cap, int64_t(0x7FFFFFFF)));
+  const int first = min(max(start_p, 0), cap);
+  const int members_fetched = min(max(start_next - first, 0), cap - first);
   const int64_t list = (int64_t(n - 1) * pb.B + g) * pb.group_cap + first;
   const uint32_t* member = a.member_slot + list;
   const uint64_t* member_keys = a.member_key + list;
@@ -781,7 +801,39 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
   uint32_t parked0[kPartUnroll];
 #pragma unroll
   for (int u = 0; u < kPartUnroll; ++u) parked0[u] = 0;
+  // A whole call that needs this order's ids nowhere (no later order is derived from them) and
+  // counts here can count by table entry: no ids, no second look into the table.
+  const bool by_entry = a.with_count && !((a.ids_wanted >> n) & 1);
+
+  // The first 4096 members' keys (and, to count by entry, their slots) -- all of them in a
+  // partition of the expected size -- are requested before the table is cleared, so that the
+  // clearing runs while they are on their way; those of the next 4096 after it.
+  constexpr int kHalf = kPartUnroll / 2;
+  uint64_t key0[kHalf];
+  uint32_t slot0[kHalf];
+#pragma unroll
+  for (int u = 0; u < kHalf; ++u) key0[u] = 0, slot0[u] = 0;
+  if (members_fetched > 0) {  // uniform
+#pragma unroll
+    for (int u = 0; u < kHalf; ++u)
+      key0[u] = member_keys[min(u * nt + tid, members_fetched - 1)];
+    if (by_entry) {
+#pragma unroll
+      for (int u = 0; u < kHalf; ++u) slot0[u] = member[min(u * nt + tid, members_fetched - 1)];
+    }
+  }
+  gi.set_order(n);
+  const int count = int(min(int64_t(gi.start(pb.R + 1)), pb.group_cap));
+  const int seq_end = (lane <= pb.R) ? gi.end_in_lane() : 0x7FFFFFFF;
+  const int members = min(members_fetched, max(count - first, 0));
   const uint32_t last_slot = uint32_t(max(count - 1, 0));
+  // the sequence of a slot (how many sequences end at or before it), in bits 16 and up
+  auto sequence_bits = [&](uint32_t slot) {
+    int f = 0;
+    for (int j = 0; j < pb.R; ++j)
+      f += (int(min(slot, last_slot)) >= __builtin_amdgcn_readlane(seq_end, j)) ? 1 : 0;
+    return uint32_t(f) << 16;
+  };
 
   {  // T + 1 entries (entry T belongs to the all-ones key), 16 bytes per store
     uint4* t4 = reinterpret_cast<uint4*>(table);
@@ -790,79 +842,108 @@ __global__ __launch_bounds__(kPartThreads, 8) void part_dictionary_kernel(PartAr
     if (tid == 0) *next_id = 0;
   }
   __syncthreads();
-
+  TB_PSTAMP(1);
   // Far more members than a partition expects means that some n-gram occurs thousands of times
   // (a frequent token in a long text): its occurrences would queue up at one LDS address.
   const bool crowded = members > 2 * kPartTarget;
   bool lost = false;  // a probe sequence ran through the whole table
   int created = 0;    // table entries that this thread's compare-and-swaps created ...
   uint32_t created0 = 0;  // ... bit u: among them the one of member u * nt + tid
-  auto insert_members = [&](auto peek) {
+  // Half a round: the members base + (u0 + u) * nt + tid, u < 4.  A member's table entry is
+  // remembered (in registers for the first round of 8192, in member_ids beyond); counting by
+  // entry, its sequence rides along in bits 16 and up (found from the member's slot number).
+  auto insert_half = [&](auto peek, int base, auto first_u, const uint64_t (&key)[kHalf],
+                         const uint32_t (&slot)[kHalf]) {
     constexpr bool kPeek = decltype(peek)::value;
-    for (int base = 0; base < members; base += kPartUnroll * nt) {
-      uint64_t key[kPartUnroll];
+    constexpr int u0 = decltype(first_u)::value;
+    {
   #pragma unroll
-      for (int u = 0; u < kPartUnroll; ++u)
-        key[u] = member_keys[min(base + u * nt + tid, members - 1)];
-  #pragma unroll
-      for (int u = 0; u < kPartUnroll; ++u) {
+      for (int v = 0; v < kHalf; ++v) {
+        const int u = u0 + v;
         if (base + u * nt + tid >= members) continue;
-        if (key[u] == kFreeEntry) {
+        const uint32_t seq = by_entry ? sequence_bits(slot[v]) : 0u;
+        if (key[v] == kFreeEntry) {
           const uint32_t made = atomicCAS(&table[T], kFreeEntry, 0ull) == kFreeEntry ? 1u : 0u;
           created += int(made);
           if (base == 0) {
-            parked0[u] = uint32_t(T);
+            parked0[u] = uint32_t(T) | seq;
             created0 |= made << u;
           } else {
-            member_ids[base + u * nt + tid] = uint32_t(T) | (made << 31);
+            member_ids[base + u * nt + tid] = uint32_t(T) | seq | (made << 31);
           }
           continue;
         }
-        const uint32_t h = part_hash(key[u]);
+        const uint32_t h = part_hash(key[v]);
         const uint32_t step = (h >> 3) | 1u;
         uint32_t s = h >> shift;
         // crowded partition: a plain read answers for a key that is already there, and only an
         // empty entry is worth an atomic
         unsigned long long old = kPeek ? table[s] : kFreeEntry;
-        if (old == kFreeEntry) old = atomicCAS(&table[s], kFreeEntry, key[u]);
+        if (old == kFreeEntry) old = atomicCAS(&table[s], kFreeEntry, key[v]);
         int rounds = 0;
-        while (int(old != kFreeEntry) & int(old != key[u]) & int(rounds < T)) {
+        while (int(old != kFreeEntry) & int(old != key[v]) & int(rounds < T)) {
           s = (s + step) & mask;
           old = kPeek ? table[s] : kFreeEntry;
-          if (old == kFreeEntry) old = atomicCAS(&table[s], kFreeEntry, key[u]);
+          if (old == kFreeEntry) old = atomicCAS(&table[s], kFreeEntry, key[v]);
           ++rounds;
         }
-        lost |= (old != kFreeEntry && old != key[u]);
+        lost |= (old != kFreeEntry && old != key[v]);
         const uint32_t made = old == kFreeEntry ? 1u : 0u;
         created += int(made);
         if (base == 0) {
-          parked0[u] = s;
+          parked0[u] = s | seq;
           created0 |= made << u;
         } else {
-          member_ids[base + u * nt + tid] = s | (made << 31);
+          member_ids[base + u * nt + tid] = s | seq | (made << 31);
         }
       }
+    }
+  };
+  // the members [base + u0 * nt, base + (u0 + 4) * nt), loaded here
+  auto load_and_insert_half = [&](auto peek, int base, auto first_u) {
+    constexpr int u0 = decltype(first_u)::value;
+    if (base + u0 * nt >= members) return;  // uniform
+    uint64_t key[kHalf];
+    uint32_t slot[kHalf];
+#pragma unroll
+    for (int v = 0; v < kHalf; ++v)
+      key[v] = member_keys[min(base + (u0 + v) * nt + tid, members - 1)];
+#pragma unroll
+    for (int v = 0; v < kHalf; ++v)
+      slot[v] = by_entry ? member[min(base + (u0 + v) * nt + tid, members - 1)] : 0u;
+    insert_half(peek, base, first_u, key, slot);
+  };
+  auto insert_members = [&](auto peek) {
+    using First = std::integral_constant<int, 0>;
+    using Second = std::integral_constant<int, kHalf>;
+    insert_half(peek, 0, First{}, key0, slot0);
+    load_and_insert_half(peek, 0, Second{});
+    for (int base = kPartUnroll * nt; base < members; base += kPartUnroll * nt) {
+      load_and_insert_half(peek, base, First{});
+      load_and_insert_half(peek, base, Second{});
     }
   };
   if (crowded)
     insert_members(std::true_type{});
   else
     insert_members(std::false_type{});
-  // A whole call that needs this order's ids nowhere (no later order is derived from them) and
-  // counts here can count by table entry: no ids, no second look into the table.
-  if (a.with_count && !((a.ids_wanted >> n) & 1)) {
+  if (by_entry) {
+    TB_PSTAMP(2);
     const int distinct = block_sum(created, scan_scratch);  // (its barriers end the insertions)
+    TB_PSTAMP(3);
     if (lost || distinct > kPartIdCap) {
       if (pb.status) atomicOr(pb.status, TB_DEV_TABLE_OVERFLOW);
       if (a.ws.overflow) a.ws.overflow[g] = 1;
     }
     if (tid == 0)
       a.part_distinct[(int64_t(g) * pb.N + n - 1) * (int64_t(1) << a.log2_parts) + p] = distinct;
-    // (the members' words hold their table entries; their sequences follow from their slots)
-    const int part = count_clip_partition<true, true>(
-        reinterpret_cast<uint32_t*>(smem), T + 1, a.words, a.fields_per_word, pb.R, members,
-        member_ids, parked0, member, last_slot, seq_end);
+    // (the members' words hold their table entries and sequences)
+    const int part = count_clip_partition<true>(reinterpret_cast<uint32_t*>(smem), T + 1,
+                                                a.words, a.fields_per_word, pb.R, members,
+                                                member_ids, parked0);
+    TB_PSTAMP(7);
     const int clipped = block_sum(part, scan_scratch);
+    TB_PSTAMP(8);
     if (tid == 0) {
       const int64_t stat = int64_t(g) * pb.N + n - 1;
       if (clipped) atomicAdd(&a.st.clipped[stat], clipped);
