@@ -219,6 +219,40 @@ NUM_CUS, CLOCK_GHZ = 256, 2.4
 ISSUE_PEAK = {"valu": 1.5, "salu": 1.0, "mixed": 1.7}
 
 
+def paper_grid(steps, torch, tb, syn, np, dev):
+    """The sizes the paper tabulates (its Section 5.1): sequence lengths 256 and 1024, batch
+    sizes 16..512, one reference each (the paper states none; workloads as configuration 1 at
+    these sizes).  Per size: device time per call with the host queued ahead, and the paper's
+    protocol, the mean wall-clock time of 5 calls each synchronised on its own (Section 4.2)."""
+    rows = []
+    for L in (256, 1024):
+        for B in (16, 32, 64, 128, 256, 512):
+            w = syn.config1(B=B, L=L)
+            run = [r for r in w.runs if not r.corpus][-1]
+            to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+            cand, cl, refs, rl = to(w.cand), to(w.cand_len), to(w.refs), to(w.ref_len)
+            cs, rs = int(w.cand.shape[1]), int(w.refs.shape[2])
+            cfg = tb.make_config(max_n=w.max_n, weights=w.weights, smoothing=run.smoothing,
+                                 smooth_param=run.smooth_param, vocab_size=w.vocab, path="auto")
+            ws = tb.allocate_workspace(w.B, w.R, cs, rs, cfg, dev)
+            out = torch.empty(w.B, dtype=torch.float32, device=dev)
+            fn = lambda: tb.tensorbleu_sentence(cand, cl, refs, rl, cfg, out=out, workspace=ws)
+            for _ in range(5):
+                fn()
+            ms = time_region(fn, steps, torch)
+            runs = []
+            for _ in range(5):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                runs.append((time.perf_counter() - t0) * 1e3)
+            rows.append({"L": L, "B": B, "R": w.R, "vocab": w.vocab, "device_us": round(ms * 1e3, 2),
+                         "sentences_per_s": round(B / (ms * 1e-3), 1),
+                         "ms_mean_of_5_synchronised_calls": round(sum(runs) / 5, 4)})
+    return rows
+
+
 def profile_counters(workload, pass_name):
     """Counters of the kernel that implements `pass_name`, read from the committed rocprofv3
     summary profiles/pmc_<workload>.md (sections '## `kernel`' with '* COUNTER: value' lines;
@@ -285,6 +319,8 @@ def main():
                     help="with --long-form: the number of candidates")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short measurements of the other BASELINE configurations")
+    ap.add_argument("--paper-grid", action="store_true",
+                    help="also time the sizes the paper tabulates (L = 256 and 1024, B = 16..512)")
     ap.add_argument("--no-global-passes", action="store_true",
                     help="skip the per-pass timing of the GLOBAL path")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -432,6 +468,8 @@ def main():
     }
     if global_section is not None and path != "global":
         result["global_path"] = global_section
+    if a.paper_grid:
+        result["paper_grid"] = paper_grid(a.steps, torch, tb, syn, np, dev)
     if a.rouge:
         # the ROUGE-N extension on the same batch (same kernel family, order a.rouge)
         rws = tb.allocate_workspace(w.B, w.R, cs, rs, tb.make_config(
