@@ -73,7 +73,8 @@ enum { TB_DEV_TOKEN_RANGE = 1,  /* a token inside a row's length was outside [0,
                                    hold; cannot happen unless keys are built to collide.  The
                                    score of such a group is NaN (and so is a corpus score it
                                    enters), so that it cannot pass for a reward; its integer
-                                   statistics are unspecified */ };
+                                   statistics are unspecified.  The same call with
+                                   cfg->workspace_tables set cannot overflow */ };
 
 typedef struct tb_config {
   int32_t max_n;        /* N: highest n-gram order, 1..8 (Section 2.1 names 1 to 4 as the usual range);
@@ -112,6 +113,13 @@ typedef struct tb_config {
                            are clamped and reported through TB_DEV_LENGTH_RANGE, as is an empty
                            span.  Not together with ref_count (TB_ERR_INVALID_ARG). */
   int64_t ref_rows;     /* with ref_offsets: the number of reference rows in `refs` / `ref_len` */
+  int32_t workspace_tables; /* non-zero: the GLOBAL path keeps its hash tables and counters in the
+                           workspace whatever the shape (the kernels it otherwise uses beyond
+                           2 097 152 slots per group).  Several times slower than tables in LDS,
+                           but no table has a capacity that data can exceed: the way to re-issue a
+                           call that reported TB_DEV_TABLE_OVERFLOW.  BLEU only (tensorrouge_n
+                           then returns TB_ERR_UNSUPPORTED on the GLOBAL path); workspace sizes
+                           and layouts depend on it like on the other fields */
 } tb_config_t;
 
 /* Optional integer outputs (each pointer may be NULL).  These are what the parity tests compare

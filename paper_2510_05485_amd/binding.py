@@ -36,7 +36,7 @@ class tb_config_t(ctypes.Structure):
                 ("vocab_size", ctypes.c_int32), ("force_path", ctypes.c_int32),
                 ("token_bytes", ctypes.c_int32), ("score_bytes", ctypes.c_int32),
                 ("ref_count", ctypes.c_void_p), ("ref_offsets", ctypes.c_void_p),
-                ("ref_rows", ctypes.c_int64)]
+                ("ref_rows", ctypes.c_int64), ("workspace_tables", ctypes.c_int32)]
 
 
 class tb_stats_t(ctypes.Structure):
@@ -122,13 +122,16 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
                 smoothing: str = "none", smooth_param: float = 0.0, vocab_size: int = 1 << 16,
                 path: str = "auto", ref_count: Optional[torch.Tensor] = None,
                 score_dtype: torch.dtype = torch.float32,
-                ref_offsets: Optional[torch.Tensor] = None, max_refs: int = 0) -> tb_config_t:
+                ref_offsets: Optional[torch.Tensor] = None, max_refs: int = 0,
+                workspace_tables: bool = False) -> tb_config_t:
     """ref_count: optional int32 device tensor [B]; candidate i is scored against its first
     ref_count[i] references only.  The config keeps the tensor alive.
     ref_offsets: optional int32 device tensor [B + 1]: reference lists in CSR form (`refs` is then
     [rows, Lr] and `ref_len` [rows]; candidate i owns rows ref_offsets[i] .. ref_offsets[i+1]-1);
     max_refs is the largest number of references of any candidate.
-    score_dtype: torch.float32, or torch.bfloat16 for scores stored as bfloat16."""
+    score_dtype: torch.float32, or torch.bfloat16 for scores stored as bfloat16.
+    workspace_tables: the GLOBAL path with its hash tables in the workspace whatever the shape
+    (slower; no table can overflow: for re-issuing a call that reported TB_DEV_TABLE_OVERFLOW)."""
     if score_dtype not in (torch.float32, torch.bfloat16):
         raise TensorBLEUError(f"score_dtype must be float32 or bfloat16 (got {score_dtype})")
     cfg = tb_config_t()
@@ -144,6 +147,7 @@ def make_config(max_n: int = 4, weights: Optional[Sequence[float]] = None,
     cfg.force_path = PATHS[path] if isinstance(path, str) else int(path)
     cfg.token_bytes = 4
     cfg.score_bytes = 2 if score_dtype == torch.bfloat16 else 4
+    cfg.workspace_tables = 1 if workspace_tables else 0
     cfg.ref_count = None
     if ref_count is not None:
         if ref_count.dtype != torch.int32 or not ref_count.is_contiguous() or ref_count.dim() != 1:

@@ -140,12 +140,15 @@ int make_plans(int32_t B, int32_t R, int64_t cand_stride, int64_t ref_stride,
   const bool global_n = N * L.bits <= 128;  // the GLOBAL path packs whole n-grams into keys
   // one LDS table per group: the hierarchical-key kernels where their plan fits, else the
   // packed-key ones
-  p->use_hier = global_n && plan_hier(L.group_cap, cand_stride, ref_stride, R, N, L.bits, &p->hier);
+  // (cfg->workspace_tables: none of the LDS plans, tables in the workspace for every shape)
+  const bool lds_allowed = global_n && !cfg->workspace_tables;
+  p->use_hier =
+      lds_allowed && plan_hier(L.group_cap, cand_stride, ref_stride, R, N, L.bits, &p->hier);
   const bool lds_ok = p->use_hier ||
-                      (global_n &&
+                      (lds_allowed &&
                        plan_dictionary(L.group_cap, L.key_bytes, N, L.bits, &p->dict) &&
                        plan_count(L.group_cap, cand_stride, ref_stride, R, &p->count));
-  p->use_part = global_n && !lds_ok &&
+  p->use_part = lds_allowed && !lds_ok &&
                 plan_part(L.group_cap, cand_stride, ref_stride, R, N, L.key_bytes, &p->part);
   p->use_big = global_n && !lds_ok && !p->use_part && plan_big(L.group_cap, N, &p->big);
   L.id_stride = p->use_part ? p->part.id_stride : L.group_cap;

@@ -259,6 +259,26 @@ def test_fused_keys_that_use_the_top_bit():
     check(w, syn.Run("exp"), "global")
 
 
+@pytest.mark.parametrize("seed,B,R,V,L", [(143, 9, 2, 300, 200), (144, 3, 1, 262144, 3000)])
+def test_workspace_tables_on_shapes_that_fit_lds(seed, B, R, V, L):
+    # cfg->workspace_tables: the kernels with tables in the workspace on shapes that would
+    # otherwise take an LDS plan give the same statistics and scores
+    w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=L // 3)
+    ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len, smoothing="exp")
+    cfg = tb.make_config(smoothing="exp", vocab_size=V, path="global", workspace_tables=True)
+    lay = tb.tensorbleu_workspace_layout(w.B, w.R, w.cand.shape[1], w.refs.shape[2], cfg)
+    assert lay.global_tables_in_hbm == 1 and lay.global_candidate_first == 0
+    d = Device(w)
+    st = tb.Stats.allocate(w.B, 4, DEV)
+    out = tb.tensorbleu_sentence(d.cand, d.cand_len, d.refs, d.ref_len, cfg, stats=st)
+    torch.cuda.synchronize()
+    assert st.device_status.item() == 0
+    np.testing.assert_array_equal(st.clipped.cpu().numpy(), ref.clipped)
+    np.testing.assert_array_equal(st.total.cpu().numpy(), ref.total)
+    np.testing.assert_array_equal(st.group_distinct.cpu().numpy(), ref.group_distinct)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ref.bleu).max() <= TOL
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_largest_supported_group(path):
     # cand_stride + R * ref_stride = 12288 n-gram slots: the limit of both LDS plans

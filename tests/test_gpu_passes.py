@@ -230,6 +230,18 @@ def test_partition_overflow_is_reported_not_hidden():
     cout = tb.tensorbleu_corpus(dev(cand), dev(cl), dev(refs), dev(rl), cfg)
     torch.cuda.synchronize()
     assert np.isnan(cout.cpu().numpy()).all()
+    # the remedy the header names: the same call with the tables in the workspace, which have no
+    # capacity to exceed -- right statistics and score, nothing flagged
+    safe = tb.make_config(vocab_size=40000, path="global", workspace_tables=True)
+    slay = tb.tensorbleu_workspace_layout(1, 1, L, L, safe)
+    assert slay.global_partitions == 0 and slay.global_tables_in_hbm == 1
+    exact = oracle.bleu(cand, cl, refs, rl)
+    st = tb.Stats.allocate(1, 4, DEV)
+    out = tb.tensorbleu_sentence(dev(cand), dev(cl), dev(refs), dev(rl), safe, stats=st)
+    torch.cuda.synchronize()
+    assert st.device_status.item() == 0
+    np.testing.assert_array_equal(st.clipped.cpu().numpy(), exact.clipped)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - exact.bleu).max() <= 1e-5
     # the same shape with ordinary tokens is scored and not flagged
     w = syn.random_small(206, B=1, R=1, vocab=40000, max_len=L, min_len=7000)
     ref = oracle.bleu(w.cand, w.cand_len, w.refs, w.ref_len)
