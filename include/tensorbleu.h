@@ -117,9 +117,9 @@ typedef struct tb_config {
                            workspace whatever the shape (the kernels it otherwise uses beyond
                            2 097 152 slots per group).  Several times slower than tables in LDS,
                            but no table has a capacity that data can exceed: the way to re-issue a
-                           call that reported TB_DEV_TABLE_OVERFLOW.  BLEU only (tensorrouge_n
-                           then returns TB_ERR_UNSUPPORTED on the GLOBAL path); workspace sizes
-                           and layouts depend on it like on the other fields */
+                           call that reported TB_DEV_TABLE_OVERFLOW, and to get ROUGE-N for the
+                           shapes tensorrouge_n otherwise refuses on the GLOBAL path.  Workspace
+                           sizes and layouts depend on it like on the other fields */
 } tb_config_t;
 
 /* Optional integer outputs (each pointer may be NULL).  These are what the parity tests compare
@@ -251,9 +251,10 @@ size_t tensorbleu_static_scratch_bytes(void);
  * cfg->ref_count[i] are 0.  cfg->weights and cfg->smoothing are ignored; vocab_size, token_bytes
  * and ref_count mean what they mean for BLEU.  Paths as for BLEU (cfg->force_path; AUTO takes
  * FUSED where the shape fits it, else GLOBAL: pack and dictionary for the orders 1..n, then the
- * count pass for order n with per-reference sums).  On GLOBAL, LDS-resident groups with plain
- * packed-key tables (global_candidate_first == 0 and global_partitions == 0) and groups on
- * workspace tables (global_tables_in_hbm) return TB_ERR_UNSUPPORTED.  Workspace:
+ * count pass for order n with per-reference sums).  On GLOBAL, one kind of shape returns
+ * TB_ERR_UNSUPPORTED: LDS-resident groups on plain packed-key tables (global_candidate_first == 0,
+ * global_partitions == 0, global_tables_in_hbm == 0: more than 62 references, or (id, token) keys
+ * beyond 32 bits); the same call with cfg->workspace_tables set serves it.  Workspace:
  * tensorbleu_workspace_bytes for the same arguments (cfg->max_n = n).  stats: only
  * device_status is used. */
 int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len,

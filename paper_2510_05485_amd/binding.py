@@ -336,15 +336,22 @@ def tensorrouge_n(cand, cand_len, refs, ref_len, n: int = 2, beta: float = 1.0, 
                   want_overlap: bool = False, want_best: bool = False,
                   workspace: Optional[torch.Tensor] = None, stats: Optional[Stats] = None,
                   stream=None, score_dtype: torch.dtype = torch.float32, path: str = "auto",
-                  ref_offsets: Optional[torch.Tensor] = None, max_refs: int = 0):
+                  ref_offsets: Optional[torch.Tensor] = None, max_refs: int = 0,
+                  workspace_tables: bool = False):
     """ROUGE-N of every candidate against its references: float32 (or bfloat16) [B, 3] (precision,
     recall, F of the best reference), plus overlap int32 [B, R] and best-reference index int32 [B]
-    on request (returned as a tuple then)."""
+    on request (returned as a tuple then).  Without a workspace argument, a shape that the GLOBAL
+    path would serve with its BLEU-only packed-key kernels is run with workspace_tables set."""
     cfg = make_config(max_n=n, smooth_param=beta, vocab_size=vocab_size, path=path,
                       ref_count=ref_count, score_dtype=score_dtype, ref_offsets=ref_offsets,
-                      max_refs=max_refs)
+                      max_refs=max_refs, workspace_tables=workspace_tables)
     b = _batch(cand, cand_len, refs, ref_len, cfg)
     if workspace is None:
+        lay = tensorbleu_workspace_layout(b.B, b.R, b.cand_stride, b.ref_stride, cfg)
+        if lay.path == PATHS["global"] and not (lay.global_candidate_first or
+                                                lay.global_partitions or
+                                                lay.global_tables_in_hbm):
+            cfg.workspace_tables = 1
         workspace = allocate_workspace(b.B, b.R, b.cand_stride, b.ref_stride, cfg, b.cand.device)
     dev = b.cand.device
     out = _score_out(None, cfg, (b.B, 3), dev)

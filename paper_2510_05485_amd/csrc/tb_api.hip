@@ -414,14 +414,18 @@ int tensorrouge_n(const void* cand, int64_t cand_stride, const int32_t* cand_len
     return hip_rc(launch_fused(c.pb, c.plans.fused, c.st, c.sp, nullptr, c.stream, &ro));
   // GLOBAL: pack and dictionary as for BLEU (the keys of order n build on the ids of the orders
   // below), then the count pass for order n alone, which also sums the per-reference overlaps
-  if (!c.plans.use_hier && !c.plans.use_part) return TB_ERR_UNSUPPORTED;  // BLEU-only kernels
+  // (the packed-key LDS count kernels are BLEU-only: such a shape is served with
+  // cfg->workspace_tables set)
+  if (!c.plans.use_hier && !c.plans.use_part && !c.plans.use_big) return TB_ERR_UNSUPPORTED;
   int32_t* ov = reinterpret_cast<int32_t*>(w + L.overlap_off);
   if (!c.plans.use_part && (rc = hip_rc(launch_pack(c.pb, c.ws, c.stream))) != TB_OK) return rc;
   if ((rc = hip_rc(run_dictionary(c, false, true))) != TB_OK) return rc;
   rc = hip_rc(c.plans.use_hier
                   ? launch_hier_count_clip(c.pb, c.ws, c.plans.hier, c.st, c.cand_distinct,
                                            c.stream, ov)
-                  : launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream, ov));
+              : c.plans.use_part
+                  ? launch_part_count_clip(c.pb, c.ws, c.plans.part, c.st, c.stream, ov)
+                  : launch_big_count_clip(c.pb, c.ws, c.plans.big, c.st, c.stream, ov));
   if (rc != TB_OK) return rc;
   return hip_rc(launch_rouge_finalize(c.pb, c.sp, ov, ro, c.stream));
 }

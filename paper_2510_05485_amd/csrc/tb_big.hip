@@ -19,6 +19,7 @@ struct BigArgs {
   unsigned long long* tables;  // [B * N] tables of `slots` + 8 entries
   int64_t slots;               // power of two >= 2 * group_cap
   int table_shift;             // 32 - log2(slots) (slots <= 2^31)
+  int32_t* rouge_overlap;      // count kernel, ROUGE-N: [B, R] (then order N only), or null
 };
 
 __device__ __forceinline__ int big_seq_len(const Problem& pb, int g, int j) {
@@ -134,8 +135,11 @@ __global__ __launch_bounds__(1024) void big_count_kernel(BigArgs a) {
   __shared__ int red_scratch[17];
   const Problem& pb = a.pb;
   const int nt = blockDim.x, tid = threadIdx.x;
-  const int g = blockIdx.x / pb.N;
-  const int n = blockIdx.x % pb.N + 1;
+  // BLEU: one workgroup per (group, order).  ROUGE-N: one per group, order N, and every
+  // reference's pass also sums min(candidate count, the reference's count) over the ids.
+  const bool rouge = a.rouge_overlap != nullptr;
+  const int g = rouge ? int(blockIdx.x) : int(blockIdx.x) / pb.N;
+  const int n = rouge ? pb.N : int(blockIdx.x) % pb.N + 1;
   const int64_t cap = pb.group_cap;
   uint32_t* acc = reinterpret_cast<uint32_t*>(a.tables + (int64_t(g) * pb.N + n - 1) * (a.slots + 8));
   uint32_t* cur = acc + cap;
@@ -164,9 +168,16 @@ __global__ __launch_bounds__(1024) void big_count_kernel(BigArgs a) {
     }
     lo = hi;
     __syncthreads();
+    int both = 0;
     for (int64_t u = tid; u < U; u += nt) {  // entry u always belongs to the same thread
-      mx[u] = max(mx[u], word_load(&cur[u]));
+      const uint32_t c = word_load(&cur[u]);
+      mx[u] = max(mx[u], c);
+      if (rouge) both += int(min(word_load(&acc[u]), c));
       cur[u] = 0;
+    }
+    if (rouge) {  // uniform
+      const int overlap = block_sum(both, red_scratch);
+      if (tid == 0) a.rouge_overlap[int64_t(g) * pb.R + j] = overlap;
     }
     __syncthreads();
   }
@@ -190,6 +201,7 @@ BigArgs make_args(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
   int lg = 0;
   while ((int64_t(1) << lg) < plan.slots) ++lg;
   a.table_shift = 32 - lg;
+  a.rouge_overlap = nullptr;
   return a;
 }
 
@@ -227,9 +239,10 @@ hipError_t launch_big_dictionary(const Problem& pb, const GlobalWs& ws, const Bi
 }
 
 hipError_t launch_big_count_clip(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
-                                 const StatPtrs& st, hipStream_t s) {
-  const BigArgs a = make_args(pb, ws, plan, st);
-  const int64_t blocks = int64_t(pb.B) * pb.N;
+                                 const StatPtrs& st, hipStream_t s, int32_t* rouge_overlap) {
+  BigArgs a = make_args(pb, ws, plan, st);
+  a.rouge_overlap = rouge_overlap;
+  const int64_t blocks = rouge_overlap ? int64_t(pb.B) : int64_t(pb.B) * pb.N;
   if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipLaunchKernelGGL(big_count_kernel, dim3(uint32_t(blocks)), dim3(1024), 0, s, a);
   return hipGetLastError();

@@ -134,8 +134,10 @@ hipError_t launch_part_count_clip(const Problem& pb, const GlobalWs& ws, const P
 bool plan_big(int64_t group_cap, int N, BigPlan* plan);
 hipError_t launch_big_dictionary(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
                                  const StatPtrs& st, hipStream_t s);
+// rouge_overlap != null: ROUGE-N instead, as for launch_hier_count_clip
 hipError_t launch_big_count_clip(const Problem& pb, const GlobalWs& ws, const BigPlan& plan,
-                                 const StatPtrs& st, hipStream_t s);
+                                 const StatPtrs& st, hipStream_t s,
+                                 int32_t* rouge_overlap = nullptr);
 
 bool plan_dictionary(int64_t group_cap, const int32_t* key_bytes, int N, int bits,
                      DictPlan* plan);

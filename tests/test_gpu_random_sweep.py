@@ -88,10 +88,10 @@ def test_random_sweep(sweep_seed):
             rlay = tb.tensorbleu_workspace_layout(B, R, cand.shape[1], refs.shape[2], rcfg)
         except tb.TensorBLEUError:
             rlay = None
-        # ROUGE-N runs on the fused kernel and on the GLOBAL path's hierarchical-key and
-        # partitioned kernels
-        if rlay is not None and (rlay.path == 1 or rlay.global_candidate_first or
-                                 rlay.global_partitions):
+        # ROUGE-N runs on the fused kernel and on the GLOBAL path's hierarchical-key,
+        # partitioned and workspace-table kernels (the wrapper takes the last for shapes that
+        # would otherwise get the BLEU-only packed-key kernels)
+        if rlay is not None:
             rr = oracle.rouge_n(w.cand, w.cand_len, w.refs, w.ref_len, n=n, beta=beta,
                                 ref_count=rc)
             o, ov, best = tb.tensorrouge_n(cand, cl, refs, rl, n=n, beta=beta, vocab_size=V,

@@ -112,8 +112,28 @@ def test_rouge_n_closed_forms_and_unsupported_shapes():
     with pytest.raises(tb.TensorBLEUError):
         tb.tensorrouge_n(dev(big.cand), dev(big.cand_len), dev(big.refs), dev(big.ref_len), n=2,
                          vocab_size=big.vocab, path="fused")
-    # 31-bit ids on the GLOBAL path: the packed-key kernels score BLEU only
+    # 31-bit ids on the GLOBAL path: the packed-key LDS kernels score BLEU only, so the entry
+    # point refuses the shape as planned by default ...
     wide = syn.random_small(508, B=2, R=1, vocab=2 ** 31 - 1, max_len=60)
+    wcfg = tb.make_config(max_n=2, vocab_size=wide.vocab, path="global")
+    wws = tb.allocate_workspace(wide.B, wide.R, wide.cand.shape[1], wide.refs.shape[2], wcfg, DEV)
     with pytest.raises(tb.TensorBLEUError):
         tb.tensorrouge_n(dev(wide.cand), dev(wide.cand_len), dev(wide.refs), dev(wide.ref_len),
-                         n=2, vocab_size=wide.vocab, path="global")
+                         n=2, vocab_size=wide.vocab, path="global", workspace=wws)
+    # ... and serves it on the workspace-table kernels, which the wrapper selects by itself
+    check(wide, 2, path="global")
+
+
+@pytest.mark.parametrize("seed,B,R,V,L", [
+    (531, 4, 70, 300, 120),          # more references than the LDS kernels' one lane each
+    (532, 3, 2, 2 ** 31 - 1, 900),   # (id, token) keys beyond 32 bits
+    (533, 2, 3, 50257, 2500),        # a shape the hierarchical-key kernels would take
+])
+def test_rouge_n_on_workspace_tables(seed, B, R, V, L):
+    w = syn.random_small(seed, B=B, R=R, vocab=V, max_len=L, min_len=L // 4)
+    for n, beta in ((1, 1.0), (3, 2.0)):
+        rr = oracle.rouge_n(w.cand, w.cand_len, w.refs, w.ref_len, n=n, beta=beta)
+        o, ov, best = tb.tensorrouge_n(dev(w.cand), dev(w.cand_len), dev(w.refs), dev(w.ref_len),
+                                       n=n, beta=beta, vocab_size=V, want_overlap=True,
+                                       want_best=True, path="global", workspace_tables=True)
+        check_rouge(rr, ov.cpu().numpy(), best.cpu().numpy(), o.cpu().numpy(), 1e-5)
