@@ -151,7 +151,7 @@ def cpu_baseline(w, run, gpu=None, budget_s=10.0):
 
 
 def other_configs(skip, steps, torch, tb, syn, np, dev):
-    """The remaining BASELINE configurations and the long-generation workload (128 candidates of
+    """The remaining benchmark configurations and the long-generation workload (128 candidates of
     8192 tokens, one reference each) in short form: sentences/s of the default path and
     the three main GLOBAL passes as fractions of the HBM peak.  A failure is recorded, not
     raised: it must not take the headline line with it."""
@@ -313,12 +313,12 @@ def main():
     ap.add_argument("--int64", action="store_true",
                     help="feed int64 token ids (the usual tokenizer dtype) instead of int32")
     ap.add_argument("--long-form", type=int, default=0, metavar="L",
-                    help="instead of a BASELINE configuration: 128 candidates of about L tokens "
+                    help="instead of a benchmark configuration: 128 candidates of about L tokens "
                          "with one reference each (groups beyond one LDS table for L > 6144)")
     ap.add_argument("--long-batch", type=int, default=128, metavar="B",
                     help="with --long-form: the number of candidates")
     ap.add_argument("--no-other-configs", action="store_true",
-                    help="skip the short measurements of the other BASELINE configurations")
+                    help="skip the short measurements of the other benchmark configurations")
     ap.add_argument("--paper-grid", action="store_true",
                     help="also time the sizes the paper tabulates (L = 256 and 1024, B = 16..512)")
     ap.add_argument("--no-global-passes", action="store_true",
